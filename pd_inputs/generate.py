@@ -1,0 +1,133 @@
+"""Seeded generators for weights and context token ids.
+
+Every tensor is drawn from its own counter-based (Philox) streams keyed by
+(seed, tensor id, chunk index), in fixed-size chunks, so the values do not
+depend on how many threads fill them.  Matrices are N(0, 0.02); for bf16
+workloads they are rounded once to bf16 (round-to-nearest-even) and handed out
+as raw 16-bit patterns.  Norm gains/biases stay fp32.
+"""
+
+from concurrent.futures import ThreadPoolExecutor
+import os
+
+import numpy as np
+
+from .configs import (WorkloadConfig, DTYPE_BF16, FFN_SWIGLU, NORM_LAYERNORM, POS_LEARNED,
+                      max_positions)
+
+_CHUNK = 1 << 22
+_STD = 0.02
+
+
+def bf16_bits(x: np.ndarray) -> np.ndarray:
+    """float32 array -> uint16 bf16 bit patterns, round-to-nearest-even."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    rounding = ((u >> 16) & 1) + np.uint32(0x7FFF)
+    return ((u + rounding) >> 16).astype(np.uint16)
+
+
+def bits_to_f32(bits: np.ndarray) -> np.ndarray:
+    """uint16 bf16 bit patterns -> float32 values (exact)."""
+    return (bits.astype(np.uint32) << 16).view(np.float32)
+
+
+def bf16_round(x: np.ndarray) -> np.ndarray:
+    """Round float32 values to the nearest bf16, returned as float32."""
+    return bits_to_f32(bf16_bits(x))
+
+
+def _fill_chunk(out_flat, lo, hi, seed, tensor_id, chunk, std, as_bf16):
+    bitgen = np.random.Philox(key=[(seed << 32) | tensor_id, chunk])
+    g = np.random.Generator(bitgen)
+    z = g.standard_normal(hi - lo, dtype=np.float32)
+    z *= np.float32(std)
+    if as_bf16:
+        out_flat[lo:hi] = bf16_bits(z)
+    else:
+        out_flat[lo:hi] = z
+
+
+def _normal(shape, seed, tensor_id, as_bf16, pool, std=_STD, mean=0.0):
+    n = int(np.prod(shape))
+    out = np.empty(n, dtype=np.uint16 if as_bf16 else np.float32)
+    jobs = []
+    for c, lo in enumerate(range(0, n, _CHUNK)):
+        hi = min(n, lo + _CHUNK)
+        jobs.append(pool.submit(_fill_chunk, out, lo, hi, seed, tensor_id, c, std, as_bf16))
+    for j in jobs:
+        j.result()
+    out = out.reshape(shape)
+    if mean != 0.0:
+        assert not as_bf16
+        out += np.float32(mean)
+    return out
+
+
+def make_weights(cfg: WorkloadConfig, threads: int | None = None) -> dict:
+    """Draw all weights of `cfg`.
+
+    Returns a dict: "tok_emb" [V,d], "pos_emb" [max_pos,d] (learned positions only),
+    "lm_head" [V,d], "final_norm_g"/"final_norm_b" [d], and "layers": a list of
+    dicts with "wqkv" [3d,d], "wo" [d,d], "w1" [ff,d] (GELU up / SwiGLU gate),
+    "w_up" [ff,d] (SwiGLU only), "w2" [d,ff], "norm1_g/b", "norm2_g/b" [d].
+    All matrices are row-major [out][in]; uint16 bf16 bit patterns when
+    cfg.dtype is bf16, float32 otherwise.  Norm vectors are float32; biases are
+    present for LayerNorm only.
+    """
+    as_bf16 = cfg.dtype == DTYPE_BF16
+    threads = threads or min(16, os.cpu_count() or 1)
+    d, ff, V = cfg.d_model, cfg.d_ff, cfg.vocab
+    assert cfg.n_head * cfg.head_dim == d
+    random_norm = cfg.norm_init == "random"
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        tid = iter(range(1, 1 << 20))
+
+        def mat(*shape):
+            return _normal(shape, cfg.seed, next(tid), as_bf16, pool)
+
+        def gain():
+            t = next(tid)
+            if random_norm:
+                return _normal((d,), cfg.seed, t, False, pool, std=0.1, mean=1.0)
+            return np.ones(d, dtype=np.float32)
+
+        def bias():
+            t = next(tid)
+            if cfg.norm_kind != NORM_LAYERNORM:
+                return None
+            if random_norm:
+                return _normal((d,), cfg.seed, t, False, pool, std=0.1)
+            return np.zeros(d, dtype=np.float32)
+
+        w = {"tok_emb": mat(V, d)}
+        t_pos = next(tid)
+        if cfg.pos_kind == POS_LEARNED:
+            w["pos_emb"] = _normal((max_positions(cfg), d), cfg.seed, t_pos, as_bf16, pool)
+        w["lm_head"] = mat(V, d)
+        w["final_norm_g"] = gain()
+        w["final_norm_b"] = bias()
+        layers = []
+        for _ in range(cfg.n_layer):
+            lw = {"wqkv": mat(3 * d, d), "wo": mat(d, d), "w1": mat(ff, d)}
+            t_up = next(tid)
+            if cfg.ffn_kind == FFN_SWIGLU:
+                lw["w_up"] = _normal((ff, d), cfg.seed, t_up, as_bf16, pool)
+            lw["w2"] = mat(d, ff)
+            lw["norm1_g"], lw["norm1_b"] = gain(), bias()
+            lw["norm2_g"], lw["norm2_b"] = gain(), bias()
+            layers.append(lw)
+        w["layers"] = layers
+    return w
+
+
+def make_context(cfg: WorkloadConfig) -> np.ndarray:
+    """Context token ids, int32 [B][L], uniform in [0, vocab)."""
+    g = np.random.Generator(np.random.Philox(key=[(cfg.seed << 32) | 0xC0DE, 0]))
+    return g.integers(0, cfg.vocab, size=(cfg.batch, cfg.ctx_len), dtype=np.int32)
+
+
+def make_forced_tokens(cfg: WorkloadConfig, steps: int, salt: int = 1) -> np.ndarray:
+    """Arbitrary token ids, int32 [steps][B][S], uniform in [0, vocab): a seeded
+    stand-in for "the tokens that were generated", for teacher-forced runs."""
+    g = np.random.Generator(np.random.Philox(key=[(cfg.seed << 32) | 0xF0CE, salt]))
+    return g.integers(0, cfg.vocab, size=(steps, cfg.batch, cfg.n_sub), dtype=np.int32)
