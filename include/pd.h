@@ -1,0 +1,164 @@
+/*
+ * pd.h -- C ABI of the pipelined-decoder library for AMD MI355X (gfx950).
+ *
+ * The library implements the decode hot path of the pipelined decoder (paper
+ * Section 3): Algorithm 1 driven one time-step at a time, where every time-step
+ * feeds the newest token of each open subsequence through a decoder-only
+ * transformer (Eq. 3) under the dependency rule of Section 3.2 and selects the
+ * most probable next token for each of them (Eq. 4).
+ *
+ * Conventions
+ *   - "device" pointers are HIP device memory on the current device, "host"
+ *     pointers are ordinary host memory.  The library never allocates or frees
+ *     device memory: weights and the workspace are allocated by the caller (for
+ *     example as PyTorch tensors) and must outlive the pd_ctx.
+ *   - All matrices are row-major [out][in].  dtype 0: fp32 weights, fp32 KV cache.
+ *     dtype 1: bf16 weights (raw 16-bit patterns), bf16 KV cache, fp32 accumulation
+ *     and fp32 residual stream.  Norm gains/biases are always fp32.
+ *   - Every function returns PD_OK (0) or a negative PD_E* code; on error no output
+ *     argument is written and pd_last_error() describes the failure.  Nothing
+ *     throws or aborts across this boundary.
+ *   - A pd_ctx is not re-entrant: one thread and one stream at a time.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).
+ */
+#ifndef PD_H
+#define PD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PD_OK      0
+#define PD_EINVAL -1   /* bad argument: NULL, shape out of range, L > max_ctx, ...      */
+#define PD_ESTATE -2   /* call out of order: decode step before prefill                 */
+#define PD_ENOMEM -3   /* workspace too small                                            */
+#define PD_EHIP   -4   /* a HIP runtime call failed                                      */
+
+typedef struct pd_ctx pd_ctx;   /* opaque; owned by the library between create and destroy */
+
+/* Model shape and capacity.  The paper only says "stacked transformer decoder";
+ * the block is pre-norm, without linear biases:
+ *   x0 = E_tok[token] (+ E_pos[p]);  h = x + Wo Attn(N1(x));  x' = h + FFN(N2(h));
+ *   logits = W_lm N_f(x_last). */
+typedef struct {
+  int32_t n_layer, d_model, n_head, head_dim, d_ff, vocab;  /* n_head*head_dim == d_model */
+  int32_t ffn_kind;    /* 0: W2 gelu_erf(W1 u);  1: W2 (silu(W1 u) * (W_up u))  (SwiGLU)   */
+  int32_t norm_kind;   /* 0: LayerNorm(gain, bias);  1: RMSNorm(gain)                      */
+  int32_t pos_kind;    /* 0: learned absolute table [max_pos][d];  1: rotary, rotate-half  */
+  float   rope_base, norm_eps;
+  int32_t dtype;       /* 0: fp32;  1: bf16 weights + bf16 KV, fp32 accumulate             */
+  int32_t bos_id, eos_id;   /* eos_id < 0 disables end-of-sequence termination             */
+  int32_t max_batch, max_ctx, max_sub, max_sub_tokens;   /* capacity (workspace sizing)    */
+  int32_t max_pos;     /* rows of the learned position table (ignored for rotary)          */
+} pd_config;
+
+/* Device pointers to the weights; per-layer entries are HOST arrays of n_layer
+ * device pointers.  Read-only to the library. */
+typedef struct {
+  const void *tok_emb;        /* [vocab][d]                                  */
+  const void *pos_emb;        /* [max_pos][d], NULL for rotary               */
+  const void *lm_head;        /* [vocab][d] (not tied to tok_emb)            */
+  const float *final_norm_g, *final_norm_b;   /* [d]; bias NULL for RMSNorm  */
+  const void *const *wqkv;    /* [3d][d]: rows 0..d-1 = Q, d..2d-1 = K, 2d..3d-1 = V; head h = rows h*hd.. */
+  const void *const *wo;      /* [d][d]                                      */
+  const void *const *w1;      /* [ff][d]  (GELU: up;  SwiGLU: gate)          */
+  const void *const *w_up;    /* [ff][d]  SwiGLU only, else NULL             */
+  const void *const *w2;      /* [d][ff]                                     */
+  const float *const *norm1_g, *const *norm1_b, *const *norm2_g, *const *norm2_b;   /* [d] */
+} pd_weights;
+
+/* Bytes of device workspace pd_create needs for this configuration (KV caches in
+ * the library's own layout, re-packed weights for the bf16 path, activations,
+ * schedule state).  Returns 0 if the configuration is invalid. */
+size_t pd_workspace_bytes(const pd_config *cfg);
+
+/* Creates a context on the current device.  `dev_workspace` (device, 256-byte
+ * aligned, >= pd_workspace_bytes) is cleared and, for dtype 1, receives a
+ * re-packed copy of every matrix; this runs on `hip_stream` and is complete when
+ * the call returns. */
+int pd_create(const pd_config *cfg, const pd_weights *w, void *dev_workspace, size_t bytes,
+              void *hip_stream, pd_ctx **out);
+int pd_destroy(pd_ctx *ctx);
+
+/* Encodes B contexts of L tokens each (the role of Eq. 1: the input is encoded
+ * once; here as the causal prefix of a decoder-only model, context token j at
+ * position j) into the context KV cache, fixes the decode parameters of Algorithm 1
+ * and resets time to t = 0.
+ *   ctx_tokens  host int32 [B][L], ids in [0, vocab)
+ *   n_sub       sub^max >= 1,  delta_t >= 1,  time_max >= 0
+ *   max_sub_tokens  M >= 1: a subsequence also ends after M generated tokens
+ * Asynchronous on hip_stream except for the copy of ctx_tokens. */
+int pd_prefill_context(pd_ctx *ctx, const int32_t *ctx_tokens, int B, int L, int n_sub,
+                       int delta_t, int max_sub_tokens, int time_max, void *hip_stream);
+
+/* Advances Algorithm 1 by exactly one time-step t (lines 5-13): opens a new
+ * subsequence when (t-1) mod delta_t == 0 and fewer than n_sub exist; feeds the
+ * newest token of every subsequence that has one (position p = L + (t-1) + (i-1));
+ * each row attends to all L context tokens plus the generated-side tokens of
+ * subsequences i' <= i fed so far, including this step's (Section 3.2); appends
+ * argmax(logits) (lowest index on ties, Eq. 4) to every unfinished subsequence;
+ * marks requests whose opened subsequences have all finished.
+ *   force_tokens  host int32 [B][n_sub] or NULL: where >= 0 the value replaces the
+ *                 argmax result of that subsequence (teacher forcing)
+ *   out_tokens    host int32 [B][n_sub] or NULL: token appended this step, -1 if none
+ *   out_logits    DEVICE fp32 [B][n_sub][vocab] or NULL: logits of every row that was
+ *                 fed this step (rows not fed are left untouched)
+ *   out_all_done  host int32 or NULL: 1 when every request has terminated
+ * Host outputs force a stream synchronisation; with all of them NULL the call
+ * only enqueues work.  After termination further calls are no-ops. */
+int pd_decode_step(pd_ctx *ctx, const int32_t *force_tokens, int32_t *out_tokens,
+                   float *out_logits, int32_t *out_all_done, void *hip_stream);
+
+/* pd_prefill_context followed by decode steps until every request has terminated
+ * or time_max steps have run (Algorithm 1 as a whole).
+ *   out_tokens  host int32 [B][n_sub][M]: the subsequences in index order without
+ *               <bos>/<eos>, padded with -1
+ *   out_lens    host int32 [B][n_sub]: tokens in each (0 for subsequences never opened)
+ *   out_steps   host int32 [B]: time-steps run for each request
+ * Synchronises the stream before returning. */
+int pd_generate(pd_ctx *ctx, const int32_t *ctx_tokens, int B, int L, int n_sub, int delta_t,
+                int max_sub_tokens, int time_max, int32_t *out_tokens, int32_t *out_lens,
+                int32_t *out_steps, void *hip_stream);
+
+/* Runs `n_steps` decode steps (no host inputs or outputs) back to back on the
+ * stream; used for timing.  Does not synchronise. */
+int pd_decode_steps(pd_ctx *ctx, int n_steps, void *hip_stream);
+
+/* Restarts decoding at t = 0 for the contexts already encoded (keeps the context
+ * KV cache, drops everything generated).  Asynchronous. */
+int pd_reset_decode(pd_ctx *ctx, void *hip_stream);
+
+/* Tunables and instrumentation.  Keys:
+ *   PD_OPT_ATTN_SPLITS   work-groups per (request, head) in the attention kernel (0 = auto)
+ *   PD_OPT_USE_GRAPH     1: replay each decode step from a captured HIP graph
+ *   PD_OPT_PROFILE       1: bracket the attention kernel of every layer with HIP events
+ *                        (adds event overhead to the step; for measurement only)
+ *   PD_OPT_SPLIT_ACT     bf16 path: 1 (default) carries every activation that enters a matrix
+ *                        multiply as a pair of bf16 values (about 16 mantissa bits) and runs two
+ *                        matrix-core passes per weight / key / value fragment; 0 uses plain bf16
+ *                        activations (half the matrix-core work, larger rounding error)
+ *   PD_OPT_ATTN_PREFETCH 1: each attention wave keeps a second key/value block in flight
+ *                        (more registers, fewer resident waves); 0 (default): one block per wave
+ * The environment variable PD_IMPL=simple makes pd_create choose the fp32-activation kernels
+ * for dtype 1 too (debugging aid).                                                     */
+#define PD_OPT_ATTN_SPLITS 1
+#define PD_OPT_USE_GRAPH   2
+#define PD_OPT_PROFILE     3
+#define PD_OPT_SPLIT_ACT   4
+#define PD_OPT_ATTN_PREFETCH 5
+int pd_set_option(pd_ctx *ctx, int key, int value);
+
+/* Average duration in microseconds of the attention-kernel launches bracketed since
+ * the last call (PD_OPT_PROFILE), and how many there were.  Synchronises. */
+int pd_profile_read(pd_ctx *ctx, double *attn_avg_us, int32_t *attn_launches);
+
+/* Message for the last error on this thread (static storage, never NULL). */
+const char *pd_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PD_H */

@@ -1,0 +1,210 @@
+"""ctypes binding of libpd.so: argument marshalling only.
+
+PyTorch is used for device memory (weights, workspace, logits) and for the
+current HIP stream; every step of the method runs inside the library.
+"""
+
+import ctypes as C
+import os
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libpd.so")
+
+PD_OPT_ATTN_SPLITS, PD_OPT_USE_GRAPH, PD_OPT_PROFILE, PD_OPT_SPLIT_ACT, PD_OPT_ATTN_PREFETCH = 1, 2, 3, 4, 5
+
+EXPORTS = ["pd_workspace_bytes", "pd_create", "pd_destroy", "pd_prefill_context", "pd_decode_step",
+           "pd_generate", "pd_decode_steps", "pd_reset_decode", "pd_set_option", "pd_profile_read",
+           "pd_last_error"]
+
+
+class PdError(RuntimeError):
+    pass
+
+
+class PdConfig(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layer", "d_model", "n_head", "head_dim", "d_ff", "vocab",
+                                         "ffn_kind", "norm_kind", "pos_kind")] + \
+               [("rope_base", C.c_float), ("norm_eps", C.c_float)] + \
+               [(n, C.c_int32) for n in ("dtype", "bos_id", "eos_id", "max_batch", "max_ctx", "max_sub",
+                                         "max_sub_tokens", "max_pos")]
+
+
+class PdWeights(C.Structure):
+    _fields_ = [("tok_emb", C.c_void_p), ("pos_emb", C.c_void_p), ("lm_head", C.c_void_p),
+                ("final_norm_g", C.c_void_p), ("final_norm_b", C.c_void_p)] + \
+               [(n, C.POINTER(C.c_void_p)) for n in ("wqkv", "wo", "w1", "w_up", "w2", "norm1_g",
+                                                      "norm1_b", "norm2_g", "norm2_b")]
+
+
+_lib = None
+
+
+def load():
+    """Loads libpd.so; fails loudly when it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise PdError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                      "(there is no fallback path)")
+    lib = C.CDLL(LIB_PATH)
+    i32p, vp = C.POINTER(C.c_int32), C.c_void_p
+    lib.pd_workspace_bytes.restype = C.c_size_t
+    lib.pd_workspace_bytes.argtypes = [C.POINTER(PdConfig)]
+    lib.pd_create.argtypes = [C.POINTER(PdConfig), C.POINTER(PdWeights), vp, C.c_size_t, vp, C.POINTER(vp)]
+    lib.pd_destroy.argtypes = [vp]
+    lib.pd_prefill_context.argtypes = [vp, i32p] + [C.c_int] * 6 + [vp]
+    lib.pd_decode_step.argtypes = [vp, i32p, i32p, vp, i32p, vp]
+    lib.pd_generate.argtypes = [vp, i32p] + [C.c_int] * 6 + [i32p, i32p, i32p, vp]
+    lib.pd_decode_steps.argtypes = [vp, C.c_int, vp]
+    lib.pd_reset_decode.argtypes = [vp, vp]
+    lib.pd_set_option.argtypes = [vp, C.c_int, C.c_int]
+    lib.pd_profile_read.argtypes = [vp, C.POINTER(C.c_double), i32p]
+    lib.pd_last_error.restype = C.c_char_p
+    for name in EXPORTS:
+        getattr(lib, name)
+    _lib = lib
+    return lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise PdError(f"libpd error {rc}: {load().pd_last_error().decode()}")
+
+
+def _i32(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a, a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+class PipelinedDecoder:
+    """Owns the device copies of the weights and the workspace of one pd_ctx.
+
+    shape: object with the model fields of pd_config (n_layer, d_model, ...),
+    weights: dict of numpy arrays as produced by pd_inputs.make_weights
+    (uint16 = bf16 bit patterns, float32 otherwise).
+    """
+
+    def __init__(self, shape, weights, max_batch, max_ctx, max_sub, max_sub_tokens, max_pos,
+                 device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.lib = load()
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        self.cfg = PdConfig(
+            n_layer=shape.n_layer, d_model=shape.d_model, n_head=shape.n_head, head_dim=shape.head_dim,
+            d_ff=shape.d_ff, vocab=shape.vocab, ffn_kind=shape.ffn_kind, norm_kind=shape.norm_kind,
+            pos_kind=shape.pos_kind, rope_base=shape.rope_base, norm_eps=shape.norm_eps,
+            dtype=shape.dtype, bos_id=shape.bos_id, eos_id=shape.eos_id, max_batch=max_batch,
+            max_ctx=max_ctx, max_sub=max_sub, max_sub_tokens=max_sub_tokens, max_pos=max_pos)
+        self.vocab = shape.vocab
+        self._keep = []          # device tensors referenced by the library
+
+        def dev(a):
+            if a is None:
+                return None, None
+            if a.dtype == np.uint16:
+                t = torch.from_numpy(a.view(np.int16)).to(self.device).view(torch.bfloat16)
+            else:
+                t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(self.device)
+            self._keep.append(t)
+            return t, t.data_ptr()
+
+        w = PdWeights()
+        for name in ("tok_emb", "pos_emb", "lm_head", "final_norm_g", "final_norm_b"):
+            setattr(w, name, dev(weights.get(name))[1])
+        n_layer = shape.n_layer
+        self._arrays = []
+        for name in ("wqkv", "wo", "w1", "w_up", "w2", "norm1_g", "norm1_b", "norm2_g", "norm2_b"):
+            ptrs = [dev(lw.get(name))[1] for lw in weights["layers"]]
+            if all(p is None for p in ptrs):
+                setattr(w, name, None)
+                continue
+            arr = (C.c_void_p * n_layer)(*ptrs)
+            self._arrays.append(arr)
+            setattr(w, name, C.cast(arr, C.POINTER(C.c_void_p)))
+        nbytes = self.lib.pd_workspace_bytes(C.byref(self.cfg))
+        if nbytes == 0:
+            raise PdError(f"invalid configuration: {self.lib.pd_last_error().decode()}")
+        self.workspace_bytes = nbytes
+        self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+        base = (self.workspace.data_ptr() + 255) // 256 * 256
+        self.ctx = C.c_void_p()
+        _check(self.lib.pd_create(C.byref(self.cfg), C.byref(w), base, nbytes, self._stream(),
+                                  C.byref(self.ctx)))
+        self.B = self.S = self.M = 0
+
+    def _stream(self):
+        return C.c_void_p(self.torch.cuda.current_stream(self.device).cuda_stream)
+
+    def close(self):
+        if getattr(self, "ctx", None) is not None and self.ctx.value:
+            self.torch.cuda.synchronize(self.device)
+            self.lib.pd_destroy(self.ctx)
+            self.ctx = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- the three calls of the boundary ---------------------------------------
+    def prefill_context(self, ctx_tokens, n_sub, delta_t, sub_tokens, time_max):
+        a, p = _i32(ctx_tokens)
+        assert a.ndim == 2
+        _check(self.lib.pd_prefill_context(self.ctx, p, a.shape[0], a.shape[1], n_sub, delta_t,
+                                           sub_tokens, time_max, self._stream()))
+        self.B, self.S, self.M = a.shape[0], n_sub, sub_tokens
+
+    def decode_step(self, force=None, want_tokens=True, want_logits=False, want_done=True):
+        """Returns (tokens int32 [B][S] or None, logits torch fp32 [B][S][V] or None, all_done or None)."""
+        fp = None
+        if force is not None:
+            fa, fp = _i32(force)
+            assert fa.shape == (self.B, self.S)
+        toks, tp = (None, None)
+        if want_tokens:
+            toks = np.full((self.B, self.S), -2, dtype=np.int32)
+            tp = toks.ctypes.data_as(C.POINTER(C.c_int32))
+        logits, lp = None, None
+        if want_logits:
+            logits = self.torch.full((self.B, self.S, self.vocab), float("nan"), dtype=self.torch.float32,
+                                     device=self.device)
+            lp = C.c_void_p(logits.data_ptr())
+        done = C.c_int32(0)
+        _check(self.lib.pd_decode_step(self.ctx, fp, tp, lp, C.byref(done) if want_done else None,
+                                       self._stream()))
+        return toks, logits, (bool(done.value) if want_done else None)
+
+    def generate(self, ctx_tokens, n_sub, delta_t, sub_tokens, time_max):
+        """Returns (tokens int32 [B][S][M] padded -1, lens int32 [B][S], steps int32 [B])."""
+        a, p = _i32(ctx_tokens)
+        B = a.shape[0]
+        toks = np.full((B, n_sub, sub_tokens), -2, dtype=np.int32)
+        lens = np.zeros((B, n_sub), dtype=np.int32)
+        steps = np.zeros((B,), dtype=np.int32)
+        i32p = C.POINTER(C.c_int32)
+        _check(self.lib.pd_generate(self.ctx, p, B, a.shape[1], n_sub, delta_t, sub_tokens, time_max,
+                                    toks.ctypes.data_as(i32p), lens.ctypes.data_as(i32p),
+                                    steps.ctypes.data_as(i32p), self._stream()))
+        self.B, self.S, self.M = B, n_sub, sub_tokens
+        return toks, lens, steps
+
+    # -- helpers ---------------------------------------------------------------
+    def decode_steps(self, n):
+        _check(self.lib.pd_decode_steps(self.ctx, n, self._stream()))
+
+    def reset_decode(self):
+        _check(self.lib.pd_reset_decode(self.ctx, self._stream()))
+
+    def set_option(self, key, value):
+        _check(self.lib.pd_set_option(self.ctx, key, value))
+
+    def profile_read(self):
+        us, n = C.c_double(0), C.c_int32(0)
+        _check(self.lib.pd_profile_read(self.ctx, C.byref(us), C.byref(n)))
+        return us.value, n.value

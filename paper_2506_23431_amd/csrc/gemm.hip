@@ -1,0 +1,441 @@
+// Weight re-packing, normalisation and the skinny bf16 GEMM with fused epilogues
+// (QKV + rotary + KV append, residual add, GELU, SwiGLU, vocabulary argmax).
+#include "mfma_common.h"
+
+// ---------------------------------------------------------------------------
+// weight re-packing (runs once, in pd_create)
+//   mode 0: row(n) = n
+//   mode 1: rotary QKV.  Inside the Q and K sections every 16-row tile holds 8 low
+//           dims and their rotation partners: tile th of head h, packed row m:
+//           dim = th*8 + (m & 7) + (m >= 8 ? hd/2 : 0).  V section: identity.
+//   mode 2: SwiGLU.  Tile t holds gate rows t*8..t*8+7 (from src) then up rows
+//           t*8..t*8+7 (from src2).
+// ---------------------------------------------------------------------------
+__global__ void k_pack_weight(bf16_t *dst, const bf16_t *src, const bf16_t *src2, int N_src,
+                              int N_pad, int K, int mode, int d, int hd) {
+  size_t gran = (size_t)blockIdx.x * blockDim.x + threadIdx.x;   // 16-byte granule index
+  int KT = K >> 5;
+  size_t total = (size_t)(N_pad >> 4) * KT * 64;
+  if (gran >= total) return;
+  int lane = gran & 63;
+  size_t frag = gran >> 6;
+  int kt = frag % KT, nt = frag / KT;
+  int m = lane & 15, g = lane >> 4;
+  int n = nt * 16 + m;
+  const bf16_t *row = nullptr;
+  if (mode == 0) {
+    if (n < N_src) row = src + (size_t)n * K;
+  } else if (mode == 1) {
+    if (n < 2 * d) {
+      int sec = n / d, nl = n % d, h = nl / hd, th = (nl % hd) >> 4;
+      int dim = th * 8 + (m & 7) + (m >= 8 ? hd / 2 : 0);
+      row = src + ((size_t)sec * d + h * hd + dim) * K;
+    } else {
+      row = src + (size_t)n * K;
+    }
+  } else {
+    int f = nt * 8 + (m & 7);
+    row = (m < 8 ? src : src2) + (size_t)f * K;
+  }
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (row) v = *(const uint4 *)(row + kt * 32 + g * 8);
+  ((uint4 *)dst)[gran] = v;
+}
+
+static int pack(bf16_t *dst, const void *src, const void *src2, int N_src, int N_pad, int K,
+                int mode, int d, int hd, hipStream_t s) {
+  size_t total = (size_t)(N_pad / 16) * (K / 32) * 64;
+  hipLaunchKernelGGL(k_pack_weight, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, dst,
+                     (const bf16_t *)src, (const bf16_t *)src2, N_src, N_pad, K, mode, d, hd);
+  PD_CHECK_HIP(hipGetLastError());
+  return PD_OK;
+}
+
+int mfma_pack_weights(pd_ctx *c, hipStream_t s) {
+  const pd_config &g = c->cfg;
+  int d = g.d_model, ff = g.d_ff, hd = g.head_dim, rc;
+  for (int l = 0; l < g.n_layer; ++l) {
+    LayerPtrs &lp = c->layers[l];
+    if ((rc = pack(lp.p_wqkv, lp.wqkv, nullptr, 3 * d, 3 * d, d, g.pos_kind == 1 ? 1 : 0, d, hd, s))) return rc;
+    if ((rc = pack(lp.p_wo, lp.wo, nullptr, d, d, d, 0, d, hd, s))) return rc;
+    if (g.ffn_kind == 1) {
+      if ((rc = pack(lp.p_w1, lp.w1, lp.w_up, ff, 2 * ff, d, 2, d, hd, s))) return rc;
+    } else {
+      if ((rc = pack(lp.p_w1, lp.w1, nullptr, ff, ff, d, 0, d, hd, s))) return rc;
+    }
+    if ((rc = pack(lp.p_w2, lp.w2, nullptr, d, d, ff, 0, d, hd, s))) return rc;
+  }
+  return pack(c->p_lm_head, c->lm_head, nullptr, g.vocab, c->vocab_pad, d, 0, d, hd, s);
+}
+
+// ---------------------------------------------------------------------------
+// norm -> bf16 activations.  One block per row; rows without a token become zero.
+// The row is read once into registers (gain and bias are requested at the same
+// time), so the kernel costs one memory round trip plus two block reductions.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float block_sum256(float v, float *sh) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return sh[0] + sh[1] + sh[2] + sh[3];
+}
+
+template <int NG>     // 8-value granules per thread: d <= 2048 * NG
+__global__ __launch_bounds__(256) void k_norm_bf16(bf16_t *xn, bf16_t *xn_lo, const float *x, const float *g,
+                                                   const float *b, int d, int kind, float eps,
+                                                   const int32_t *flags, int R) {
+  __shared__ float sh[4];
+  int r = blockIdx.x;
+  int fl = r < R ? flags[r] : 0;
+  const float *xr = x + (size_t)r * d;
+  float v[NG][8], gv[NG][8], bv[NG][8];
+#pragma unroll
+  for (int i = 0; i < NG; ++i) {
+    int c = (threadIdx.x + i * 256) * 8;
+    bool in = c < d;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      float4 t = in ? *(const float4 *)(xr + c + 4 * h) : make_float4(0.f, 0.f, 0.f, 0.f);
+      float4 tg = in ? *(const float4 *)(g + c + 4 * h) : make_float4(0.f, 0.f, 0.f, 0.f);
+      float4 tb = (in && kind == 0 && b) ? *(const float4 *)(b + c + 4 * h) : make_float4(0.f, 0.f, 0.f, 0.f);
+      v[i][4 * h] = t.x; v[i][4 * h + 1] = t.y; v[i][4 * h + 2] = t.z; v[i][4 * h + 3] = t.w;
+      gv[i][4 * h] = tg.x; gv[i][4 * h + 1] = tg.y; gv[i][4 * h + 2] = tg.z; gv[i][4 * h + 3] = tg.w;
+      bv[i][4 * h] = tb.x; bv[i][4 * h + 1] = tb.y; bv[i][4 * h + 2] = tb.z; bv[i][4 * h + 3] = tb.w;
+    }
+  }
+  bool valid = fl & ROW_VALID;
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < NG; ++i)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s += v[i][e];
+  float mean = kind == 0 ? block_sum256(s, sh) / d : 0.f;
+  float q = 0.f;
+#pragma unroll
+  for (int i = 0; i < NG; ++i) {
+    bool in = (threadIdx.x + i * 256) * 8 < d;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float t = in ? v[i][e] - mean : 0.f;
+      q += t * t;
+    }
+  }
+  float rstd = rsqrtf(block_sum256(q, sh) / d + eps);
+#pragma unroll
+  for (int i = 0; i < NG; ++i) {
+    int c = (threadIdx.x + i * 256) * 8;
+    if (c >= d) continue;
+    Frag hi, lo;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float y = valid ? (v[i][e] - mean) * rstd * gv[i][e] + bv[i][e] : 0.f;
+      hi.h[e] = f32_to_bf16(y);
+      lo.h[e] = f32_to_bf16(bf16_residual(y, hi.h[e]));
+    }
+    size_t off = act_off(r, c, d);
+    *(uint4 *)(xn + off) = hi.u;
+    if (xn_lo) *(uint4 *)(xn_lo + off) = lo.u;
+  }
+}
+
+int mfma_norm(pd_ctx *c, const float *gain, const float *bias, int R, hipStream_t s) {
+  int rows = (R + 15) / 16 * 16, d = c->cfg.d_model;
+  bf16_t *xn = (bf16_t *)c->xn;
+  const pd_config &g = c->cfg;
+  PD_REQUIRE(d <= 2048 * 4, PD_EINVAL, "d_model %d too large for the norm kernel", d);
+#define PD_NORM(V)                                                                               \
+  hipLaunchKernelGGL(k_norm_bf16<V>, dim3(rows), dim3(256), 0, s, xn, mfma_lo(c, xn, d), c->x, gain, bias, d, \
+                     g.norm_kind, g.norm_eps, c->rows.flags, R)
+  if (d <= 2048) PD_NORM(1);
+  else if (d <= 4096) PD_NORM(2);
+  else PD_NORM(4);
+#undef PD_NORM
+  PD_CHECK_HIP(hipGetLastError());
+  return PD_OK;
+}
+
+// ---------------------------------------------------------------------------
+// skinny GEMM  y[r][n] = sum_k xn[r][k] W[n][k],  r < 16*RT rows; weights and
+// activations both fragment-major.
+// The matrix core computes the transposed tile: A = weight fragment (16 output
+// columns x 32 k), B = activations (32 k x 16 rows), D[4g+j][r] = y[r][n0+4g+j].
+// A block has NW_N x NW_K waves: wave (wn, wk) streams the fragments of n-tile
+// blockIdx.x*NW_N + wn over its 1/NW_K share of K; shares are summed through LDS.
+// The launch picks NW_K so that a wave's share is at most 16 fragments: a wave
+// then requests its whole share (16 KiB of weights) before the first multiply,
+// which is what a kernel that lives for a few microseconds needs to pull HBM
+// bandwidth from the first cycle on.
+// ---------------------------------------------------------------------------
+template <int RT, int NW_N, int NW_K, int EPI, bool SPLIT>
+__global__ __launch_bounds__(64 * NW_N * NW_K) void k_gemm(GemmArgs a) {
+  __shared__ floatx4 red[NW_K > 1 ? NW_N * (NW_K - 1) * RT * 64 : 1];
+  int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  int wn = wave % NW_N, wk = wave / NW_N;
+  int nt = blockIdx.x * NW_N + wn;
+  int m = lane & 15, g = lane >> 4;
+  bool active = nt < a.n_tiles;
+  int KT = a.K >> 5;
+  int kt0 = (int)((long)wk * KT / NW_K), kt1 = (int)((long)(wk + 1) * KT / NW_K);
+  floatx4 acc[RT];
+#pragma unroll
+  for (int i = 0; i < RT; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+  if (active && kt1 > kt0) {
+    const uint4 *wp = (const uint4 *)a.W + ((size_t)nt * KT) * 64 + lane;
+    const uint4 *xp = (const uint4 *)a.xn + lane;
+    const uint4 *xl = SPLIT ? (const uint4 *)a.xn_lo + lane : nullptr;
+    constexpr int U = RT == 1 ? (SPLIT ? 8 : 16) : (RT == 2 ? 8 : 4);
+    for (int kt = kt0; kt < kt1; kt += U) {
+      Frag wa[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        int k = min(kt + u, kt1 - 1);
+        uint4 t = wp[(size_t)k * 64];
+        wa[u].u = kt + u < kt1 ? t : make_uint4(0, 0, 0, 0);
+      }
+#pragma unroll
+      for (int i = 0; i < RT; ++i) {
+        Frag xb[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          int k = min(kt + u, kt1 - 1);
+          xb[u].u = xp[((size_t)i * KT + k) * 64];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc[i] = mfma16(wa[u], xb[u], acc[i]);
+        if (SPLIT) {
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            int k = min(kt + u, kt1 - 1);
+            xb[u].u = xl[((size_t)i * KT + k) * 64];
+          }
+#pragma unroll
+          for (int u = 0; u < U; ++u) acc[i] = mfma16(wa[u], xb[u], acc[i]);
+        }
+      }
+    }
+  }
+  if (NW_K > 1) {
+    if (wk > 0) {
+#pragma unroll
+      for (int i = 0; i < RT; ++i) red[((wn * (NW_K - 1) + wk - 1) * RT + i) * 64 + lane] = acc[i];
+    }
+    __syncthreads();
+    if (wk > 0) return;
+#pragma unroll
+    for (int w = 0; w < NW_K - 1; ++w)
+#pragma unroll
+      for (int i = 0; i < RT; ++i) acc[i] += red[((wn * (NW_K - 1) + w) * RT + i) * 64 + lane];
+  }
+  if (!active) return;
+
+  // ---- epilogues: lane holds y[r][n0 + j], r = i*16 + m, n0 = nt*16 + 4g, j = 0..3
+  int n0 = nt * 16 + 4 * g;
+  if (EPI == EPI_RESID) {
+#pragma unroll
+    for (int i = 0; i < RT; ++i) {
+      int r = i * 16 + m;
+      if (r < a.R) {
+        float4 *p = (float4 *)(a.x + (size_t)r * a.ld + n0);
+        float4 v = *p;
+        v.x += acc[i][0]; v.y += acc[i][1]; v.z += acc[i][2]; v.w += acc[i][3];
+        *p = v;
+      }
+    }
+  } else if (EPI == EPI_GELU) {
+#pragma unroll
+    for (int i = 0; i < RT; ++i) {
+      int r = i * 16 + m;
+      float y[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        float t = acc[i][j];
+        y[j] = 0.5f * t * (1.f + erff(t * 0.70710678118654752f));
+      }
+      store4_split(a.out_bf, a.out_lo, act_off(r, n0, a.ld), y);
+    }
+  } else if (EPI == EPI_SWIGLU) {
+    // groups 0,1: gate of features nt*8 + 4g + j; groups 2,3: up of nt*8 + 4(g-2) + j
+#pragma unroll
+    for (int i = 0; i < RT; ++i) {
+      int r = i * 16 + m;
+      float y[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        float mine = acc[i][j];
+        float other = __shfl_xor(mine, 32);
+        y[j] = mine / (1.f + __expf(-mine)) * other;     // meaningful on groups 0,1
+      }
+      if (g < 2) store4_split(a.out_bf, a.out_lo, act_off(r, nt * 8 + 4 * g, a.ld), y);
+    }
+  } else if (EPI == EPI_QKV || EPI == EPI_QKV_ROPE) {
+    int sec = n0 / a.d, nl = n0 % a.d, h = nl / a.hd;
+    int half = a.hd >> 1;
+#pragma unroll
+    for (int i = 0; i < RT; ++i) {
+      int r = i * 16 + m;
+      bool valid = r < a.R && (a.rt.flags[r] & ROW_VALID);
+      float y[4];
+      int dim0;                                  // head-dim index of y[0]; y[j] is dim0 + j
+      if (EPI == EPI_QKV_ROPE && sec < 2) {
+        int th = (nl % a.hd) >> 4;
+        int jj = th * 8 + 4 * (g & 1);           // rotation pair index of y[0]
+        dim0 = jj + (g >= 2 ? half : 0);
+        const float *cs = a.rope_cs + ((size_t)(valid ? a.rt.pos[r] : 0) * half + jj) * 2;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          float mine = acc[i][j];
+          float other = __shfl_xor(mine, 32);
+          float cc = cs[2 * j], ss = cs[2 * j + 1];
+          // low half: x1*c - x2*s ; high half: x2*c + x1*s
+          y[j] = g < 2 ? mine * cc - other * ss : mine * cc + other * ss;
+        }
+      } else {
+        dim0 = (nl % a.hd);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) y[j] = acc[i][j];
+      }
+      if (!valid) continue;
+      if (sec == 0) {
+        store4_split(a.out_bf, a.out_lo, act_off(r, h * a.hd + dim0, a.d), y);
+      } else {
+        size_t head_base = ((size_t)a.rt.req[r] * a.H + h) * a.kv_cap * a.hd;
+        int slot = a.rt.slot[r];
+        if (sec == 1) {
+          *(uint2 *)(a.kc + head_base + k_cache_off(slot, dim0, a.hd)) =
+              make_uint2(pack2(y[0], y[1]), pack2(y[2], y[3]));
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            a.vc[head_base + v_cache_off(slot, dim0 + j, a.hd)] = f32_to_bf16(y[j]);
+        }
+      }
+    }
+  } else if (EPI == EPI_LM) {
+#pragma unroll
+    for (int i = 0; i < RT; ++i) {
+      int r = i * 16 + m;
+      float best = -INFINITY;
+      int bi = 0x7fffffff;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        int n = n0 + j;
+        float t = acc[i][j];
+        if (n < a.V) {
+          if (a.logits && r < a.R) a.logits[(size_t)r * a.ld_logits + n] = t;
+          if (t > best) { best = t; bi = n; }
+        }
+      }
+      // across the 4 column groups of this row; lowest index wins ties
+#pragma unroll
+      for (int o = 16; o <= 32; o <<= 1) {
+        float ov = __shfl_xor(best, o);
+        int oi = __shfl_xor(bi, o);
+        if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+      }
+      if (g == 0) {
+        a.part_val[(size_t)nt * (16 * RT) + r] = best;
+        a.part_idx[(size_t)nt * (16 * RT) + r] = bi;
+      }
+    }
+  }
+}
+
+// second stage of the argmax: one block per row over the per-tile winners
+__global__ __launch_bounds__(256) void k_lm_reduce(int32_t *row_argmax, const float *part_val,
+                                                   const int32_t *part_idx, int n_tiles, int rows,
+                                                   const int32_t *flags) {
+  __shared__ float sv[256];
+  __shared__ int si[256];
+  int r = blockIdx.x;
+  if (!(flags[r] & ROW_VALID)) return;
+  float best = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int t = threadIdx.x; t < n_tiles; t += 256) {
+    float v = part_val[(size_t)t * rows + r];
+    int ix = part_idx[(size_t)t * rows + r];
+    if (v > best || (v == best && ix < bi)) { best = v; bi = ix; }
+  }
+  sv[threadIdx.x] = best; si[threadIdx.x] = bi;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) {
+      float ov = sv[threadIdx.x + o]; int oi = si[threadIdx.x + o];
+      if (ov > sv[threadIdx.x] || (ov == sv[threadIdx.x] && oi < si[threadIdx.x])) {
+        sv[threadIdx.x] = ov; si[threadIdx.x] = oi;
+      }
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) row_argmax[r] = si[0];
+}
+
+int mfma_lm_reduce(pd_ctx *c, int n_tiles, int R, hipStream_t s) {
+  hipLaunchKernelGGL(k_lm_reduce, dim3(R), dim3(256), 0, s, c->row_argmax, c->lm_part_val,
+                     c->lm_part_idx, n_tiles, mfma_gemm_row_tiles(R), c->rows.flags);
+  PD_CHECK_HIP(hipGetLastError());
+  return PD_OK;
+}
+
+// ---------------------------------------------------------------------------
+// launch: row tiles RT in {1,2,4,8}; waves along K so that a wave's share is <= 16
+// fragments (as far as the 1024-thread block and the LDS reduction buffer allow)
+// ---------------------------------------------------------------------------
+template <int RT, int EPI, bool SPLIT>
+static int launch_gemm_rt(const GemmArgs &a, hipStream_t s) {
+  int KT = a.K / 32;
+  int nwk = 1;
+  constexpr int SHARE = SPLIT && RT == 1 ? 8 : 16;   // fragments requested at once by a wave
+  while (nwk < 16 && KT > SHARE * nwk) nwk *= 2;
+  if (RT == 8 && nwk > 8) nwk = 8;
+  // plenty of column tiles: fewer, longer-lived waves are enough to keep HBM busy
+  if ((long)a.n_tiles * nwk > 16384 && nwk > 1) nwk /= 2;
+  switch (nwk) {
+    case 1: hipLaunchKernelGGL((k_gemm<RT, 4, 1, EPI, SPLIT>), dim3((a.n_tiles + 3) / 4), dim3(256), 0, s, a); break;
+    case 2: hipLaunchKernelGGL((k_gemm<RT, 2, 2, EPI, SPLIT>), dim3((a.n_tiles + 1) / 2), dim3(256), 0, s, a); break;
+    case 4: hipLaunchKernelGGL((k_gemm<RT, 1, 4, EPI, SPLIT>), dim3(a.n_tiles), dim3(256), 0, s, a); break;
+    case 8: hipLaunchKernelGGL((k_gemm<RT, 1, 8, EPI, SPLIT>), dim3(a.n_tiles), dim3(512), 0, s, a); break;
+    default:
+      if (RT < 8) hipLaunchKernelGGL((k_gemm<RT, 1, (RT < 8 ? 16 : 8), EPI, SPLIT>), dim3(a.n_tiles), dim3(1024), 0, s, a);
+      break;
+  }
+  PD_CHECK_HIP(hipGetLastError());
+  return PD_OK;
+}
+
+int mfma_gemm_row_tiles(int rows) {
+  int rt = (rows + 15) / 16;
+  return (rt <= 1 ? 1 : rt <= 2 ? 2 : rt <= 4 ? 4 : 8) * 16;
+}
+
+template <int EPI>
+static int launch_gemm(const GemmArgs &a, int rows, hipStream_t s) {
+  PD_REQUIRE(rows <= 128, PD_EINVAL, "more than 128 rows per launch (%d)", rows);
+  if (a.xn_lo) {
+    switch (mfma_gemm_row_tiles(rows)) {
+      case 16: return launch_gemm_rt<1, EPI, true>(a, s);
+      case 32: return launch_gemm_rt<2, EPI, true>(a, s);
+      case 64: return launch_gemm_rt<4, EPI, true>(a, s);
+      default: return launch_gemm_rt<8, EPI, true>(a, s);
+    }
+  }
+  switch (mfma_gemm_row_tiles(rows)) {
+    case 16: return launch_gemm_rt<1, EPI, false>(a, s);
+    case 32: return launch_gemm_rt<2, EPI, false>(a, s);
+    case 64: return launch_gemm_rt<4, EPI, false>(a, s);
+    default: return launch_gemm_rt<8, EPI, false>(a, s);
+  }
+}
+
+int mfma_gemm(int epi, const GemmArgs &a, int rows, hipStream_t s) {
+  switch (epi) {
+    case EPI_QKV: return launch_gemm<EPI_QKV>(a, rows, s);
+    case EPI_QKV_ROPE: return launch_gemm<EPI_QKV_ROPE>(a, rows, s);
+    case EPI_RESID: return launch_gemm<EPI_RESID>(a, rows, s);
+    case EPI_GELU: return launch_gemm<EPI_GELU>(a, rows, s);
+    case EPI_SWIGLU: return launch_gemm<EPI_SWIGLU>(a, rows, s);
+    case EPI_LM: return launch_gemm<EPI_LM>(a, rows, s);
+  }
+  pd_set_error("unknown epilogue %d", epi);
+  return PD_EINVAL;
+}

@@ -1,0 +1,54 @@
+// Launch sequences of the bf16 matrix-core path: one transformer layer and the head.
+#include "mfma_common.h"
+
+bf16_t *mfma_lo(pd_ctx *c, void *buf, size_t cols) {
+  // every activation buffer is sized for fp32 rows; the low parts live in its second half
+  return c->opt_split ? (bf16_t *)buf + (size_t)c->R_pad * cols : nullptr;
+}
+
+int mfma_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_override, hipStream_t s) {
+  const pd_config &g = c->cfg;
+  const LayerPtrs &lw = c->layers[l];
+  int d = g.d_model, ff = g.d_ff, rc;
+  if ((rc = mfma_norm(c, lw.n1g, lw.n1b, R, s))) return rc;
+  GemmArgs a;
+  memset(&a, 0, sizeof(a));
+  a.R = R; a.rt = c->rows; a.d = d; a.H = g.n_head; a.hd = g.head_dim; a.kv_cap = c->kv_cap;
+  // QKV projection (+ rotary) + KV append
+  a.W = lw.p_wqkv; a.xn = (const bf16_t *)c->xn; a.xn_lo = mfma_lo(c, c->xn, d); a.K = d;
+  a.n_tiles = 3 * d / 16; a.out_bf = (bf16_t *)c->q; a.out_lo = mfma_lo(c, c->q, d); a.kc = (bf16_t *)lw.kc; a.vc = (bf16_t *)lw.vc; a.rope_cs = c->rope_cs;
+  if ((rc = mfma_gemm(g.pos_kind == 1 ? EPI_QKV_ROPE : EPI_QKV, a, R, s))) return rc;
+  if ((rc = mfma_attention(c, lw, A, nreq, req0, kv_override, s))) return rc;
+  // output projection + residual
+  a.W = lw.p_wo; a.xn = (const bf16_t *)c->att; a.xn_lo = mfma_lo(c, c->att, d); a.K = d; a.n_tiles = d / 16; a.x = c->x; a.ld = d;
+  if ((rc = mfma_gemm(EPI_RESID, a, R, s))) return rc;
+  if ((rc = mfma_norm(c, lw.n2g, lw.n2b, R, s))) return rc;
+  // FFN
+  a.xn = (const bf16_t *)c->xn; a.xn_lo = mfma_lo(c, c->xn, d); a.K = d;
+  a.out_bf = (bf16_t *)c->hb; a.out_lo = mfma_lo(c, c->hb, ff); a.ld = ff; a.W = lw.p_w1;
+  if (g.ffn_kind == 1) {
+    a.n_tiles = 2 * ff / 16;
+    rc = mfma_gemm(EPI_SWIGLU, a, R, s);
+  } else {
+    a.n_tiles = ff / 16;
+    rc = mfma_gemm(EPI_GELU, a, R, s);
+  }
+  if (rc) return rc;
+  a.W = lw.p_w2; a.xn = (const bf16_t *)c->hb; a.xn_lo = mfma_lo(c, c->hb, ff); a.K = ff; a.n_tiles = d / 16; a.x = c->x; a.ld = d;
+  return mfma_gemm(EPI_RESID, a, R, s);
+}
+
+int mfma_head(pd_ctx *c, int R, bool want_logits, hipStream_t s) {
+  const pd_config &g = c->cfg;
+  int rc;
+  if ((rc = mfma_norm(c, c->fng, c->fnb, R, s))) return rc;
+  GemmArgs a;
+  memset(&a, 0, sizeof(a));
+  a.R = R; a.rt = c->rows; a.W = c->p_lm_head; a.xn = (const bf16_t *)c->xn;
+  a.xn_lo = mfma_lo(c, c->xn, g.d_model); a.K = g.d_model;
+  a.n_tiles = c->vocab_pad / 16; a.V = g.vocab;
+  a.logits = want_logits ? c->logits : nullptr; a.ld_logits = g.vocab;
+  a.part_val = c->lm_part_val; a.part_idx = c->lm_part_idx;
+  if ((rc = mfma_gemm(EPI_LM, a, R, s))) return rc;
+  return mfma_lm_reduce(c, a.n_tiles, R, s);
+}

@@ -1,0 +1,106 @@
+// bf16 matrix-core path for gfx950.
+//
+// Design rule of this file: every large operand that is streamed from HBM once per
+// step (weights, key cache, value cache) is stored in HBM in the exact order in
+// which the 16x16x32 bf16 MFMA instruction wants it in registers.  A "fragment" is
+// the A operand of one such instruction: 16 rows x 32 contraction values = 1 KiB,
+// lane l (0..63) holding 8 consecutive contraction values (16 bytes) of row l%16,
+// contraction group l/16.  A fragment is stored as 64 consecutive 16-byte granules
+// in lane order, so one wave-wide 16-byte load reads 1 KiB contiguous and lands in
+// the operand registers with no shuffle and no LDS round trip.
+//
+//   packed weight  W[N][K]:  fragments [N/16][K/32]; fragment (nt, kt) row m, group g,
+//                            element e  <->  W[row(nt*16+m)][kt*32 + g*8 + e]
+//   K cache (per request, head): blocks of 32 keys; block kb holds 2 tiles x (hd/32)
+//                            fragments; tile t row m=4g'+j <-> key kb*32 + 8g' + 4t + j,
+//                            contraction = head-dim chunk c: dim c*32 + g*8 + e
+//   V cache (per request, head): block kb holds hd/16 fragments; fragment hb row r <->
+//                            dim hb*16 + r, contraction slot (g, e) <-> key kb*32 + 8g + e
+//
+// The key order inside a K tile is chosen so that the score tile S^T = K Q^T comes out
+// of the matrix core already in the register order the P^T operand of O^T = V^T P^T
+// needs: scores never leave registers between the two contractions.
+#pragma once
+#include "pd_internal.h"
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+union Frag {
+  uint4 u;
+  bf16x8 v;
+  bf16_t h[8];
+};
+
+__device__ __forceinline__ floatx4 mfma16(const Frag &a, const Frag &b, floatx4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+// Activations are carried as a pair of bf16 values, x ~ hi + lo with hi = bf16(x) and
+// lo = bf16(x - hi): two matrix-core passes over the same weight fragment then see the
+// activation to about 16 mantissa bits, which costs no extra HBM traffic.
+__device__ __forceinline__ float bf16_residual(float x, bf16_t hi) { return x - bf16_to_f32(hi); }
+
+// Activation matrices [rows][K] that feed a matrix multiply are stored fragment-major too:
+// the B operand of the instruction for row tile rt (16 rows) and k-tile kt (32 values) is
+// 64 consecutive 16-byte granules, lane g*16 + m holding row rt*16 + m, k = kt*32 + g*8 .. +7.
+// A wave therefore reads a B operand as 1 KiB contiguous, like a weight fragment.
+__device__ __forceinline__ size_t act_off(int r, int k, int K) {
+  return ((((size_t)(r >> 4) * (K >> 5) + (k >> 5)) * 64) + ((k & 31) >> 3) * 16 + (r & 15)) * 8 + (k & 7);
+}
+
+// store 4 consecutive values (k multiple of 4) as hi (and, if lo != NULL, lo) bf16 quadruples
+__device__ __forceinline__ void store4_split(bf16_t *hi, bf16_t *lo, size_t off, const float y[4]) {
+  bf16_t h0 = f32_to_bf16(y[0]), h1 = f32_to_bf16(y[1]), h2 = f32_to_bf16(y[2]), h3 = f32_to_bf16(y[3]);
+  *(uint2 *)(hi + off) = make_uint2((uint32_t)h0 | ((uint32_t)h1 << 16), (uint32_t)h2 | ((uint32_t)h3 << 16));
+  if (lo)
+    *(uint2 *)(lo + off) = make_uint2(pack2(bf16_residual(y[0], h0), bf16_residual(y[1], h1)),
+                                      pack2(bf16_residual(y[2], h2), bf16_residual(y[3], h3)));
+}
+
+// element offsets inside the packed caches (per request and head)
+__device__ __forceinline__ size_t k_cache_off(int key, int dim, int hd) {
+  int kb = key >> 5, w = key & 31, gk = w >> 3, j8 = w & 7, t = j8 >> 2, m = gk * 4 + (j8 & 3);
+  int c = dim >> 5, g = (dim & 31) >> 3, e = dim & 7;
+  return ((size_t)(kb * 2 + t) * (hd >> 5) + c) * 512 + (g * 16 + m) * 8 + e;
+}
+__device__ __forceinline__ size_t v_cache_off(int key, int dim, int hd) {
+  int kb = key >> 5, w = key & 31, g = w >> 3, e = w & 7;
+  int hb = dim >> 4, r = dim & 15;
+  return ((size_t)kb * (hd >> 4) + hb) * 512 + (g * 16 + r) * 8 + e;
+}
+
+
+// ---- entry points between the sources of the bf16 path -------------------------------------
+enum { EPI_QKV = 0, EPI_QKV_ROPE = 1, EPI_RESID = 2, EPI_GELU = 3, EPI_SWIGLU = 4, EPI_LM = 5 };
+
+struct GemmArgs {
+  const bf16_t *W;       // packed
+  const bf16_t *xn;      // [16*RT][K] bf16: activations (high part)
+  const bf16_t *xn_lo;   // same shape: bf16(x - high part), or NULL to use the high part only
+  int K, n_tiles, R;
+  // epilogue
+  float *x;              // EPI_RESID: residual stream [R][ld], updated in place
+  bf16_t *out_bf;        // EPI_GELU / EPI_SWIGLU: [rows][ld]; EPI_QKV*: q [rows][d]
+  bf16_t *out_lo;        // low parts of out_bf (written when not NULL)
+  int ld;
+  bf16_t *kc, *vc;       // EPI_QKV*: caches of this layer
+  RowTables rt;
+  const float *rope_cs;
+  int d, H, hd, kv_cap;
+  float *logits; int V, ld_logits;     // EPI_LM: optional logits [rows][ld_logits]
+  float *part_val; int32_t *part_idx;  // EPI_LM: [n_tiles][16*RT] best value / index per tile
+};
+
+int mfma_gemm(int epi, const GemmArgs &a, int rows, hipStream_t s);
+int mfma_gemm_row_tiles(int rows);            // rows a launch reads/writes: 16 * RT
+int mfma_norm(pd_ctx *c, const float *gain, const float *bias, int R, hipStream_t s);
+// low-part twin of an activation buffer (NULL when the split is switched off)
+bf16_t *mfma_lo(pd_ctx *c, void *buf, size_t cols);
+int mfma_lm_reduce(pd_ctx *c, int n_tiles, int R, hipStream_t s);
+int mfma_attention(pd_ctx *c, const LayerPtrs &lw, int A, int nreq, int req0, int kv_override,
+                   hipStream_t s);

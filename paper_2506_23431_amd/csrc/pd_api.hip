@@ -1,0 +1,448 @@
+// Host side of the C ABI: argument validation, workspace carve-up, and the
+// launch sequences for prefill / decode step / generate.  No arithmetic of the
+// method lives here; every step runs in the kernels of sched/simple/mfma.hip.
+#include <stdarg.h>
+#include <stdlib.h>
+
+#include <algorithm>
+#include <new>
+
+#include "pd_internal.h"
+
+static thread_local char g_err[512] = "no error";
+
+void pd_set_error(const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+extern "C" const char *pd_last_error(void) { return g_err; }
+
+// ---------------------------------------------------------------------------
+// configuration checks and derived capacities
+// ---------------------------------------------------------------------------
+static int check_config(const pd_config *g) {
+  PD_REQUIRE(g != nullptr, PD_EINVAL, "config is NULL");
+  PD_REQUIRE(g->n_layer >= 1 && g->d_model >= 1 && g->n_head >= 1 && g->head_dim >= 2 &&
+                 g->d_ff >= 1 && g->vocab >= 1,
+             PD_EINVAL, "model dimensions must be positive");
+  PD_REQUIRE((int64_t)g->n_head * g->head_dim == g->d_model, PD_EINVAL,
+             "n_head * head_dim (%d * %d) != d_model (%d)", g->n_head, g->head_dim, g->d_model);
+  PD_REQUIRE(g->head_dim % 2 == 0 && g->head_dim <= 256, PD_EINVAL,
+             "head_dim must be even and <= 256 (got %d)", g->head_dim);
+  PD_REQUIRE(g->ffn_kind == 0 || g->ffn_kind == 1, PD_EINVAL, "ffn_kind must be 0 or 1");
+  PD_REQUIRE(g->norm_kind == 0 || g->norm_kind == 1, PD_EINVAL, "norm_kind must be 0 or 1");
+  PD_REQUIRE(g->pos_kind == 0 || g->pos_kind == 1, PD_EINVAL, "pos_kind must be 0 or 1");
+  PD_REQUIRE(g->dtype == 0 || g->dtype == 1, PD_EINVAL, "dtype must be 0 (fp32) or 1 (bf16)");
+  PD_REQUIRE(g->norm_eps > 0.f, PD_EINVAL, "norm_eps must be positive");
+  PD_REQUIRE(g->pos_kind == 0 || g->rope_base > 1.f, PD_EINVAL, "rope_base must be > 1");
+  PD_REQUIRE(g->max_batch >= 1 && g->max_ctx >= 1 && g->max_sub >= 1 && g->max_sub_tokens >= 1,
+             PD_EINVAL, "capacities (max_batch, max_ctx, max_sub, max_sub_tokens) must be >= 1");
+  PD_REQUIRE(g->max_pos >= 1, PD_EINVAL, "max_pos must be >= 1");
+  PD_REQUIRE(g->bos_id >= 0 && g->bos_id < g->vocab, PD_EINVAL, "bos_id out of range");
+  PD_REQUIRE(g->eos_id < g->vocab, PD_EINVAL, "eos_id out of range");
+  PD_REQUIRE((int64_t)g->max_sub * (g->max_sub_tokens + 1) + g->max_ctx < (1 << 24), PD_EINVAL,
+             "KV capacity too large");
+  return PD_OK;
+}
+
+static bool mfma_eligible(const pd_config *g) {
+  return g->dtype == 1 && g->head_dim % 32 == 0 && g->head_dim <= 128 && g->d_model % 32 == 0 &&
+         g->d_ff % 32 == 0;
+}
+
+struct Carver {
+  char *base; size_t off;
+  template <typename T> T *take(size_t n) {
+    off = (off + 255) & ~(size_t)255;
+    T *p = base ? (T *)(base + off) : nullptr;
+    off += n * sizeof(T);
+    return p;
+  }
+};
+
+// Lays the workspace out; with base == NULL only the size is computed.
+static size_t carve(const pd_config *g, char *base, pd_ctx *c) {
+  pd_ctx tmp_ctx;
+  pd_ctx *x = c ? c : &tmp_ctx;
+  int d = g->d_model, ff = g->d_ff, H = g->n_head, hd = g->head_dim, V = g->vocab;
+  int B = g->max_batch, S = g->max_sub, M = g->max_sub_tokens;
+  x->impl = mfma_eligible(g) ? 1 : 0;
+  if (const char *e = getenv("PD_IMPL")) {        // debugging aid: PD_IMPL=simple
+    if (!strcmp(e, "simple")) x->impl = 0;
+  }
+  x->gen_cap = S * (M + 1);
+  x->kv_cap = (g->max_ctx + x->gen_cap + 63) / 64 * 64;
+  x->prefill_chunk = 64;
+  int a_max = std::min(S, M + 1);
+  x->R_cap = std::max(B * a_max, x->prefill_chunk);
+  // row buffers are read in tiles of 16 rows, 1/2/4/8 tiles per launch
+  int tiles = (x->R_cap + 15) / 16, t2 = 1;
+  while (t2 < tiles && t2 < 8) t2 *= 2;
+  x->R_pad = std::max(tiles, t2) * 16;
+  x->vocab_pad = (V + 63) / 64 * 64;
+  size_t es = g->dtype == 0 ? 4 : 2;
+  x->kv_layer_bytes = (size_t)B * H * x->kv_cap * hd * es;
+  Carver cv{base, 0};
+  x->layers.resize(g->n_layer);
+  for (int l = 0; l < g->n_layer; ++l) {
+    x->layers[l].kc = cv.take<char>(x->kv_layer_bytes);
+    x->layers[l].vc = cv.take<char>(x->kv_layer_bytes);
+  }
+  size_t Rp = x->R_pad;
+  x->x = cv.take<float>(Rp * d);
+  x->xn = cv.take<float>(Rp * d);
+  x->q = cv.take<float>(Rp * d);
+  x->att = cv.take<float>(Rp * d);
+  x->hb = cv.take<float>(Rp * ff);
+  x->qkv32 = cv.take<float>(Rp * 3 * d);
+  x->logits = cv.take<float>(Rp * (size_t)x->vocab_pad);
+  x->scores = x->impl == 0 ? cv.take<float>((size_t)x->R_cap * H * x->kv_cap) : nullptr;
+  x->att_part = cv.take<float>((size_t)4096 * 16 * (hd + 2));
+  x->lm_parts = (x->vocab_pad / 16);
+  x->lm_part_val = cv.take<float>((size_t)x->lm_parts * Rp);
+  x->lm_part_idx = cv.take<int32_t>((size_t)x->lm_parts * Rp);
+  x->row_argmax = cv.take<int32_t>(Rp);
+  x->rope_rows = g->pos_kind == 1 ? g->max_pos : 0;
+  x->rope_cs = g->pos_kind == 1 ? cv.take<float>((size_t)x->rope_rows * hd) : nullptr;
+  RowTables &rt = x->rows;
+  rt.req = cv.take<int32_t>(Rp); rt.sub = cv.take<int32_t>(Rp); rt.tok = cv.take<int32_t>(Rp);
+  rt.pos = cv.take<int32_t>(Rp); rt.slot = cv.take<int32_t>(Rp); rt.lim = cv.take<int32_t>(Rp);
+  rt.flags = cv.take<int32_t>(Rp); rt.qinfo = cv.take<int4>(Rp);
+  SchedState &st = x->sch;
+  st.step = cv.take<int32_t>(B); st.k_open = cv.take<int32_t>(B);
+  st.n_tok = cv.take<int32_t>((size_t)B * S); st.n_fed = cv.take<int32_t>((size_t)B * S);
+  st.fin = cv.take<int32_t>((size_t)B * S); st.done = cv.take<int32_t>(B);
+  st.steps = cv.take<int32_t>(B); st.n_gen = cv.take<int32_t>(B); st.kv_len = cv.take<int32_t>(B);
+  st.n_rows = cv.take<int32_t>(B);
+  st.grid = cv.take<int32_t>((size_t)B * S * (M + 1));
+  st.gen_sub = cv.take<int32_t>((size_t)B * x->gen_cap);
+  st.step_tok = cv.take<int32_t>((size_t)B * S); st.force = cv.take<int32_t>((size_t)B * S);
+  st.all_done = cv.take<int32_t>(1); st.row_of = cv.take<int32_t>((size_t)B * S);
+  x->ctx_tok = cv.take<int32_t>((size_t)B * g->max_ctx);
+  if (x->impl == 1) {
+    // re-packed weights: same element counts as the originals, rows padded to 16
+    size_t dd = (size_t)d;
+    for (int l = 0; l < g->n_layer; ++l) {
+      LayerPtrs &lp = x->layers[l];
+      lp.p_wqkv = cv.take<bf16_t>(3 * dd * d);
+      lp.p_wo = cv.take<bf16_t>(dd * d);
+      lp.p_w1 = cv.take<bf16_t>((g->ffn_kind == 1 ? 2 : 1) * (size_t)ff * d);
+      lp.p_w2 = cv.take<bf16_t>(dd * ff);
+    }
+    x->p_lm_head = cv.take<bf16_t>((size_t)x->vocab_pad * d);
+  }
+  return (cv.off + 255) & ~(size_t)255;
+}
+
+extern "C" size_t pd_workspace_bytes(const pd_config *cfg) {
+  if (check_config(cfg) != PD_OK) return 0;
+  return carve(cfg, nullptr, nullptr);
+}
+
+// ---------------------------------------------------------------------------
+// create / destroy
+// ---------------------------------------------------------------------------
+extern "C" int pd_create(const pd_config *cfg, const pd_weights *w, void *dev_workspace,
+                         size_t bytes, void *hip_stream, pd_ctx **out) {
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  PD_REQUIRE(w && out && dev_workspace, PD_EINVAL, "weights, workspace and out must not be NULL");
+  PD_REQUIRE(((uintptr_t)dev_workspace & 255) == 0, PD_EINVAL, "workspace must be 256-byte aligned");
+  size_t need = carve(cfg, nullptr, nullptr);
+  PD_REQUIRE(bytes >= need, PD_ENOMEM, "workspace too small: %zu bytes given, %zu needed", bytes, need);
+  PD_REQUIRE(w->tok_emb && w->lm_head && w->final_norm_g && w->wqkv && w->wo && w->w1 && w->w2 &&
+                 w->norm1_g && w->norm2_g,
+             PD_EINVAL, "a required weight pointer is NULL");
+  PD_REQUIRE(cfg->pos_kind == 1 || w->pos_emb, PD_EINVAL, "pos_emb is NULL with learned positions");
+  PD_REQUIRE(cfg->ffn_kind == 0 || w->w_up, PD_EINVAL, "w_up is NULL with SwiGLU");
+  PD_REQUIRE(cfg->norm_kind == 1 || (w->final_norm_b && w->norm1_b && w->norm2_b), PD_EINVAL,
+             "LayerNorm bias pointer is NULL");
+  for (int l = 0; l < cfg->n_layer; ++l) {
+    PD_REQUIRE(w->wqkv[l] && w->wo[l] && w->w1[l] && w->w2[l] && w->norm1_g[l] && w->norm2_g[l],
+               PD_EINVAL, "layer %d: a required weight pointer is NULL", l);
+    PD_REQUIRE(cfg->ffn_kind == 0 || w->w_up[l], PD_EINVAL, "layer %d: w_up is NULL", l);
+    PD_REQUIRE(cfg->norm_kind == 1 || (w->norm1_b[l] && w->norm2_b[l]), PD_EINVAL,
+               "layer %d: LayerNorm bias is NULL", l);
+  }
+  pd_ctx *c = new (std::nothrow) pd_ctx();
+  PD_REQUIRE(c, PD_ENOMEM, "out of host memory");
+  c->cfg = *cfg;
+  c->ws = (char *)dev_workspace; c->ws_bytes = bytes;
+  carve(cfg, c->ws, c);
+  c->tok_emb = w->tok_emb; c->pos_emb = cfg->pos_kind == 0 ? w->pos_emb : nullptr;
+  c->lm_head = w->lm_head; c->fng = w->final_norm_g;
+  c->fnb = cfg->norm_kind == 0 ? w->final_norm_b : nullptr;
+  for (int l = 0; l < cfg->n_layer; ++l) {
+    LayerPtrs &lp = c->layers[l];
+    lp.wqkv = w->wqkv[l]; lp.wo = w->wo[l]; lp.w1 = w->w1[l];
+    lp.w_up = cfg->ffn_kind == 1 ? w->w_up[l] : nullptr; lp.w2 = w->w2[l];
+    lp.n1g = w->norm1_g[l]; lp.n2g = w->norm2_g[l];
+    lp.n1b = cfg->norm_kind == 0 ? w->norm1_b[l] : nullptr;
+    lp.n2b = cfg->norm_kind == 0 ? w->norm2_b[l] : nullptr;
+  }
+  c->prefilled = false; c->host_steps = 0;
+  c->opt_splits = 0; c->opt_graph = 0; c->opt_profile = 0; c->opt_split = 1; c->opt_db = 0;
+  c->graph_exec = nullptr; c->graph_ready = false; c->ev_used = 0; c->h_pinned = nullptr;
+  c->B = c->L = c->S = c->dt = c->M = c->time_max = c->A = c->R = 0;
+  hipStream_t s = (hipStream_t)hip_stream;
+  auto fail = [&](int code) { if (c->h_pinned) (void)hipHostFree(c->h_pinned); delete c; return code; };
+  hipError_t e = hipHostMalloc((void **)&c->h_pinned,
+                               sizeof(int32_t) * (2 * (size_t)cfg->max_batch * cfg->max_sub + 16), 0);
+  if (e != hipSuccess) { pd_set_error("hipHostMalloc failed: %s", hipGetErrorString(e)); return fail(PD_EHIP); }
+  // Clear everything up to the re-packed weights: caches must hold finite values
+  // (masked keys are multiplied by zero), state must start at zero.
+  e = hipMemsetAsync(c->ws, 0, need, s);
+  if (e != hipSuccess) { pd_set_error("hipMemsetAsync failed: %s", hipGetErrorString(e)); return fail(PD_EHIP); }
+  if (cfg->pos_kind == 1 && (rc = launch_rope_table(c, s))) return fail(rc);
+  if (c->impl == 1 && (rc = mfma_pack_weights(c, s))) return fail(rc);
+  e = hipStreamSynchronize(s);
+  if (e != hipSuccess) { pd_set_error("pd_create: %s", hipGetErrorString(e)); return fail(PD_EHIP); }
+  *out = c;
+  return PD_OK;
+}
+
+extern "C" int pd_destroy(pd_ctx *c) {
+  if (!c) return PD_OK;
+  if (c->graph_exec) (void)hipGraphExecDestroy(c->graph_exec);
+  for (hipEvent_t ev : c->ev_pool) (void)hipEventDestroy(ev);
+  if (c->h_pinned) (void)hipHostFree(c->h_pinned);
+  delete c;
+  return PD_OK;
+}
+
+// ---------------------------------------------------------------------------
+// options / instrumentation
+// ---------------------------------------------------------------------------
+static void drop_graph(pd_ctx *c) {
+  if (c->graph_exec) (void)hipGraphExecDestroy(c->graph_exec);
+  c->graph_exec = nullptr; c->graph_ready = false;
+}
+
+extern "C" int pd_set_option(pd_ctx *c, int key, int value) {
+  PD_REQUIRE(c, PD_EINVAL, "ctx is NULL");
+  switch (key) {
+    case PD_OPT_ATTN_SPLITS:
+      PD_REQUIRE(value >= 0 && value <= 256, PD_EINVAL, "attention splits must be in [0, 256]");
+      c->opt_splits = value; drop_graph(c); return PD_OK;
+    case PD_OPT_USE_GRAPH:
+      c->opt_graph = value ? 1 : 0; drop_graph(c); return PD_OK;
+    case PD_OPT_SPLIT_ACT:
+      c->opt_split = value ? 1 : 0; drop_graph(c); return PD_OK;
+    case PD_OPT_ATTN_PREFETCH:
+      c->opt_db = value ? 1 : 0; drop_graph(c); return PD_OK;
+    case PD_OPT_PROFILE:
+      c->opt_profile = value ? 1 : 0; drop_graph(c); c->ev_used = 0; return PD_OK;
+    default:
+      pd_set_error("unknown option key %d", key);
+      return PD_EINVAL;
+  }
+}
+
+extern "C" int pd_profile_read(pd_ctx *c, double *attn_avg_us, int32_t *attn_launches) {
+  PD_REQUIRE(c && attn_avg_us && attn_launches, PD_EINVAL, "NULL argument");
+  size_t pairs = c->ev_used / 2;
+  double total = 0.0;
+  if (pairs) PD_CHECK_HIP(hipEventSynchronize(c->ev_pool[c->ev_used - 1]));
+  for (size_t i = 0; i < pairs; ++i) {
+    float ms = 0.f;
+    PD_CHECK_HIP(hipEventElapsedTime(&ms, c->ev_pool[2 * i], c->ev_pool[2 * i + 1]));
+    total += ms;
+  }
+  *attn_avg_us = pairs ? total * 1000.0 / (double)pairs : 0.0;
+  *attn_launches = (int32_t)pairs;
+  c->ev_used = 0;
+  return PD_OK;
+}
+
+// ---------------------------------------------------------------------------
+// prefill
+// ---------------------------------------------------------------------------
+static int run_layers(pd_ctx *c, int R, int A, int nreq, int req0, int kv_override,
+                      hipStream_t s) {
+  int rc;
+  if ((rc = launch_embed(c, R, s))) return rc;
+  for (int l = 0; l < c->cfg.n_layer; ++l) {
+    rc = c->impl == 1 ? mfma_layer(c, l, R, A, nreq, req0, kv_override, s)
+                      : simple_layer(c, l, R, A, nreq, req0, kv_override, s);
+    if (rc) return rc;
+  }
+  return PD_OK;
+}
+
+extern "C" int pd_prefill_context(pd_ctx *c, const int32_t *ctx_tokens, int B, int L, int n_sub,
+                                  int delta_t, int max_sub_tokens, int time_max, void *hip_stream) {
+  PD_REQUIRE(c && ctx_tokens, PD_EINVAL, "ctx or ctx_tokens is NULL");
+  const pd_config &g = c->cfg;
+  PD_REQUIRE(B >= 1 && B <= g.max_batch, PD_EINVAL, "B = %d out of range [1, %d]", B, g.max_batch);
+  PD_REQUIRE(L >= 1 && L <= g.max_ctx, PD_EINVAL, "L = %d out of range [1, %d]", L, g.max_ctx);
+  PD_REQUIRE(n_sub >= 1 && n_sub <= g.max_sub, PD_EINVAL, "n_sub = %d out of range [1, %d]", n_sub, g.max_sub);
+  PD_REQUIRE(delta_t >= 1, PD_EINVAL, "delta_t must be >= 1 (got %d)", delta_t);
+  PD_REQUIRE(max_sub_tokens >= 1 && max_sub_tokens <= g.max_sub_tokens, PD_EINVAL,
+             "max_sub_tokens = %d out of range [1, %d]", max_sub_tokens, g.max_sub_tokens);
+  PD_REQUIRE(time_max >= 0, PD_EINVAL, "time_max must be >= 0");
+  int64_t t_last = std::min<int64_t>(time_max, (int64_t)(n_sub - 1) * delta_t + max_sub_tokens + 1);
+  int64_t p_max = (int64_t)L + std::max<int64_t>(t_last, 1) + n_sub - 2;
+  PD_REQUIRE(p_max < g.max_pos, PD_EINVAL,
+             "largest position index %lld does not fit max_pos = %d", (long long)p_max, g.max_pos);
+  for (int64_t i = 0; i < (int64_t)B * L; ++i)
+    PD_REQUIRE(ctx_tokens[i] >= 0 && ctx_tokens[i] < g.vocab, PD_EINVAL,
+               "context token %lld = %d out of range [0, %d)", (long long)i, ctx_tokens[i], g.vocab);
+  hipStream_t s = (hipStream_t)hip_stream;
+  c->prefilled = false;
+  drop_graph(c);
+  c->B = B; c->L = L; c->S = n_sub; c->dt = delta_t; c->M = max_sub_tokens; c->time_max = time_max;
+  c->A = std::min(n_sub, max_sub_tokens / delta_t + 1);
+  c->R = B * c->A;
+  PD_REQUIRE(c->impl == 0 || c->R <= 128, PD_EINVAL,
+             "B * rows-per-request = %d exceeds the 128 rows one bf16 step supports", c->R);
+  PD_CHECK_HIP(hipMemcpyAsync(c->ctx_tok, ctx_tokens, sizeof(int32_t) * (size_t)B * L,
+                              hipMemcpyHostToDevice, s));
+  PD_CHECK_HIP(hipStreamSynchronize(s));
+  int rc;
+  if ((rc = launch_reset_state(c, s))) return rc;
+  for (int b = 0; b < B; ++b) {
+    for (int p0 = 0; p0 < L; p0 += c->prefill_chunk) {
+      int n = std::min(c->prefill_chunk, L - p0);
+      if ((rc = launch_prefill_rows(c, b, p0, n, s))) return rc;
+      if ((rc = run_layers(c, n, n, 1, b, p0 + n, s))) return rc;
+    }
+  }
+  // leave the row tables empty so that a stray head/commit sees no rows
+  if ((rc = launch_reset_state(c, s))) return rc;
+  c->prefilled = true;
+  c->host_steps = 0;
+  return PD_OK;
+}
+
+extern "C" int pd_reset_decode(pd_ctx *c, void *hip_stream) {
+  PD_REQUIRE(c, PD_EINVAL, "ctx is NULL");
+  PD_REQUIRE(c->prefilled, PD_ESTATE, "pd_reset_decode before pd_prefill_context");
+  c->host_steps = 0;
+  return launch_reset_state(c, (hipStream_t)hip_stream);
+}
+
+// ---------------------------------------------------------------------------
+// decode step
+// ---------------------------------------------------------------------------
+static int enqueue_step(pd_ctx *c, float *out_logits, hipStream_t s) {
+  int rc;
+  if ((rc = launch_tick(c, s))) return rc;
+  if ((rc = run_layers(c, c->R, c->A, c->B, 0, -1, s))) return rc;
+  rc = c->impl == 1 ? mfma_head(c, c->R, out_logits != nullptr, s) : simple_head(c, c->R, s);
+  if (rc) return rc;
+  return launch_commit(c, out_logits, s);
+}
+
+// One step, optionally replayed from a captured graph (only without logits output
+// and without profiling events, which cannot be recorded into a graph here).
+static int run_step(pd_ctx *c, float *out_logits, hipStream_t s) {
+  if (!c->opt_graph || out_logits || c->opt_profile) return enqueue_step(c, out_logits, s);
+  if (!c->graph_ready) {
+    hipGraph_t graph = nullptr;
+    PD_CHECK_HIP(hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
+    int rc = enqueue_step(c, nullptr, s);
+    hipError_t e = hipStreamEndCapture(s, &graph);
+    if (rc) { if (graph) (void)hipGraphDestroy(graph); return rc; }
+    PD_CHECK_HIP(e);
+    e = hipGraphInstantiate(&c->graph_exec, graph, nullptr, nullptr, 0);
+    (void)hipGraphDestroy(graph);
+    PD_CHECK_HIP(e);
+    c->graph_ready = true;
+  }
+  PD_CHECK_HIP(hipGraphLaunch(c->graph_exec, s));
+  return PD_OK;
+}
+
+extern "C" int pd_decode_step(pd_ctx *c, const int32_t *force_tokens, int32_t *out_tokens,
+                              float *out_logits, int32_t *out_all_done, void *hip_stream) {
+  PD_REQUIRE(c, PD_EINVAL, "ctx is NULL");
+  PD_REQUIRE(c->prefilled, PD_ESTATE, "pd_decode_step before pd_prefill_context");
+  hipStream_t s = (hipStream_t)hip_stream;
+  size_t bs = (size_t)c->B * c->S;
+  if (force_tokens) {
+    for (size_t i = 0; i < bs; ++i)
+      PD_REQUIRE(force_tokens[i] < c->cfg.vocab, PD_EINVAL, "force token %zu = %d out of range", i,
+                 force_tokens[i]);
+    // the staging buffer may still be in flight from the previous call
+    PD_CHECK_HIP(hipStreamSynchronize(s));
+    memcpy(c->h_pinned, force_tokens, bs * sizeof(int32_t));
+    PD_CHECK_HIP(hipMemcpyAsync(c->sch.force, c->h_pinned, bs * sizeof(int32_t),
+                                hipMemcpyHostToDevice, s));
+  }
+  int rc = run_step(c, out_logits, s);
+  if (rc) return rc;
+  c->host_steps++;
+  if (out_tokens || out_all_done) {
+    int32_t *h_tok = c->h_pinned + bs, *h_done = c->h_pinned + 2 * bs;
+    PD_CHECK_HIP(hipMemcpyAsync(h_tok, c->sch.step_tok, bs * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    PD_CHECK_HIP(hipMemcpyAsync(h_done, c->sch.all_done, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    PD_CHECK_HIP(hipStreamSynchronize(s));
+    if (out_tokens) memcpy(out_tokens, h_tok, bs * sizeof(int32_t));
+    if (out_all_done) *out_all_done = (*h_done >= c->B) ? 1 : 0;
+  }
+  return PD_OK;
+}
+
+extern "C" int pd_decode_steps(pd_ctx *c, int n_steps, void *hip_stream) {
+  PD_REQUIRE(c, PD_EINVAL, "ctx is NULL");
+  PD_REQUIRE(c->prefilled, PD_ESTATE, "pd_decode_steps before pd_prefill_context");
+  PD_REQUIRE(n_steps >= 0, PD_EINVAL, "n_steps must be >= 0");
+  for (int i = 0; i < n_steps; ++i) {
+    int rc = run_step(c, nullptr, (hipStream_t)hip_stream);
+    if (rc) return rc;
+    c->host_steps++;
+  }
+  return PD_OK;
+}
+
+// ---------------------------------------------------------------------------
+// generate: Algorithm 1 as a whole
+// ---------------------------------------------------------------------------
+extern "C" int pd_generate(pd_ctx *c, const int32_t *ctx_tokens, int B, int L, int n_sub,
+                           int delta_t, int max_sub_tokens, int time_max, int32_t *out_tokens,
+                           int32_t *out_lens, int32_t *out_steps, void *hip_stream) {
+  PD_REQUIRE(out_tokens && out_lens && out_steps, PD_EINVAL, "output pointer is NULL");
+  int rc = pd_prefill_context(c, ctx_tokens, B, L, n_sub, delta_t, max_sub_tokens, time_max, hip_stream);
+  if (rc) return rc;
+  hipStream_t s = (hipStream_t)hip_stream;
+  int S = n_sub, M = max_sub_tokens;
+  // Upper bound on the iterations: the loop cannot outlast time_max, nor the step
+  // after which every subsequence has reached its length limit.
+  int64_t bound = std::min<int64_t>(time_max, (int64_t)(S - 1) * delta_t + M);
+  int32_t *h_done = c->h_pinned + 2 * (size_t)B * S;
+  int64_t t = 0;
+  bool finished = bound == 0;
+  while (!finished) {
+    // Without <eos> the length of the run is known; otherwise look at the
+    // termination counter every few steps (steps after termination are no-ops).
+    int burst = c->cfg.eos_id < 0 ? (int)std::min<int64_t>(bound - t, 64) : (int)std::min<int64_t>(bound - t, 8);
+    if ((rc = pd_decode_steps(c, burst, s))) return rc;
+    t += burst;
+    PD_CHECK_HIP(hipMemcpyAsync(h_done, c->sch.all_done, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    PD_CHECK_HIP(hipStreamSynchronize(s));
+    finished = (*h_done >= B) || t >= bound;
+  }
+  if (bound == 0) {            // time_max == 0: one tick marks the requests terminated
+    if ((rc = launch_tick(c, s))) return rc;
+  }
+  std::vector<int32_t> grid((size_t)B * S * (M + 1)), ntok((size_t)B * S), fin((size_t)B * S), steps(B);
+  PD_CHECK_HIP(hipMemcpyAsync(grid.data(), c->sch.grid, grid.size() * 4, hipMemcpyDeviceToHost, s));
+  PD_CHECK_HIP(hipMemcpyAsync(ntok.data(), c->sch.n_tok, ntok.size() * 4, hipMemcpyDeviceToHost, s));
+  PD_CHECK_HIP(hipMemcpyAsync(fin.data(), c->sch.fin, fin.size() * 4, hipMemcpyDeviceToHost, s));
+  PD_CHECK_HIP(hipMemcpyAsync(steps.data(), c->sch.steps, steps.size() * 4, hipMemcpyDeviceToHost, s));
+  PD_CHECK_HIP(hipStreamSynchronize(s));
+  for (int b = 0; b < B; ++b) {
+    out_steps[b] = steps[b];
+    for (int i = 0; i < S; ++i) {
+      size_t bi = (size_t)b * S + i;
+      int n = ntok[bi] > 0 ? ntok[bi] - 1 - (fin[bi] == 1 ? 1 : 0) : 0;   // drop <bos> and <eos>
+      out_lens[bi] = n;
+      for (int j = 0; j < M; ++j)
+        out_tokens[bi * M + j] = j < n ? grid[bi * (M + 1) + 1 + j] : -1;
+    }
+  }
+  return PD_OK;
+}

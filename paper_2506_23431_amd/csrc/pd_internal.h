@@ -1,0 +1,150 @@
+// Internal declarations shared by the HIP sources of libpd.  Not part of the ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+#include <vector>
+
+#include "pd.h"
+
+typedef uint16_t bf16_t;   // raw bf16 bit pattern
+
+// ---------------------------------------------------------------------------
+// error plumbing
+// ---------------------------------------------------------------------------
+void pd_set_error(const char *fmt, ...);
+
+#define PD_CHECK_HIP(expr)                                                         \
+  do {                                                                             \
+    hipError_t e_ = (expr);                                                        \
+    if (e_ != hipSuccess) {                                                        \
+      pd_set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+      return PD_EHIP;                                                              \
+    }                                                                              \
+  } while (0)
+
+#define PD_REQUIRE(cond, code, ...)                                                \
+  do {                                                                             \
+    if (!(cond)) {                                                                 \
+      pd_set_error(__VA_ARGS__);                                                   \
+      return (code);                                                               \
+    }                                                                              \
+  } while (0)
+
+// ---------------------------------------------------------------------------
+// device helpers
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// round-to-nearest-even; inputs are finite in this library
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float ld_f32(const float *p, size_t i) { return p[i]; }
+__device__ __forceinline__ float ld_f32(const bf16_t *p, size_t i) { return bf16_to_f32(p[i]); }
+__device__ __forceinline__ void st_f32(float *p, size_t i, float v) { p[i] = v; }
+__device__ __forceinline__ void st_f32(bf16_t *p, size_t i, float v) { p[i] = f32_to_bf16(v); }
+
+// ---------------------------------------------------------------------------
+// per-row tables written by the schedule tick (decode) or the prefill set-up.
+// Row r of a launch belongs to request row_req[r]; invalid rows have flags == 0.
+// ---------------------------------------------------------------------------
+#define ROW_VALID   1   // the row carries a token this step
+#define ROW_PRODUCE 2   // a next token is selected from this row's logits
+
+struct RowTables {
+  int32_t *req;    // [R] request index
+  int32_t *sub;    // [R] subsequence index (1-based); prefill rows: 0
+  int32_t *tok;    // [R] token id fed
+  int32_t *pos;    // [R] position index p
+  int32_t *slot;   // [R] KV slot (unified index: context j -> j, generated g -> L + g)
+  int32_t *lim;    // [R] keys with index < lim are visible unconditionally
+  int32_t *flags;  // [R]
+  int4 *qinfo;     // [R] {flags, sub, lim, req} again, packed so that one load fetches them
+};
+
+// schedule state of Algorithm 1, one instance per request, all on the device
+struct SchedState {
+  int32_t *step;      // [B]   iterations started so far (t of the current step)
+  int32_t *k_open;    // [B]   subsequences opened
+  int32_t *n_tok;     // [B][S] tokens held incl. <bos> (0 = not opened)
+  int32_t *n_fed;     // [B][S] tokens already fed to the decoder
+  int32_t *fin;       // [B][S] finished flag (1 = by <eos>, 2 = by the length limit)
+  int32_t *done;      // [B]   request terminated
+  int32_t *steps;     // [B]   iterations run when it terminated
+  int32_t *n_gen;     // [B]   generated-side KV slots in use
+  int32_t *kv_len;    // [B]   L + n_gen
+  int32_t *n_rows;    // [B]   rows this step
+  int32_t *grid;      // [B][S][M+1] token grid, index 0 = <bos>
+  int32_t *gen_sub;   // [B][gen_cap] subsequence of each generated-side KV slot
+  int32_t *step_tok;  // [B][S] token appended this step (-1 = none)
+  int32_t *force;     // [B][S] teacher-forcing input (-1 = none)
+  int32_t *all_done;  // [1]   number of requests that have terminated
+  int32_t *row_of;    // [B][S] row index of subsequence this step (-1 = none)
+};
+
+struct LayerPtrs {
+  const void *wqkv, *wo, *w1, *w_up, *w2;          // caller's row-major matrices
+  const float *n1g, *n1b, *n2g, *n2b;
+  // MFMA path: re-packed copies inside the workspace
+  bf16_t *p_wqkv, *p_wo, *p_w1, *p_w2;
+  void *kc, *vc;                                   // KV caches of this layer
+};
+
+struct pd_ctx {
+  pd_config cfg;
+  const void *tok_emb, *pos_emb, *lm_head;
+  bf16_t *p_lm_head;
+  const float *fng, *fnb;
+  std::vector<LayerPtrs> layers;
+  int impl;                 // 0: fp32-activation kernels; 1: bf16 MFMA kernels
+  // capacities
+  int gen_cap, kv_cap, R_cap, R_pad, vocab_pad, prefill_chunk;
+  size_t kv_layer_bytes;    // bytes of one K (or V) cache of one layer
+  // workspace carve-up
+  char *ws; size_t ws_bytes;
+  float *x;                 // [R_cap][d] residual stream
+  void *xn, *q, *att, *hb;  // activations (type depends on impl)
+  float *qkv32;             // simple path: [R_cap][3d]
+  float *logits;            // [R_cap][vocab] internal logits (simple path / parity output)
+  float *scores;            // simple path attention scratch
+  float *att_part;          // split-K partials of the attention kernel
+  float *lm_part_val; int32_t *lm_part_idx; int lm_parts;
+  int32_t *row_argmax;      // [R_cap] argmax of each row's logits
+  float *rope_cs;           // [max_pos][hd/2][2] cos, sin
+  int rope_rows;
+  RowTables rows;
+  SchedState sch;
+  int32_t *ctx_tok;         // [B][L] device copy of the context ids
+  // decode parameters fixed by prefill
+  int B, L, S, dt, M, time_max, A, R;
+  bool prefilled;
+  int host_steps;           // decode steps enqueued since prefill/reset
+  // options
+  int opt_splits, opt_graph, opt_profile, opt_split, opt_db;
+  hipGraphExec_t graph_exec; bool graph_ready;
+  std::vector<hipEvent_t> ev_pool; size_t ev_used;
+  int32_t *h_pinned;        // small pinned host staging buffer
+};
+
+// ---- launchers (each returns PD_OK or an error code) -----------------------
+// schedule / glue (sched.hip)
+int launch_reset_state(pd_ctx *c, hipStream_t s);
+int launch_tick(pd_ctx *c, hipStream_t s);
+int launch_prefill_rows(pd_ctx *c, int b, int p0, int n, hipStream_t s);
+int launch_embed(pd_ctx *c, int R, hipStream_t s);
+int launch_commit(pd_ctx *c, float *out_logits, hipStream_t s);
+int launch_rope_table(pd_ctx *c, hipStream_t s);
+// fp32-activation path (simple.hip)
+int simple_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_override, hipStream_t s);
+int simple_head(pd_ctx *c, int R, hipStream_t s);
+// MFMA path (mfma.hip)
+int mfma_pack_weights(pd_ctx *c, hipStream_t s);
+int mfma_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_override, hipStream_t s);
+int mfma_head(pd_ctx *c, int R, bool want_logits, hipStream_t s);
+size_t mfma_packed_weight_bytes(const pd_config *cfg);

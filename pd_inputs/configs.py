@@ -40,6 +40,9 @@ class WorkloadConfig:
     sub_tokens: int = 16  # M = per-subsequence token limit
     # norm parameters: "identity" (gain 1, bias 0) or "random"
     norm_init: str = "identity"
+    # standard deviation of the QKV projection (0.02 everywhere in the named workloads; test
+    # cases raise it to make the attention distribution peaky, so that mask errors show)
+    qkv_std: float = 0.02
 
     @property
     def time_steps(self) -> int:

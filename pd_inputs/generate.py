@@ -108,7 +108,8 @@ def make_weights(cfg: WorkloadConfig, threads: int | None = None) -> dict:
         w["final_norm_b"] = bias()
         layers = []
         for _ in range(cfg.n_layer):
-            lw = {"wqkv": mat(3 * d, d), "wo": mat(d, d), "w1": mat(ff, d)}
+            lw = {"wqkv": _normal((3 * d, d), cfg.seed, next(tid), as_bf16, pool, std=cfg.qkv_std),
+                  "wo": mat(d, d), "w1": mat(ff, d)}
             t_up = next(tid)
             if cfg.ffn_kind == FFN_SWIGLU:
                 lw["w_up"] = _normal((ff, d), cfg.seed, t_up, as_bf16, pool)

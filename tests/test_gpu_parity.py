@@ -1,0 +1,161 @@
+"""GPU parity: the HIP library against the CPU oracle, element by element, through the C ABI.
+Small and medium workloads that the oracle finishes in seconds: several tiles, ragged tails,
+both code paths (fp32-activation kernels and bf16 MFMA kernels), all block variants."""
+
+import sys
+
+import numpy as np
+import pytest
+
+import pd_inputs as pi
+from pd_inputs.configs import (WorkloadConfig, DTYPE_F32, DTYPE_BF16, FFN_SWIGLU, NORM_RMSNORM, POS_ROPE)
+from parity_util import oracle_run, make_decoder, compare_teacher_forced
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def small(name, **kw):
+    base = dict(name=name, seed=21, dtype=DTYPE_F32, n_layer=2, d_model=48, n_head=4, head_dim=12,
+                d_ff=80, vocab=203, batch=2, ctx_len=37, n_sub=5, delta_t=2, sub_tokens=6,
+                norm_init="random", qkv_std=0.3)
+    base.update(kw)
+    if base["dtype"] == DTYPE_BF16 and "qkv_std" not in kw:
+        # bf16 rounding of q and k scales with the score magnitude: keep the attention peaky
+        # (score std about 1) but within what the 2e-2 logit tolerance can resolve
+        base["qkv_std"] = 0.1
+    return WorkloadConfig(**base)
+
+
+LLAMA = dict(ffn_kind=FFN_SWIGLU, norm_kind=NORM_RMSNORM, pos_kind=POS_ROPE)
+
+CASES = {
+    # fp32 kernels
+    "cfg1": pi.get_config("cfg1"),
+    "f32-ragged": small("f32-ragged"),
+    "f32-llama": small("f32-llama", seed=22, **LLAMA),
+    "f32-dt1": small("f32-dt1", seed=23, delta_t=1, n_sub=6, sub_tokens=4, batch=1),
+    # bf16 weights on the fp32-activation kernels (head_dim not a multiple of 32)
+    "bf16-simple": small("bf16-simple", seed=24, dtype=DTYPE_BF16, head_dim=12),
+    # bf16 MFMA kernels: head_dim 32 / 64 / 128, vocab not a multiple of 16, context not a
+    # multiple of the 32-key block, more than 16 rows, rotary + SwiGLU, peaky attention
+    "mfma-hd64": small("mfma-hd64", seed=25, dtype=DTYPE_BF16, d_model=128, n_head=2, head_dim=64,
+                       d_ff=256, vocab=1003, ctx_len=150, n_sub=5, delta_t=2, sub_tokens=7),
+    "mfma-hd32": small("mfma-hd32", seed=26, dtype=DTYPE_BF16, d_model=96, n_head=3, head_dim=32,
+                       d_ff=160, vocab=517, ctx_len=75, n_sub=4, delta_t=1, sub_tokens=5, batch=3),
+    "mfma-hd128-llama": small("mfma-hd128-llama", seed=27, dtype=DTYPE_BF16, d_model=256, n_head=2,
+                              head_dim=128, d_ff=352, vocab=777, ctx_len=200, n_sub=6, delta_t=2,
+                              sub_tokens=9, batch=2, **LLAMA),
+    "mfma-manyrows": small("mfma-manyrows", seed=28, dtype=DTYPE_BF16, d_model=128, n_head=2,
+                           head_dim=64, d_ff=256, vocab=640, ctx_len=97, n_sub=20, delta_t=1,
+                           sub_tokens=24, batch=2, n_layer=1),
+    "mfma-flat": small("mfma-flat", seed=29, dtype=DTYPE_BF16, d_model=128, n_head=2, head_dim=64,
+                       d_ff=256, vocab=1000, ctx_len=600, n_sub=4, delta_t=3, sub_tokens=8, batch=1,
+                       qkv_std=0.02, norm_init="identity"),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_teacher_forced_parity(name):
+    cfg = CASES[name]
+    say(f"[case] {name}: {cfg}")
+    w = pi.make_weights(cfg, threads=4)
+    ctx = pi.make_context(cfg)
+    outs = oracle_run(cfg, w, ctx)
+    dec = make_decoder(cfg, w)
+    stats = compare_teacher_forced(cfg, w, ctx, dec, outs, log=say)
+    assert stats["rows"] == cfg.batch * (cfg.n_sub * (cfg.sub_tokens + 1) - 1)
+    dec.close()
+
+
+def test_forced_arbitrary_tokens_and_eos():
+    """Arbitrary forced tokens (not the model's own), with <eos> among them: subsequences end
+    early, their last token is fed once more, exploratory subsequences keep opening."""
+    cfg = small("f32-eos", seed=31, eos_id=7, n_sub=6, delta_t=1, sub_tokens=6, batch=2)
+    w = pi.make_weights(cfg, threads=4)
+    ctx = pi.make_context(cfg)
+    force = 8 + pi.make_forced_tokens(cfg, cfg.time_steps) % (cfg.vocab - 8)
+    force[2, 0, 0] = 7          # request 0: subsequence 1 ends at step 3
+    force[4, 0, 2] = 7          # request 0: subsequence 3 ends at step 5
+    force[3, 1, 1] = 7          # request 1: subsequence 2 ends at step 4
+    outs = oracle_run(cfg, w, ctx, force=force)
+    assert len(outs[0]["result"][0]) == 2 and len(outs[1]["result"][1]) == 2
+    dec = make_decoder(cfg, w)
+    compare_teacher_forced(cfg, w, ctx, dec, outs, force=force, log=say)
+    dec.close()
+
+
+@pytest.mark.parametrize("name", ["cfg1", "mfma-hd64"])
+def test_generate_matches_oracle_until_a_close_call(name):
+    """Free-running pd_generate: identical tokens up to the first iteration in which some row's
+    top-2 margin is too small to expect the same decision; step counts and lengths always agree
+    (EOS is disabled in these workloads)."""
+    cfg = CASES[name]
+    w = pi.make_weights(cfg, threads=4)
+    ctx = pi.make_context(cfg)
+    outs = oracle_run(cfg, w, ctx)
+    dec = make_decoder(cfg, w)
+    toks, lens, steps = dec.generate(ctx, cfg.n_sub, cfg.delta_t, cfg.sub_tokens, cfg.time_steps)
+    thr = 1e-3 if cfg.dtype == 0 else 0.05
+    for b, o in enumerate(outs):
+        assert steps[b] == o["steps"] == cfg.time_steps
+        assert lens[b].tolist() == [len(r) for r in o["result"]]
+        safe = len(o["trace"])
+        for t, rec in enumerate(o["trace"]):
+            top2 = np.partition(rec["logits"], -2, axis=1)[:, -2:]
+            if (top2[:, 1] - top2[:, 0]).min() < thr:
+                safe = t
+                break
+        checked = 0
+        for t in range(safe):
+            for i, tok in o["emitted"][t].items():
+                j = t - (i - 1) * cfg.delta_t          # token index inside subsequence i
+                assert toks[b, i - 1, j] == tok, f"request {b} step {t + 1} subsequence {i}"
+                checked += 1
+        say(f"[generate] {name} request {b}: {checked} tokens identical before the first close call "
+            f"(iteration {safe + 1} of {o['steps']})")
+    dec.close()
+
+
+def test_boundary_errors():
+    from paper_2506_23431_amd import PdError
+    cfg = CASES["cfg1"]
+    w = pi.make_weights(cfg, threads=2)
+    ctx = pi.make_context(cfg)
+    dec = make_decoder(cfg, w)
+    with pytest.raises(PdError, match="before pd_prefill_context"):
+        dec.B, dec.S = 1, cfg.n_sub
+        dec.decode_step()
+    with pytest.raises(PdError, match="delta_t"):
+        dec.prefill_context(ctx, cfg.n_sub, 0, cfg.sub_tokens, 10)
+    with pytest.raises(PdError, match="n_sub"):
+        dec.prefill_context(ctx, cfg.n_sub + 1, 1, cfg.sub_tokens, 10)
+    with pytest.raises(PdError, match="out of range"):
+        bad = ctx.copy(); bad[0, 3] = cfg.vocab
+        dec.prefill_context(bad, cfg.n_sub, 1, cfg.sub_tokens, 10)
+    with pytest.raises(PdError, match="L ="):
+        dec.prefill_context(np.zeros((1, cfg.ctx_len + 1), np.int32), cfg.n_sub, 1, cfg.sub_tokens, 10)
+    # time_max bounds the loop: 3 steps, then further steps are no-ops
+    toks, lens, steps = dec.generate(ctx, cfg.n_sub, cfg.delta_t, cfg.sub_tokens, 3)
+    assert steps[0] == 3 and lens[0].tolist() == [3, 1, 0, 0]
+    t, _, done = dec.decode_step()
+    assert done and np.all(t == -1)
+    dec.close()
+
+
+def test_cfg2_full_size():
+    """BART-base-shaped workload at full size: all 92 iterations, every logit row."""
+    cfg = pi.get_config("cfg2")
+    say(f"[case] cfg2 full size: {cfg}")
+    w = pi.make_weights(cfg)
+    ctx = pi.make_context(cfg)
+    outs = oracle_run(cfg, w, ctx)
+    say("[cfg2] oracle done")
+    dec = make_decoder(cfg, w)
+    stats = compare_teacher_forced(cfg, w, ctx, dec, outs, log=say)
+    assert stats["rows"] == cfg.n_sub * (cfg.sub_tokens + 1) - 1
+    dec.close()
