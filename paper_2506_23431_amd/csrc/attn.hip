@@ -6,12 +6,10 @@
 // so the rule is one integer compare per key.  Prefill rows use the same kernel
 // with a causal limit instead (key index < lim).
 //
-// grid (split, head, request * query-group); block = 4 waves.  A block owns a
-// contiguous range of 32-key blocks of one (request, head); the range is a static
-// share of the largest key count the launch can meet, so the first K/V fragments
-// are requested before anything else is known.  Its waves take the blocks
-// round-robin, with the next block's 16 KiB in flight while the current one is
-// multiplied.  Per block of 32 keys: 2*(hd/32) K fragments and hd/16 V fragments
+// grid (split, head, request * query-group); block = 4 waves.  The 32-key blocks of one
+// (request, head) are dealt round-robin to the 4*nsplit waves that serve it, so the
+// first block of every wave is known at launch and its K/V fragments are requested
+// before anything else is read.  Per block of 32 keys: 2*(hd/32) K fragments and hd/16 V fragments
 // (1 KiB each, contiguous), two 16-key score tiles S^T = K Q^T, mask, online
 // softmax (running max / sum per query), O^T += V^T P^T.  Up to 16 query rows of a
 // request share every key/value byte read.  Waves are merged through LDS; blocks
@@ -50,7 +48,7 @@ __device__ __forceinline__ void load_block(KVBlock<HD> &b, const uint4 *Kp, cons
 }
 
 template <int HD, bool SPLIT, bool DB>
-__global__ __launch_bounds__(256) void k_attn_mfma(AttnArgs a) {
+__global__ __launch_bounds__(256, DB ? 1 : 3) void k_attn_mfma(AttnArgs a) {
   constexpr int NC = HD / 32, NHB = HD / 16, PSTR = HD + 2;   // partial: m, l, O[HD] per query
   __shared__ float sm_m[4][16], sm_l[4][16];
   __shared__ float sm_o[4][HD][17];
@@ -61,11 +59,12 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnArgs a) {
 
   const uint4 *Kp = (const uint4 *)(a.kc + ((size_t)req * a.H + h) * a.kv_cap * HD) + lane;
   const uint4 *Vp = (const uint4 *)(a.vc + ((size_t)req * a.H + h) * a.kv_cap * HD) + lane;
-  int bps = (a.nblk_static + a.nsplit - 1) / a.nsplit;
-  int b0 = split * bps, b1 = min(a.nblk_static, b0 + bps);
-  int kb = b0 + wave;
+  // 32-key blocks are dealt round-robin to the 4*nsplit waves that serve this (request, head):
+  // whatever the current key count, no wave gets more than one block above the average
+  const int stride = 4 * a.nsplit;
+  int kb = split * 4 + wave;
   KVBlock<HD> A, B;
-  if (kb < b1) load_block<HD>(A, Kp, Vp, kb);      // in flight while the row data is fetched
+  if (kb < a.nblk_static) load_block<HD>(A, Kp, Vp, kb);   // in flight while the row data is fetched
 
   // everything the block needs to know about its queries, requested in one go: no load
   // below depends on the result of another
@@ -93,7 +92,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnArgs a) {
   // keys any query of this group can see
   int reach = qvalid ? (n_keys > a.L && q_sub >= 1 ? n_keys : min(q_lim, n_keys)) : 0;
   for (int o = 1; o < 16; o <<= 1) reach = max(reach, __shfl_xor(reach, o));
-  int end = min(b1, (reach + 31) >> 5);
+  int end = min(a.nblk_static, (reach + 31) >> 5);
   const int32_t *gs = a.gen_sub + (size_t)req * a.gen_cap;
 
   float m_run = -INFINITY, l_run = 0.f;
@@ -160,12 +159,12 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnArgs a) {
     // ping-pong over the wave's blocks kb, kb+4, ...: the next block is requested
     // before the current one is consumed
     while (kb < end) {
-      int kn = kb + 4;
+      int kn = kb + stride;
       if (kn < end) load_block<HD>(B, Kp, Vp, kn);
       compute(A, kb);
       if (kn >= end) break;
       kb = kn;
-      kn = kb + 4;
+      kn = kb + stride;
       if (kn < end) load_block<HD>(A, Kp, Vp, kn);
       compute(B, kb);
       kb = kn;
@@ -174,7 +173,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnArgs a) {
     // one block in flight per wave; the resident waves of the compute unit overlap
     while (kb < end) {
       compute(A, kb);
-      kb += 4;
+      kb += stride;
       if (kb < end) load_block<HD>(A, Kp, Vp, kb);
     }
   }
@@ -215,86 +214,80 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnArgs a) {
     }
     return;
   }
+  // partial of this block: rows m, l, O[0..HD) of 16 floats (one per query): stores of
+  // neighbouring lanes are contiguous
   size_t unit = (size_t)z * a.H + h;
-  float *pp = a.part + ((unit * a.nsplit + split) * 16 + qn) * (size_t)PSTR;
-  if (dd == 0) { pp[0] = M; pp[1] = lsum; }
+  float *pp = a.part + (unit * a.nsplit + split) * (size_t)(PSTR * 16) + qn;
+  if (dd == 0) { pp[0] = M; pp[16] = lsum; }
   for (int dim = dd; dim < HD; dim += 16) {
     float o = 0.f;
 #pragma unroll
     for (int w = 0; w < 4; ++w) o += fw[w] * sm_o[w][dim][qn];
-    pp[2 + dim] = o;
+    pp[(2 + dim) * 16] = o;
   }
 }
 
-// Merge of the split partials.  Block = (unit, group of 4 queries), one wave per query.
-// Lane sp first fetches (max, sum) of split sp, the wave reduces them to the global max and
-// the normaliser; then lane t accumulates dims t and t+64 over the splits, 8 splits' loads in
-// flight at a time.
+// Merge of the split partials by log-sum-exp.  Block = (unit, 16 dims); thread = (query, dim).
+// The (max, sum) pairs of a query are read once, spread over the 4 lanes of a wave that share
+// the query, and reduced by shuffles; then every thread accumulates its dim over the splits with
+// 16 splits' loads in flight at a time.  Neighbouring lanes read neighbouring floats.
 template <int HD>
 __global__ __launch_bounds__(256) void k_attn_merge(AttnArgs a) {
   constexpr int PSTR = HD + 2;
   int unit = blockIdx.x, z = unit / a.H, h = unit % a.H;
   int reqi = z / a.nqg, qg = z % a.nqg;
-  int qn = blockIdx.y * 4 + (threadIdx.x >> 6), t = threadIdx.x & 63;
-  int qa = qg * 16 + qn, r = reqi * a.A + qa;
-  if (qa >= a.A) return;
+  int qn = threadIdx.x & 15, dg = (threadIdx.x >> 4) & 3, dim = blockIdx.y * 16 + (threadIdx.x >> 4);
+  int qa = qg * 16 + qn, r = reqi * a.A + min(qa, a.A - 1);
   int fl = a.rt.flags[r];
-  const float *pb = a.part + ((size_t)unit * a.nsplit * 16 + qn) * PSTR;
-  const size_t sstr = (size_t)16 * PSTR;
-  // nsplit <= 256: lane t covers splits t, t+64, t+128, t+192
-  float mloc[4], lloc[4], M = -INFINITY;
+  const float *pb = a.part + (size_t)unit * a.nsplit * (PSTR * 16) + qn;
+  const size_t sstr = (size_t)PSTR * 16;
+  // lane group dg takes splits dg, dg + 4, ...  (nsplit <= 256: at most 64 each, 16 per pass)
+  float M = -INFINITY, lg = 0.f;
+  for (int s0 = dg; s0 < a.nsplit; s0 += 64) {
+    float mv[16], lv[16];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    int sp = t + 64 * i;
-    bool in = sp < a.nsplit;
-    mloc[i] = in ? pb[sp * sstr] : -INFINITY;
-    lloc[i] = in ? pb[sp * sstr + 1] : 0.f;
-  }
-  if (!(fl & ROW_VALID)) return;
+    for (int u = 0; u < 16; ++u) {
+      int sp = s0 + 4 * u;
+      bool in = sp < a.nsplit;
+      mv[u] = in ? pb[sp * sstr] : -INFINITY;
+      lv[u] = in ? pb[sp * sstr + 16] : 0.f;
+    }
+    float Mn = M;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) M = fmaxf(M, mloc[i]);
-  for (int o = 32; o > 0; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
-  float floc[4], lg = 0.f;
+    for (int u = 0; u < 16; ++u) Mn = fmaxf(Mn, mv[u]);
+    if (Mn != -INFINITY) {
+      lg *= exp2f(M - Mn);        // M == -inf: lg is 0 and stays 0
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    floc[i] = mloc[i] == -INFINITY ? 0.f : exp2f(mloc[i] - M);
-    lg += floc[i] * lloc[i];
-  }
-  for (int o = 32; o > 0; o >>= 1) lg += __shfl_xor(lg, o);
-  float o0 = 0.f, o1 = 0.f;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    for (int s0 = 64 * i; s0 < min(a.nsplit, 64 * (i + 1)); s0 += 8) {
-      float v0[8], v1[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        int sp = min(s0 + u, a.nsplit - 1);
-        v0[u] = t < HD ? pb[sp * sstr + 2 + t] : 0.f;
-        v1[u] = t + 64 < HD ? pb[sp * sstr + 2 + t + 64] : 0.f;
-      }
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        int sp = s0 + u;
-        float f = __shfl(floc[i], sp & 63);
-        if (sp >= a.nsplit) f = 0.f;
-        o0 += f * v0[u];
-        o1 += f * v1[u];
-      }
+      for (int u = 0; u < 16; ++u) lg += mv[u] == -INFINITY ? 0.f : exp2f(mv[u] - Mn) * lv[u];
+      M = Mn;
     }
   }
-  float inv = 1.f / lg;
-  if (t < HD) {
-    bf16_t hi = f32_to_bf16(o0 * inv);
-    size_t off = act_off(r, h * HD + t, a.d);
-    a.out[off] = hi;
-    if (a.out_lo) a.out_lo[off] = f32_to_bf16(bf16_residual(o0 * inv, hi));
+#pragma unroll
+  for (int off = 16; off <= 32; off <<= 1) {     // combine the 4 lane groups of the query
+    float Mo = __shfl_xor(M, off), lo = __shfl_xor(lg, off);
+    float Mn = fmaxf(M, Mo);
+    lg = (M == -INFINITY ? 0.f : lg * exp2f(M - Mn)) + (Mo == -INFINITY ? 0.f : lo * exp2f(Mo - Mn));
+    M = Mn;
   }
-  if (t + 64 < HD) {
-    bf16_t hi = f32_to_bf16(o1 * inv);
-    size_t off = act_off(r, h * HD + t + 64, a.d);
-    a.out[off] = hi;
-    if (a.out_lo) a.out_lo[off] = f32_to_bf16(bf16_residual(o1 * inv, hi));
+  float o = 0.f;
+  for (int s0 = 0; s0 < a.nsplit; s0 += 16) {
+    float mv[16], ov[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      size_t sp = min(s0 + u, a.nsplit - 1);
+      mv[u] = pb[sp * sstr];
+      ov[u] = pb[sp * sstr + (2 + dim) * 16];
+    }
+#pragma unroll
+    for (int u = 0; u < 16; ++u)
+      o += (s0 + u < a.nsplit && mv[u] != -INFINITY) ? exp2f(mv[u] - M) * ov[u] : 0.f;
   }
+  if (qa >= a.A || !(fl & ROW_VALID)) return;
+  float y = o / lg;
+  bf16_t hi = f32_to_bf16(y);
+  size_t off = act_off(r, h * HD + dim, a.d);
+  a.out[off] = hi;
+  if (a.out_lo) a.out_lo[off] = f32_to_bf16(bf16_residual(y, hi));
 }
 
 static int pick_splits(pd_ctx *c, int units, int nblk) {
@@ -340,7 +333,7 @@ int mfma_attention(pd_ctx *c, const LayerPtrs &lw, int A, int nreq, int req0, in
     else if (c->opt_db) hipLaunchKernelGGL((k_attn_mfma<HDV, false, true>), grid, dim3(256), 0, s, a);       \
     else hipLaunchKernelGGL((k_attn_mfma<HDV, false, false>), grid, dim3(256), 0, s, a);                     \
     if (a.nsplit > 1)                                                                       \
-      hipLaunchKernelGGL(k_attn_merge<HDV>, dim3(units, 4), dim3(256), 0, s, a);            \
+      hipLaunchKernelGGL(k_attn_merge<HDV>, dim3(units, HDV / 16), dim3(256), 0, s, a);            \
   } while (0)
   switch (g.head_dim) {
     case 32: PD_ATTN(32); break;

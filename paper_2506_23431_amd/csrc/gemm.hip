@@ -84,7 +84,8 @@ __device__ __forceinline__ float block_sum256(float v, float *sh) {
 template <int NG>     // 8-value granules per thread: d <= 2048 * NG
 __global__ __launch_bounds__(256) void k_norm_bf16(bf16_t *xn, bf16_t *xn_lo, const float *x, const float *g,
                                                    const float *b, int d, int kind, float eps,
-                                                   const int32_t *flags, int R) {
+                                                   const int32_t *flags, int R, float *xw,
+                                                   const float *ypart, int nparts, size_t part_stride) {
   __shared__ float sh[4];
   int r = blockIdx.x;
   int fl = r < R ? flags[r] : 0;
@@ -99,6 +100,12 @@ __global__ __launch_bounds__(256) void k_norm_bf16(bf16_t *xn, bf16_t *xn_lo, co
       float4 t = in ? *(const float4 *)(xr + c + 4 * h) : make_float4(0.f, 0.f, 0.f, 0.f);
       float4 tg = in ? *(const float4 *)(g + c + 4 * h) : make_float4(0.f, 0.f, 0.f, 0.f);
       float4 tb = (in && kind == 0 && b) ? *(const float4 *)(b + c + 4 * h) : make_float4(0.f, 0.f, 0.f, 0.f);
+      for (int pp = 0; pp < nparts; ++pp) {      // pending split-K slices of the last projection
+        float4 y = in ? *(const float4 *)(ypart + pp * part_stride + (size_t)r * d + c + 4 * h)
+                      : make_float4(0.f, 0.f, 0.f, 0.f);
+        t.x += y.x; t.y += y.y; t.z += y.z; t.w += y.w;
+      }
+      if (nparts > 0 && in && r < R) *(float4 *)(xw + (size_t)r * d + c + 4 * h) = t;
       v[i][4 * h] = t.x; v[i][4 * h + 1] = t.y; v[i][4 * h + 2] = t.z; v[i][4 * h + 3] = t.w;
       gv[i][4 * h] = tg.x; gv[i][4 * h + 1] = tg.y; gv[i][4 * h + 2] = tg.z; gv[i][4 * h + 3] = tg.w;
       bv[i][4 * h] = tb.x; bv[i][4 * h + 1] = tb.y; bv[i][4 * h + 2] = tb.z; bv[i][4 * h + 3] = tb.w;
@@ -146,12 +153,14 @@ int mfma_norm(pd_ctx *c, const float *gain, const float *bias, int R, hipStream_
   PD_REQUIRE(d <= 2048 * 4, PD_EINVAL, "d_model %d too large for the norm kernel", d);
 #define PD_NORM(V)                                                                               \
   hipLaunchKernelGGL(k_norm_bf16<V>, dim3(rows), dim3(256), 0, s, xn, mfma_lo(c, xn, d), c->x, gain, bias, d, \
-                     g.norm_kind, g.norm_eps, c->rows.flags, R)
+                     g.norm_kind, g.norm_eps, c->rows.flags, R, c->x, c->ypart, c->pend_parts,         \
+                     (size_t)c->R_pad * d)
   if (d <= 2048) PD_NORM(1);
   else if (d <= 4096) PD_NORM(2);
   else PD_NORM(4);
 #undef PD_NORM
   PD_CHECK_HIP(hipGetLastError());
+  c->pend_parts = 0;
   return PD_OK;
 }
 
@@ -176,7 +185,15 @@ __global__ __launch_bounds__(64 * NW_N * NW_K) void k_gemm(GemmArgs a) {
   int m = lane & 15, g = lane >> 4;
   bool active = nt < a.n_tiles;
   int KT = a.K >> 5;
-  int kt0 = (int)((long)wk * KT / NW_K), kt1 = (int)((long)(wk + 1) * KT / NW_K);
+  // waves along K: NW_K in this block times gridDim.y blocks (EPI_RESID only)
+  int gk = blockIdx.y * NW_K + wk, nk = gridDim.y * NW_K;
+  int kt0 = (int)((long)gk * KT / nk), kt1 = (int)((long)(gk + 1) * KT / nk);
+  // row data of the KV-append epilogue, requested now so that it arrives with the weights
+  int4 kvi[(EPI == EPI_QKV || EPI == EPI_QKV_ROPE) ? RT : 1];
+  if (EPI == EPI_QKV || EPI == EPI_QKV_ROPE) {
+#pragma unroll
+    for (int i = 0; i < RT; ++i) kvi[i] = a.rt.kvinfo[i * 16 + m];
+  }
   floatx4 acc[RT];
 #pragma unroll
   for (int i = 0; i < RT; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -232,15 +249,12 @@ __global__ __launch_bounds__(64 * NW_N * NW_K) void k_gemm(GemmArgs a) {
   // ---- epilogues: lane holds y[r][n0 + j], r = i*16 + m, n0 = nt*16 + 4g, j = 0..3
   int n0 = nt * 16 + 4 * g;
   if (EPI == EPI_RESID) {
+    // split-K slice blockIdx.y of y; the following norm kernel adds the slices to x
+    float *yp = a.x + (size_t)blockIdx.y * a.part_stride;
 #pragma unroll
     for (int i = 0; i < RT; ++i) {
       int r = i * 16 + m;
-      if (r < a.R) {
-        float4 *p = (float4 *)(a.x + (size_t)r * a.ld + n0);
-        float4 v = *p;
-        v.x += acc[i][0]; v.y += acc[i][1]; v.z += acc[i][2]; v.w += acc[i][3];
-        *p = v;
-      }
+      *(float4 *)(yp + (size_t)r * a.ld + n0) = make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
     }
   } else if (EPI == EPI_GELU) {
 #pragma unroll
@@ -274,14 +288,14 @@ __global__ __launch_bounds__(64 * NW_N * NW_K) void k_gemm(GemmArgs a) {
 #pragma unroll
     for (int i = 0; i < RT; ++i) {
       int r = i * 16 + m;
-      bool valid = r < a.R && (a.rt.flags[r] & ROW_VALID);
+      bool valid = r < a.R && (kvi[i].x & ROW_VALID);
       float y[4];
       int dim0;                                  // head-dim index of y[0]; y[j] is dim0 + j
       if (EPI == EPI_QKV_ROPE && sec < 2) {
         int th = (nl % a.hd) >> 4;
         int jj = th * 8 + 4 * (g & 1);           // rotation pair index of y[0]
         dim0 = jj + (g >= 2 ? half : 0);
-        const float *cs = a.rope_cs + ((size_t)(valid ? a.rt.pos[r] : 0) * half + jj) * 2;
+        const float *cs = a.rope_cs + ((size_t)(valid ? kvi[i].w : 0) * half + jj) * 2;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           float mine = acc[i][j];
@@ -299,8 +313,8 @@ __global__ __launch_bounds__(64 * NW_N * NW_K) void k_gemm(GemmArgs a) {
       if (sec == 0) {
         store4_split(a.out_bf, a.out_lo, act_off(r, h * a.hd + dim0, a.d), y);
       } else {
-        size_t head_base = ((size_t)a.rt.req[r] * a.H + h) * a.kv_cap * a.hd;
-        int slot = a.rt.slot[r];
+        size_t head_base = ((size_t)kvi[i].y * a.H + h) * a.kv_cap * a.hd;
+        int slot = kvi[i].z;
         if (sec == 1) {
           *(uint2 *)(a.kc + head_base + k_cache_off(slot, dim0, a.hd)) =
               make_uint2(pack2(y[0], y[1]), pack2(y[2], y[3]));
@@ -384,22 +398,32 @@ int mfma_lm_reduce(pd_ctx *c, int n_tiles, int R, hipStream_t s) {
 template <int RT, int EPI, bool SPLIT>
 static int launch_gemm_rt(const GemmArgs &a, hipStream_t s) {
   int KT = a.K / 32;
-  int nwk = 1;
   constexpr int SHARE = SPLIT && RT == 1 ? 8 : 16;   // fragments requested at once by a wave
-  while (nwk < 16 && KT > SHARE * nwk) nwk *= 2;
-  if (RT == 8 && nwk > 8) nwk = 8;
+  int waves_k = (KT + SHARE - 1) / SHARE;            // waves along K so that a share is one request
+  int nwk = 1, ks = 1;
+  const int max_nwk = RT == 8 ? 8 : 16;
+  if (EPI == EPI_RESID) {
+    // the split-K slices are summed by the next norm kernel, so K may also be split over
+    // blocks: enough blocks to occupy every compute unit, at most a.max_parts slices
+    while (ks < a.max_parts && (a.n_tiles * ks < 256 || waves_k > max_nwk * ks)) ks *= 2;
+    waves_k = (waves_k + ks - 1) / ks;
+  }
+  while (nwk < max_nwk && nwk < waves_k) nwk *= 2;
   // plenty of column tiles: fewer, longer-lived waves are enough to keep HBM busy
   if ((long)a.n_tiles * nwk > 16384 && nwk > 1) nwk /= 2;
+  dim3 grid(1, ks);
   switch (nwk) {
-    case 1: hipLaunchKernelGGL((k_gemm<RT, 4, 1, EPI, SPLIT>), dim3((a.n_tiles + 3) / 4), dim3(256), 0, s, a); break;
-    case 2: hipLaunchKernelGGL((k_gemm<RT, 2, 2, EPI, SPLIT>), dim3((a.n_tiles + 1) / 2), dim3(256), 0, s, a); break;
-    case 4: hipLaunchKernelGGL((k_gemm<RT, 1, 4, EPI, SPLIT>), dim3(a.n_tiles), dim3(256), 0, s, a); break;
-    case 8: hipLaunchKernelGGL((k_gemm<RT, 1, 8, EPI, SPLIT>), dim3(a.n_tiles), dim3(512), 0, s, a); break;
+    case 1: grid.x = (a.n_tiles + 3) / 4; hipLaunchKernelGGL((k_gemm<RT, 4, 1, EPI, SPLIT>), grid, dim3(256), 0, s, a); break;
+    case 2: grid.x = (a.n_tiles + 1) / 2; hipLaunchKernelGGL((k_gemm<RT, 2, 2, EPI, SPLIT>), grid, dim3(256), 0, s, a); break;
+    case 4: grid.x = a.n_tiles; hipLaunchKernelGGL((k_gemm<RT, 1, 4, EPI, SPLIT>), grid, dim3(256), 0, s, a); break;
+    case 8: grid.x = a.n_tiles; hipLaunchKernelGGL((k_gemm<RT, 1, 8, EPI, SPLIT>), grid, dim3(512), 0, s, a); break;
     default:
-      if (RT < 8) hipLaunchKernelGGL((k_gemm<RT, 1, (RT < 8 ? 16 : 8), EPI, SPLIT>), dim3(a.n_tiles), dim3(1024), 0, s, a);
+      grid.x = a.n_tiles;
+      if (RT < 8) hipLaunchKernelGGL((k_gemm<RT, 1, (RT < 8 ? 16 : 8), EPI, SPLIT>), grid, dim3(1024), 0, s, a);
       break;
   }
   PD_CHECK_HIP(hipGetLastError());
+  if (EPI == EPI_RESID && a.parts_out) *a.parts_out = ks;
   return PD_OK;
 }
 

@@ -20,7 +20,8 @@ int mfma_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_overri
   if ((rc = mfma_gemm(g.pos_kind == 1 ? EPI_QKV_ROPE : EPI_QKV, a, R, s))) return rc;
   if ((rc = mfma_attention(c, lw, A, nreq, req0, kv_override, s))) return rc;
   // output projection + residual
-  a.W = lw.p_wo; a.xn = (const bf16_t *)c->att; a.xn_lo = mfma_lo(c, c->att, d); a.K = d; a.n_tiles = d / 16; a.x = c->x; a.ld = d;
+  a.W = lw.p_wo; a.xn = (const bf16_t *)c->att; a.xn_lo = mfma_lo(c, c->att, d); a.K = d; a.n_tiles = d / 16; a.x = c->ypart; a.ld = d;
+  a.part_stride = (size_t)c->R_pad * d; a.max_parts = 4; a.parts_out = &c->pend_parts;
   if ((rc = mfma_gemm(EPI_RESID, a, R, s))) return rc;
   if ((rc = mfma_norm(c, lw.n2g, lw.n2b, R, s))) return rc;
   // FFN
@@ -34,7 +35,7 @@ int mfma_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_overri
     rc = mfma_gemm(EPI_GELU, a, R, s);
   }
   if (rc) return rc;
-  a.W = lw.p_w2; a.xn = (const bf16_t *)c->hb; a.xn_lo = mfma_lo(c, c->hb, ff); a.K = ff; a.n_tiles = d / 16; a.x = c->x; a.ld = d;
+  a.W = lw.p_w2; a.xn = (const bf16_t *)c->hb; a.xn_lo = mfma_lo(c, c->hb, ff); a.K = ff; a.n_tiles = d / 16; a.x = c->ypart; a.ld = d;
   return mfma_gemm(EPI_RESID, a, R, s);
 }
 

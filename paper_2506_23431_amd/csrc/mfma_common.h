@@ -80,11 +80,12 @@ enum { EPI_QKV = 0, EPI_QKV_ROPE = 1, EPI_RESID = 2, EPI_GELU = 3, EPI_SWIGLU = 
 
 struct GemmArgs {
   const bf16_t *W;       // packed
-  const bf16_t *xn;      // [16*RT][K] bf16: activations (high part)
+  const bf16_t *xn;      // [16*RT][K] bf16, fragment-major: activations (high part)
   const bf16_t *xn_lo;   // same shape: bf16(x - high part), or NULL to use the high part only
   int K, n_tiles, R;
   // epilogue
-  float *x;              // EPI_RESID: residual stream [R][ld], updated in place
+  float *x;              // EPI_RESID: split-K slices of y, [slices][part_stride], row-major [rows][ld]
+  size_t part_stride; int max_parts; int *parts_out;   // EPI_RESID: slice stride, limit, slices written
   bf16_t *out_bf;        // EPI_GELU / EPI_SWIGLU: [rows][ld]; EPI_QKV*: q [rows][d]
   bf16_t *out_lo;        // low parts of out_bf (written when not NULL)
   int ld;

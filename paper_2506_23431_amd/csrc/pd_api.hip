@@ -101,6 +101,7 @@ static size_t carve(const pd_config *g, char *base, pd_ctx *c) {
   x->logits = cv.take<float>(Rp * (size_t)x->vocab_pad);
   x->scores = x->impl == 0 ? cv.take<float>((size_t)x->R_cap * H * x->kv_cap) : nullptr;
   x->att_part = cv.take<float>((size_t)4096 * 16 * (hd + 2));
+  x->ypart = cv.take<float>((size_t)4 * Rp * d);
   x->lm_parts = (x->vocab_pad / 16);
   x->lm_part_val = cv.take<float>((size_t)x->lm_parts * Rp);
   x->lm_part_idx = cv.take<int32_t>((size_t)x->lm_parts * Rp);
@@ -110,7 +111,7 @@ static size_t carve(const pd_config *g, char *base, pd_ctx *c) {
   RowTables &rt = x->rows;
   rt.req = cv.take<int32_t>(Rp); rt.sub = cv.take<int32_t>(Rp); rt.tok = cv.take<int32_t>(Rp);
   rt.pos = cv.take<int32_t>(Rp); rt.slot = cv.take<int32_t>(Rp); rt.lim = cv.take<int32_t>(Rp);
-  rt.flags = cv.take<int32_t>(Rp); rt.qinfo = cv.take<int4>(Rp);
+  rt.flags = cv.take<int32_t>(Rp); rt.qinfo = cv.take<int4>(Rp); rt.kvinfo = cv.take<int4>(Rp);
   SchedState &st = x->sch;
   st.step = cv.take<int32_t>(B); st.k_open = cv.take<int32_t>(B);
   st.n_tok = cv.take<int32_t>((size_t)B * S); st.n_fed = cv.take<int32_t>((size_t)B * S);
@@ -264,6 +265,7 @@ static int run_layers(pd_ctx *c, int R, int A, int nreq, int req0, int kv_overri
                       hipStream_t s) {
   int rc;
   if ((rc = launch_embed(c, R, s))) return rc;
+  c->pend_parts = 0;
   for (int l = 0; l < c->cfg.n_layer; ++l) {
     rc = c->impl == 1 ? mfma_layer(c, l, R, A, nreq, req0, kv_override, s)
                       : simple_layer(c, l, R, A, nreq, req0, kv_override, s);

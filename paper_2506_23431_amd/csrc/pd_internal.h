@@ -66,6 +66,7 @@ struct RowTables {
   int32_t *lim;    // [R] keys with index < lim are visible unconditionally
   int32_t *flags;  // [R]
   int4 *qinfo;     // [R] {flags, sub, lim, req} again, packed so that one load fetches them
+  int4 *kvinfo;    // [R] {flags, req, slot, pos} packed likewise (KV append epilogue)
 };
 
 // schedule state of Algorithm 1, one instance per request, all on the device
@@ -114,6 +115,8 @@ struct pd_ctx {
   float *logits;            // [R_cap][vocab] internal logits (simple path / parity output)
   float *scores;            // simple path attention scratch
   float *att_part;          // split-K partials of the attention kernel
+  float *ypart;             // [4][R_pad][d] split-K partial sums of the O / FFN2 projections
+  int pend_parts;           // slices of ypart the next norm kernel has to add to x
   float *lm_part_val; int32_t *lm_part_idx; int lm_parts;
   int32_t *row_argmax;      // [R_cap] argmax of each row's logits
   float *rope_cs;           // [max_pos][hd/2][2] cos, sin

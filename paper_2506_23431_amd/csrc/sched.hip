@@ -16,7 +16,7 @@ __global__ void k_reset_state(SchedState st, RowTables rt, int B, int S, int L, 
     st.n_tok[i] = 0; st.n_fed[i] = 0; st.fin[i] = 0; st.step_tok[i] = -1; st.force[i] = -1;
     st.row_of[i] = -1;
   }
-  if (i < R_cap) { rt.flags[i] = 0; rt.qinfo[i] = make_int4(0, -1, 0, 0); }
+  if (i < R_cap) { rt.flags[i] = 0; rt.qinfo[i] = make_int4(0, -1, 0, 0); rt.kvinfo[i] = make_int4(0, 0, 0, 0); }
   if (i == 0) *st.all_done = 0;
 }
 
@@ -40,7 +40,7 @@ __global__ void k_tick(SchedState st, RowTables rt, int S, int dt, int M, int L,
                        int time_max, int bos, int gen_cap) {
   int b = blockIdx.x;
   if (threadIdx.x != 0) return;
-  for (int a = 0; a < A; ++a) { rt.flags[b * A + a] = 0; rt.qinfo[b * A + a] = make_int4(0, -1, 0, b); }
+  for (int a = 0; a < A; ++a) { rt.flags[b * A + a] = 0; rt.qinfo[b * A + a] = make_int4(0, -1, 0, b); rt.kvinfo[b * A + a] = make_int4(0, b, 0, 0); }
   for (int i = 0; i < S; ++i) { st.row_of[b * S + i] = -1; st.step_tok[b * S + i] = -1; }
   st.n_rows[b] = 0;
   if (st.done[b]) return;
@@ -70,6 +70,7 @@ __global__ void k_tick(SchedState st, RowTables rt, int S, int dt, int M, int L,
       rt.lim[r] = L;
       rt.flags[r] = ROW_VALID | (st.fin[b * S + i] ? 0 : ROW_PRODUCE);
       rt.qinfo[r] = make_int4(rt.flags[r], i + 1, L, b);
+      rt.kvinfo[r] = make_int4(rt.flags[r], b, L + ng + a, L + (t - 1) + i);
       st.gen_sub[(size_t)b * gen_cap + ng + a] = i + 1;
       st.n_fed[b * S + i] = nt;
       st.row_of[b * S + i] = r;
@@ -99,9 +100,11 @@ __global__ void k_prefill_rows(RowTables rt, const int32_t *ctx_tok, int b, int 
     rt.req[r] = b; rt.sub[r] = 0; rt.tok[r] = ctx_tok[(size_t)b * L + p]; rt.pos[r] = p;
     rt.slot[r] = p; rt.lim[r] = p + 1; rt.flags[r] = ROW_VALID;
     rt.qinfo[r] = make_int4(ROW_VALID, 0, p + 1, b);
+    rt.kvinfo[r] = make_int4(ROW_VALID, b, p, p);
   } else {
     rt.flags[r] = 0;
     rt.qinfo[r] = make_int4(0, -1, 0, b);
+    rt.kvinfo[r] = make_int4(0, b, 0, 0);
   }
 }
 
