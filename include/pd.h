@@ -13,8 +13,10 @@
  *     device memory: weights and the workspace are allocated by the caller (for
  *     example as PyTorch tensors) and must outlive the pd_ctx.
  *   - All matrices are row-major [out][in].  dtype 0: fp32 weights, fp32 KV cache.
- *     dtype 1: bf16 weights (raw 16-bit patterns), bf16 KV cache, fp32 accumulation
- *     and fp32 residual stream.  Norm gains/biases are always fp32.
+ *     dtype 1: bf16 weights (raw 16-bit patterns), 16-bit KV cache (IEEE half: the same
+ *     two bytes per element as bf16 with an 11-bit significand; values beyond +-65504
+ *     saturate), fp32 accumulation and fp32 residual stream.  Norm gains/biases are
+ *     always fp32.
  *   - Every function returns PD_OK (0) or a negative PD_E* code; on error no output
  *     argument is written and pd_last_error() describes the failure.  Nothing
  *     throws or aborts across this boundary.
@@ -49,7 +51,7 @@ typedef struct {
   int32_t norm_kind;   /* 0: LayerNorm(gain, bias);  1: RMSNorm(gain)                      */
   int32_t pos_kind;    /* 0: learned absolute table [max_pos][d];  1: rotary, rotate-half  */
   float   rope_base, norm_eps;
-  int32_t dtype;       /* 0: fp32;  1: bf16 weights + bf16 KV, fp32 accumulate             */
+  int32_t dtype;       /* 0: fp32;  1: bf16 weights + 16-bit (half) KV, fp32 accumulate     */
   int32_t bos_id, eos_id;   /* eos_id < 0 disables end-of-sequence termination             */
   int32_t max_batch, max_ctx, max_sub, max_sub_tokens;   /* capacity (workspace sizing)    */
   int32_t max_pos;     /* rows of the learned position table (ignored for rotary)          */

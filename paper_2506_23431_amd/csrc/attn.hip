@@ -19,8 +19,8 @@
 #include <algorithm>
 
 struct AttnArgs {
-  const bf16_t *q, *q_lo;   // [rows][d] high / low parts (q_lo NULL: high part only)
-  const bf16_t *kc, *vc;    // packed caches of this layer
+  const f16_t *q, *q_lo;    // [rows][d] fp16 high / low parts (q_lo NULL: high part only)
+  const f16_t *kc, *vc;     // packed fp16 caches of this layer
   bf16_t *out, *out_lo;     // [rows][d] high / low parts (out_lo NULL: high part only)
   RowTables rt;
   const int32_t *kv_len, *gen_sub;
@@ -106,10 +106,10 @@ __global__ __launch_bounds__(256, DB ? 1 : 3) void k_attn_mfma(AttnArgs a) {
     for (int t = 0; t < 2; ++t) {
       s[t] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int c = 0; c < NC; ++c) s[t] = mfma16(blk.k[t][c], qf[c], s[t]);
+      for (int c = 0; c < NC; ++c) s[t] = mfma16h(blk.k[t][c], qf[c], s[t]);
       if (SPLIT) {
 #pragma unroll
-        for (int c = 0; c < NC; ++c) s[t] = mfma16(blk.k[t][c], ql[c], s[t]);
+        for (int c = 0; c < NC; ++c) s[t] = mfma16h(blk.k[t][c], ql[c], s[t]);
       }
     }
     // lane (n, g), tile t, register j  <->  key kbc*32 + 8g + 4t + j
@@ -144,14 +144,14 @@ __global__ __launch_bounds__(256, DB ? 1 : 3) void k_attn_mfma(AttnArgs a) {
     Frag pf, pl;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      pf.h[e] = f32_to_bf16(p[e]);
-      if (SPLIT) pl.h[e] = f32_to_bf16(bf16_residual(p[e], pf.h[e]));
+      pf.hh[e] = (f16_t)p[e];
+      if (SPLIT) pl.hh[e] = (f16_t)(p[e] - (float)pf.hh[e]);
     }
 #pragma unroll
     for (int i = 0; i < NHB; ++i) {
       o_acc[i] *= alpha;
-      o_acc[i] = mfma16(blk.v[i], pf, o_acc[i]);
-      if (SPLIT) o_acc[i] = mfma16(blk.v[i], pl, o_acc[i]);
+      o_acc[i] = mfma16h(blk.v[i], pf, o_acc[i]);
+      if (SPLIT) o_acc[i] = mfma16h(blk.v[i], pl, o_acc[i]);
     }
   };
 
@@ -303,8 +303,8 @@ int mfma_attention(pd_ctx *c, const LayerPtrs &lw, int A, int nreq, int req0, in
                    hipStream_t s) {
   const pd_config &g = c->cfg;
   AttnArgs a;
-  a.q = (const bf16_t *)c->q; a.q_lo = mfma_lo(c, c->q, g.d_model);
-  a.out_lo = mfma_lo(c, c->att, g.d_model); a.kc = (const bf16_t *)lw.kc; a.vc = (const bf16_t *)lw.vc;
+  a.q = (const f16_t *)c->q; a.q_lo = (const f16_t *)mfma_lo(c, c->q, g.d_model);
+  a.out_lo = mfma_lo(c, c->att, g.d_model); a.kc = (const f16_t *)lw.kc; a.vc = (const f16_t *)lw.vc;
   a.out = (bf16_t *)c->att; a.rt = c->rows; a.kv_len = c->sch.kv_len; a.gen_sub = c->sch.gen_sub;
   a.kv_override = kv_override; a.part = c->att_part;
   a.d = g.d_model; a.H = g.n_head; a.kv_cap = c->kv_cap; a.gen_cap = c->gen_cap; a.L = c->L;

@@ -311,17 +311,16 @@ __global__ __launch_bounds__(64 * NW_N * NW_K) void k_gemm(GemmArgs a) {
       }
       if (!valid) continue;
       if (sec == 0) {
-        store4_split(a.out_bf, a.out_lo, act_off(r, h * a.hd + dim0, a.d), y);
+        store4_split_h((f16_t *)a.out_bf, (f16_t *)a.out_lo, act_off(r, h * a.hd + dim0, a.d), y);
       } else {
         size_t head_base = ((size_t)kvi[i].y * a.H + h) * a.kv_cap * a.hd;
         int slot = kvi[i].z;
         if (sec == 1) {
-          *(uint2 *)(a.kc + head_base + k_cache_off(slot, dim0, a.hd)) =
-              make_uint2(pack2(y[0], y[1]), pack2(y[2], y[3]));
+          store4_split_h(a.kc, nullptr, head_base + k_cache_off(slot, dim0, a.hd), y);
         } else {
 #pragma unroll
           for (int j = 0; j < 4; ++j)
-            a.vc[head_base + v_cache_off(slot, dim0 + j, a.hd)] = f32_to_bf16(y[j]);
+            a.vc[head_base + v_cache_off(slot, dim0 + j, a.hd)] = f32_to_f16_sat(y[j]);
         }
       }
     }

@@ -2,7 +2,8 @@
 //
 // Design rule of this file: every large operand that is streamed from HBM once per
 // step (weights, key cache, value cache) is stored in HBM in the exact order in
-// which the 16x16x32 bf16 MFMA instruction wants it in registers.  A "fragment" is
+// which the 16x16x32 MFMA instruction (bf16 for weights x activations, fp16 for the
+// attention products) wants it in registers.  A "fragment" is
 // the A operand of one such instruction: 16 rows x 32 contraction values = 1 KiB,
 // lane l (0..63) holding 8 consecutive contraction values (16 bytes) of row l%16,
 // contraction group l/16.  A fragment is stored as 64 consecutive 16-byte granules
@@ -24,16 +25,23 @@
 #include "pd_internal.h"
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 union Frag {
   uint4 u;
   bf16x8 v;
   bf16_t h[8];
+  f16x8 hv;       // fp16 view: KV cache, queries and probabilities of the attention kernel
+  f16_t hh[8];
 };
 
 __device__ __forceinline__ floatx4 mfma16(const Frag &a, const Frag &b, floatx4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ floatx4 mfma16h(const Frag &a, const Frag &b, floatx4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(a.hv, b.hv, c, 0, 0, 0);
 }
 
 __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
@@ -60,6 +68,18 @@ __device__ __forceinline__ void store4_split(bf16_t *hi, bf16_t *lo, size_t off,
   if (lo)
     *(uint2 *)(lo + off) = make_uint2(pack2(bf16_residual(y[0], h0), bf16_residual(y[1], h1)),
                                       pack2(bf16_residual(y[2], h2), bf16_residual(y[3], h3)));
+}
+
+// the same for fp16 pairs (queries: they meet the fp16 key cache in the matrix core)
+__device__ __forceinline__ void store4_split_h(f16_t *hi, f16_t *lo, size_t off, const float y[4]) {
+  union { f16_t h[4]; uint2 u; } a, b;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    a.h[j] = f32_to_f16_sat(y[j]);
+    b.h[j] = (f16_t)(y[j] - (float)a.h[j]);
+  }
+  *(uint2 *)(hi + off) = a.u;
+  if (lo) *(uint2 *)(lo + off) = b.u;
 }
 
 // element offsets inside the packed caches (per request and head)
@@ -89,7 +109,7 @@ struct GemmArgs {
   bf16_t *out_bf;        // EPI_GELU / EPI_SWIGLU: [rows][ld]; EPI_QKV*: q [rows][d]
   bf16_t *out_lo;        // low parts of out_bf (written when not NULL)
   int ld;
-  bf16_t *kc, *vc;       // EPI_QKV*: caches of this layer
+  f16_t *kc, *vc;        // EPI_QKV*: caches of this layer (fp16)
   RowTables rt;
   const float *rope_cs;
   int d, H, hd, kv_cap;

@@ -45,7 +45,16 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
   return (bf16_t)(u >> 16);
 }
 
+// fp16 bit patterns for the KV cache of dtype 1: same two bytes per element as bf16, 11-bit
+// significand.  Values beyond the fp16 range saturate instead of becoming infinite.
+typedef _Float16 f16_t;
+__device__ __forceinline__ f16_t f32_to_f16_sat(float f) {
+  return (f16_t)fminf(fmaxf(f, -65504.f), 65504.f);
+}
+
 __device__ __forceinline__ float ld_f32(const float *p, size_t i) { return p[i]; }
+__device__ __forceinline__ float ld_f32(const f16_t *p, size_t i) { return (float)p[i]; }
+__device__ __forceinline__ void st_f32(f16_t *p, size_t i, float v) { p[i] = f32_to_f16_sat(v); }
 __device__ __forceinline__ float ld_f32(const bf16_t *p, size_t i) { return bf16_to_f32(p[i]); }
 __device__ __forceinline__ void st_f32(float *p, size_t i, float v) { p[i] = v; }
 __device__ __forceinline__ void st_f32(bf16_t *p, size_t i, float v) { p[i] = f32_to_bf16(v); }

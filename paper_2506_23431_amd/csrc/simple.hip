@@ -251,10 +251,10 @@ int simple_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_over
                        c->sch.kv_len, c->sch.gen_sub, kv_override, d, H, hd, c->kv_cap, c->gen_cap,
                        c->L, scale);
   } else {
-    hipLaunchKernelGGL(k_qkv_post<bf16_t>, dim3(R), dim3(256), 0, s, c->qkv32, (bf16_t *)lw.kc,
-                       (bf16_t *)lw.vc, c->rows, cs, d, H, hd, c->kv_cap);
-    hipLaunchKernelGGL(k_attn<bf16_t>, dim3(R, H), dim3(256), shm, s, att, c->qkv32,
-                       (const bf16_t *)lw.kc, (const bf16_t *)lw.vc, c->scores, c->rows,
+    hipLaunchKernelGGL(k_qkv_post<f16_t>, dim3(R), dim3(256), 0, s, c->qkv32, (f16_t *)lw.kc,
+                       (f16_t *)lw.vc, c->rows, cs, d, H, hd, c->kv_cap);
+    hipLaunchKernelGGL(k_attn<f16_t>, dim3(R, H), dim3(256), shm, s, att, c->qkv32,
+                       (const f16_t *)lw.kc, (const f16_t *)lw.vc, c->scores, c->rows,
                        c->sch.kv_len, c->sch.gen_sub, kv_override, d, H, hd, c->kv_cap, c->gen_cap,
                        c->L, scale);
   }

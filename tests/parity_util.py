@@ -12,16 +12,37 @@ TOL = {0: 1e-4, 1: 2e-2}      # max-abs logit tolerance: fp32 / bf16 (north-star
 MARGIN = 0.05                 # greedy tokens must agree where the oracle's top-2 margin exceeds this
 
 
-def oracle_run(cfg, weights, ctx, force=None, steps=None, context_kv=None):
-    """Oracle traces per request. force: int array [steps][B][S] or None."""
+def oracle_run(cfg, weights, ctx, force=None, steps=None, context_kv=None, log=None):
+    """Oracle traces per request. force: int array [steps][B][S] or None.
+    log: optional callable; gets a progress line at least every ~20 s of oracle work."""
+    import time
+    from oracle import controller
     model = OracleModel(cfg, weights)
     outs = []
+    last = [time.time()]
+
+    def tick(msg):
+        if log is not None and time.time() - last[0] > 20:
+            log(msg)
+            last[0] = time.time()
+
     for b in range(cfg.batch):
         f = None if force is None else force[:, b, :]
-        outs.append(pipelined.generate(
-            model, ctx[b], cfg.n_sub, cfg.delta_t, cfg.sub_tokens,
-            cfg.time_steps if steps is None else steps, cfg.bos_id, cfg.eos_id, force=f,
-            context_kv=None if context_kv is None else context_kv[b]))
+        kv = None if context_kv is None else context_kv[b]
+        if kv is None:
+            kv = model.prefill(ctx[b])
+            tick(f"[oracle] {cfg.name}: request {b} context pass done")
+        dec = pipelined.PerQueryDecoder(model, ctx[b], force=f, context_kv=kv)
+
+        def stepper(G, t, dec=dec, b=b):
+            out = dec(G, t)
+            tick(f"[oracle] {cfg.name}: request {b} iteration {t}")
+            return out
+
+        result, n_steps, emitted = controller.pipelined_decode(
+            stepper, cfg.delta_t, cfg.time_steps if steps is None else steps, cfg.n_sub, cfg.bos_id,
+            cfg.eos_id, cfg.sub_tokens)
+        outs.append({"result": result, "steps": n_steps, "emitted": emitted, "trace": dec.trace})
     return outs
 
 

@@ -159,3 +159,34 @@ def test_cfg2_full_size():
     stats = compare_teacher_forced(cfg, w, ctx, dec, outs, log=say)
     assert stats["rows"] == cfg.n_sub * (cfg.sub_tokens + 1) - 1
     dec.close()
+
+
+# --------------------------------------------------------------------------
+# Full-width workloads in the launch configuration the benchmark times: the named
+# workloads with 2 layers instead of 12-32 (every kernel's grid, tile shape and key-block
+# partition depend on widths, context length, S, dt, M and batch -- not on the depth), a
+# mildly peaky attention (QKV std 0.03 instead of 0.02) and a bounded number of iterations
+# so that the fp64 oracle finishes in about a minute.
+# --------------------------------------------------------------------------
+WIDE = {
+    # name: (config, iterations)
+    "cfg3-wide": (pi.get_config("cfg3").scaled(name="cfg3-wide", n_layer=2, qkv_std=0.03), 40),
+    "cfg4-wide": (pi.get_config("cfg4").scaled(name="cfg4-wide", n_layer=2, qkv_std=0.03), 72),
+    # dt=1 instead of 4: all 16 rows per request (64 rows in all) are reached within 16 iterations
+    "cfg5-wide": (pi.get_config("cfg5").scaled(name="cfg5-wide", n_layer=2, qkv_std=0.03, delta_t=1), 12),
+}
+
+
+@pytest.mark.parametrize("name", list(WIDE))
+def test_full_width_parity(name):
+    cfg, steps = WIDE[name]
+    say(f"[case] {name}: {cfg}, first {steps} iterations")
+    w = pi.make_weights(cfg)
+    ctx = pi.make_context(cfg)
+    say(f"[{name}] weights drawn")
+    outs = oracle_run(cfg, w, ctx, steps=steps, log=say)
+    say(f"[{name}] oracle done")
+    dec = make_decoder(cfg, w)
+    stats = compare_teacher_forced(cfg, w, ctx, dec, outs, steps=steps, log=say)
+    assert stats["rows"] > 0
+    dec.close()
