@@ -101,6 +101,9 @@ def main():
     ap.add_argument("--graph", type=int, default=0, help="replay each step from a captured HIP graph")
     ap.add_argument("--attn-splits", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy-mb", type=int, default=0,
+                    help="also run plain device-to-device copies of this many MiB (a kernel of known "
+                         "traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build runs on one GPU only (got --gpus {args.gpus}); "
@@ -124,6 +127,12 @@ def main():
                                max_sub_tokens=cfg.sub_tokens, max_pos=max_positions(cfg))
         dec.set_option(binding.PD_OPT_USE_GRAPH, args.graph)
         dec.set_option(binding.PD_OPT_ATTN_SPLITS, args.attn_splits)
+        if args.calibrate_copy_mb > 0:
+            src = torch.ones(args.calibrate_copy_mb << 20, dtype=torch.uint8, device="cuda")
+            dst = torch.empty_like(src)
+            for _ in range(3):
+                dst.copy_(src)
+            del src, dst
         torch.cuda.synchronize()
         t0 = time.time()
         dec.prefill_context(ctx, cfg.n_sub, cfg.delta_t, cfg.sub_tokens, cfg.time_steps)

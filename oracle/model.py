@@ -98,11 +98,12 @@ class OracleModel:
         return self.norm(x, self.final_g, self.final_b) @ self._lm().T
 
     # -- context pass (Eq. 1 analogue) --------------------------------------
-    def prefill(self, ctx_tokens):
+    def prefill(self, ctx_tokens, progress=None):
         """Causal forward over the context tokens at positions 0..L-1.
 
         Returns (K, V): lists over layers of arrays [H, L, hd] — the keys and
-        values (post-rotary) of every context token."""
+        values (post-rotary) of every context token.  progress: optional callable
+        invoked with the layer index after each layer (long runs report through it)."""
         s = self.s
         ctx_tokens = np.asarray(ctx_tokens)
         L = ctx_tokens.shape[0]
@@ -126,4 +127,6 @@ class OracleModel:
             x = self.after_attention(lw, x, attn)
             Ks.append(k_h)
             Vs.append(v_h)
+            if progress is not None:
+                progress(l)
         return Ks, Vs

@@ -30,7 +30,8 @@ def oracle_run(cfg, weights, ctx, force=None, steps=None, context_kv=None, log=N
         f = None if force is None else force[:, b, :]
         kv = None if context_kv is None else context_kv[b]
         if kv is None:
-            kv = model.prefill(ctx[b])
+            kv = model.prefill(ctx[b], progress=lambda l, b=b: tick(
+                f"[oracle] {cfg.name}: request {b} context pass, layer {l + 1}/{cfg.n_layer}"))
             tick(f"[oracle] {cfg.name}: request {b} context pass done")
         dec = pipelined.PerQueryDecoder(model, ctx[b], force=f, context_kv=kv)
 

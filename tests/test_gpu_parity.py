@@ -190,3 +190,26 @@ def test_full_width_parity(name):
     stats = compare_teacher_forced(cfg, w, ctx, dec, outs, steps=steps, log=say)
     assert stats["rows"] > 0
     dec.close()
+
+
+# --------------------------------------------------------------------------
+# Named workloads at full size (all layers, full context, full batch), first iterations.
+# The oracle's causal pass over the context dominates the run time (about 2.5 minutes for cfg4
+# on 16 host cores); it prints a progress line at least every 20 s.
+# --------------------------------------------------------------------------
+FULL = {"cfg3": 16, "cfg4": 3}
+
+
+@pytest.mark.parametrize("name", list(FULL))
+def test_full_size_first_iterations(name):
+    cfg, steps = pi.get_config(name), FULL[name]
+    say(f"[case] {name} at full size, first {steps} iterations")
+    w = pi.make_weights(cfg)
+    ctx = pi.make_context(cfg)
+    say(f"[{name}] weights drawn")
+    outs = oracle_run(cfg, w, ctx, steps=steps, log=say)
+    say(f"[{name}] oracle done")
+    dec = make_decoder(cfg, w)
+    stats = compare_teacher_forced(cfg, w, ctx, dec, outs, steps=steps, log=say)
+    assert stats["rows"] > 0
+    dec.close()

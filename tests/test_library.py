@@ -1,0 +1,96 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every function include/pd.h declares,
+sizes workspaces and rejects bad arguments with error codes (no GPU call is reached)."""
+
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import pd_inputs as pi
+from pd_inputs import max_positions
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2506_23431_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2506_23431_amd.build import build
+        build(verbose=False)
+    return binding.load()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "pd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pd_[a-z_]+)\s*\(", text)))
+
+
+def config_struct(cfg, **kw):
+    from paper_2506_23431_amd.binding import PdConfig
+    f = dict(n_layer=cfg.n_layer, d_model=cfg.d_model, n_head=cfg.n_head, head_dim=cfg.head_dim,
+             d_ff=cfg.d_ff, vocab=cfg.vocab, ffn_kind=cfg.ffn_kind, norm_kind=cfg.norm_kind,
+             pos_kind=cfg.pos_kind, rope_base=cfg.rope_base, norm_eps=cfg.norm_eps, dtype=cfg.dtype,
+             bos_id=cfg.bos_id, eos_id=cfg.eos_id, max_batch=cfg.batch, max_ctx=cfg.ctx_len,
+             max_sub=cfg.n_sub, max_sub_tokens=cfg.sub_tokens, max_pos=max_positions(cfg))
+    f.update(kw)
+    return PdConfig(**f)
+
+
+def test_every_declared_function_is_exported(lib):
+    names = declared_functions()
+    assert {"pd_prefill_context", "pd_decode_step", "pd_generate"} <= set(names)
+    for n in names:
+        assert getattr(lib, n) is not None, n
+    from paper_2506_23431_amd import binding
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_workspace_sizes(lib):
+    sizes = {}
+    for name in ("cfg1", "cfg2", "cfg3", "cfg4", "cfg5"):
+        cfg = pi.get_config(name)
+        n = lib.pd_workspace_bytes(C.byref(config_struct(cfg)))
+        assert n > 0 and n % 256 == 0
+        sizes[name] = n
+        # at least the two KV caches of every layer
+        kv = 2 * cfg.n_layer * cfg.batch * cfg.d_model * (cfg.ctx_len + cfg.n_sub * (cfg.sub_tokens + 1)) \
+            * (4 if cfg.dtype == 0 else 2)
+        assert n >= kv
+    assert sizes["cfg1"] < sizes["cfg2"] < sizes["cfg4"] < sizes["cfg5"] < 64 << 30
+
+
+@pytest.mark.parametrize("bad", [dict(n_head=3), dict(head_dim=7, n_head=1, d_model=7), dict(dtype=2),
+                                 dict(ffn_kind=5), dict(max_batch=0), dict(bos_id=-1), dict(norm_eps=0.0),
+                                 dict(eos_id=10 ** 6)])
+def test_invalid_configurations_are_rejected(lib, bad):
+    cfg = pi.get_config("cfg1")
+    assert lib.pd_workspace_bytes(C.byref(config_struct(cfg, **bad))) == 0
+    assert len(lib.pd_last_error()) > 0
+
+
+def test_create_rejects_bad_arguments_without_touching_the_gpu(lib):
+    from paper_2506_23431_amd.binding import PdWeights
+    cfg = config_struct(pi.get_config("cfg1"))
+    out = C.c_void_p()
+    w = PdWeights()
+    assert lib.pd_create(C.byref(cfg), None, None, 0, None, C.byref(out)) == -1          # PD_EINVAL
+    assert lib.pd_create(C.byref(cfg), C.byref(w), 256, 16, None, C.byref(out)) == -3     # PD_ENOMEM
+    assert b"workspace too small" in lib.pd_last_error()
+    need = lib.pd_workspace_bytes(C.byref(cfg))
+    assert lib.pd_create(C.byref(cfg), C.byref(w), 257, need, None, C.byref(out)) == -1   # unaligned
+    assert lib.pd_create(C.byref(cfg), C.byref(w), 256, need, None, C.byref(out)) == -1   # NULL weights
+    assert b"weight pointer is NULL" in lib.pd_last_error()
+    assert lib.pd_destroy(None) == 0
+    assert lib.pd_set_option(None, 1, 0) == -1
+    assert lib.pd_decode_steps(None, 1, None) == -1
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
+    from paper_2506_23431_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "missing.so"))
+    with pytest.raises(binding.PdError, match="no fallback"):
+        binding.load()
