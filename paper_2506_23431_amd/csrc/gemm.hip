@@ -176,77 +176,11 @@ int mfma_norm(pd_ctx *c, const float *gain, const float *bias, int R, hipStream_
 // which is what a kernel that lives for a few microseconds needs to pull HBM
 // bandwidth from the first cycle on.
 // ---------------------------------------------------------------------------
-template <int RT, int NW_N, int NW_K, int EPI, bool SPLIT>
-__global__ __launch_bounds__(64 * NW_N * NW_K) void k_gemm(GemmArgs a) {
-  __shared__ floatx4 red[NW_K > 1 ? NW_N * (NW_K - 1) * RT * 64 : 1];
-  int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  int wn = wave % NW_N, wk = wave / NW_N;
-  int nt = blockIdx.x * NW_N + wn;
+// epilogue of one 16-column tile: lane holds y[r][n0 + j], r = i*16 + m, n0 = nt*16 + 4g, j = 0..3
+template <int RT, int EPI>
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int nt, const floatx4 (&acc)[RT],
+                                              const int4 *kvi, int lane) {
   int m = lane & 15, g = lane >> 4;
-  bool active = nt < a.n_tiles;
-  int KT = a.K >> 5;
-  // waves along K: NW_K in this block times gridDim.y blocks (EPI_RESID only)
-  int gk = blockIdx.y * NW_K + wk, nk = gridDim.y * NW_K;
-  int kt0 = (int)((long)gk * KT / nk), kt1 = (int)((long)(gk + 1) * KT / nk);
-  // row data of the KV-append epilogue, requested now so that it arrives with the weights
-  int4 kvi[(EPI == EPI_QKV || EPI == EPI_QKV_ROPE) ? RT : 1];
-  if (EPI == EPI_QKV || EPI == EPI_QKV_ROPE) {
-#pragma unroll
-    for (int i = 0; i < RT; ++i) kvi[i] = a.rt.kvinfo[i * 16 + m];
-  }
-  floatx4 acc[RT];
-#pragma unroll
-  for (int i = 0; i < RT; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
-  if (active && kt1 > kt0) {
-    const uint4 *wp = (const uint4 *)a.W + ((size_t)nt * KT) * 64 + lane;
-    const uint4 *xp = (const uint4 *)a.xn + lane;
-    const uint4 *xl = SPLIT ? (const uint4 *)a.xn_lo + lane : nullptr;
-    constexpr int U = RT == 1 ? (SPLIT ? 8 : 16) : (RT == 2 ? 8 : 4);
-    for (int kt = kt0; kt < kt1; kt += U) {
-      Frag wa[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        int k = min(kt + u, kt1 - 1);
-        uint4 t = wp[(size_t)k * 64];
-        wa[u].u = kt + u < kt1 ? t : make_uint4(0, 0, 0, 0);
-      }
-#pragma unroll
-      for (int i = 0; i < RT; ++i) {
-        Frag xb[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          int k = min(kt + u, kt1 - 1);
-          xb[u].u = xp[((size_t)i * KT + k) * 64];
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) acc[i] = mfma16(wa[u], xb[u], acc[i]);
-        if (SPLIT) {
-#pragma unroll
-          for (int u = 0; u < U; ++u) {
-            int k = min(kt + u, kt1 - 1);
-            xb[u].u = xl[((size_t)i * KT + k) * 64];
-          }
-#pragma unroll
-          for (int u = 0; u < U; ++u) acc[i] = mfma16(wa[u], xb[u], acc[i]);
-        }
-      }
-    }
-  }
-  if (NW_K > 1) {
-    if (wk > 0) {
-#pragma unroll
-      for (int i = 0; i < RT; ++i) red[((wn * (NW_K - 1) + wk - 1) * RT + i) * 64 + lane] = acc[i];
-    }
-    __syncthreads();
-    if (wk > 0) return;
-#pragma unroll
-    for (int w = 0; w < NW_K - 1; ++w)
-#pragma unroll
-      for (int i = 0; i < RT; ++i) acc[i] += red[((wn * (NW_K - 1) + w) * RT + i) * 64 + lane];
-  }
-  if (!active) return;
-
-  // ---- epilogues: lane holds y[r][n0 + j], r = i*16 + m, n0 = nt*16 + 4g, j = 0..3
   int n0 = nt * 16 + 4 * g;
   if (EPI == EPI_RESID) {
     // split-K slice blockIdx.y of y; the following norm kernel adds the slices to x
@@ -354,6 +288,91 @@ __global__ __launch_bounds__(64 * NW_N * NW_K) void k_gemm(GemmArgs a) {
   }
 }
 
+template <int RT, int NT, int NW_K, int EPI, bool SPLIT>
+__global__ __launch_bounds__(64 * NW_K) void k_gemm(GemmArgs a) {
+  // A wave owns NT column tiles x RT row tiles x a share of K: every activation fragment it
+  // loads is used for NT weight fragments, every weight fragment for RT (x2) activation fragments.
+  __shared__ floatx4 red[NW_K > 1 ? (NW_K - 1) * NT * RT * 64 : 1];
+  int wk = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  int nt0 = blockIdx.x * NT;
+  int m = lane & 15;
+  int KT = a.K >> 5;
+  // waves along K: NW_K in this block times gridDim.y blocks (EPI_RESID only)
+  int gk = blockIdx.y * NW_K + wk, nk = gridDim.y * NW_K;
+  int kt0 = (int)((long)gk * KT / nk), kt1 = (int)((long)(gk + 1) * KT / nk);
+  // row data of the KV-append epilogue, requested now so that it arrives with the weights
+  int4 kvi[(EPI == EPI_QKV || EPI == EPI_QKV_ROPE) ? RT : 1];
+  if (EPI == EPI_QKV || EPI == EPI_QKV_ROPE) {
+#pragma unroll
+    for (int i = 0; i < RT; ++i) kvi[i] = a.rt.kvinfo[i * 16 + m];
+  }
+  floatx4 acc[NT][RT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int i = 0; i < RT; ++i) acc[t][i] = floatx4{0.f, 0.f, 0.f, 0.f};
+  if (kt1 > kt0) {
+    const uint4 *wp = (const uint4 *)a.W + lane;
+    const uint4 *xp = (const uint4 *)a.xn + lane;
+    const uint4 *xl = SPLIT ? (const uint4 *)a.xn_lo + lane : nullptr;
+    // k-tiles per request (1024-thread blocks have 128 registers per lane)
+    constexpr int TILE = NT * RT;
+    constexpr int U0 = TILE == 1 ? (SPLIT ? 8 : 16) : (TILE == 2 ? 8 : (TILE <= 8 ? 4 : 2));
+    constexpr int U = (NW_K == 16 && U0 > (TILE == 1 ? 8 : 4)) ? (TILE == 1 ? 8 : 4) : U0;
+    // request a chunk (weights of NT tiles x U k-tiles, then per row tile the hi and lo activation
+    // fragments), multiply, repeat; for small tiles the share of a wave is a single chunk
+    for (int kt = kt0; kt < kt1; kt += U) {
+      Frag wa[NT][U];
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        int nt = min(nt0 + t, a.n_tiles - 1);          // tiles past the end repeat the last one
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          uint4 v = wp[((size_t)nt * KT + min(kt + u, kt1 - 1)) * 64];
+          wa[t][u].u = kt + u < kt1 ? v : make_uint4(0, 0, 0, 0);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < RT; ++i) {
+        Frag xb[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) xb[u].u = xp[((size_t)i * KT + min(kt + u, kt1 - 1)) * 64];
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+          for (int u = 0; u < U; ++u) acc[t][i] = mfma16(wa[t][u], xb[u], acc[t][i]);
+        if (SPLIT) {
+#pragma unroll
+          for (int u = 0; u < U; ++u) xb[u].u = xl[((size_t)i * KT + min(kt + u, kt1 - 1)) * 64];
+#pragma unroll
+          for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int u = 0; u < U; ++u) acc[t][i] = mfma16(wa[t][u], xb[u], acc[t][i]);
+        }
+      }
+    }
+  }
+  if (NW_K > 1) {
+    if (wk > 0) {
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int i = 0; i < RT; ++i) red[(((wk - 1) * NT + t) * RT + i) * 64 + lane] = acc[t][i];
+    }
+    __syncthreads();
+    if (wk > 0) return;
+#pragma unroll
+    for (int w = 0; w < NW_K - 1; ++w)
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int i = 0; i < RT; ++i) acc[t][i] += red[((w * NT + t) * RT + i) * 64 + lane];
+  }
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+    if (nt0 + t < a.n_tiles) gemm_epilogue<RT, EPI>(a, nt0 + t, acc[t], kvi, lane);
+}
+
 // second stage of the argmax: one block per row over the per-tile winners
 __global__ __launch_bounds__(256) void k_lm_reduce(int32_t *row_argmax, const float *part_val,
                                                    const int32_t *part_idx, int n_tiles, int rows,
@@ -391,36 +410,40 @@ int mfma_lm_reduce(pd_ctx *c, int n_tiles, int R, hipStream_t s) {
 }
 
 // ---------------------------------------------------------------------------
-// launch: row tiles RT in {1,2,4,8}; waves along K so that a wave's share is <= 16
-// fragments (as far as the 1024-thread block and the LDS reduction buffer allow)
+// launch.  Row tiles RT in {1,2,4,5,8}; column tiles per wave NT = 1 (RT <= 2) or 4 (RT >= 4) so
+// that the activation fragments, which come from L2, stay at ~2-4 KiB per KiB of weights; waves along K so that a wave's share is a few requests at most and there are enough
+// waves for every SIMD.
 // ---------------------------------------------------------------------------
-template <int RT, int EPI, bool SPLIT>
+template <int RT, int NT, int EPI, bool SPLIT>
 static int launch_gemm_rt(const GemmArgs &a, hipStream_t s) {
   int KT = a.K / 32;
-  constexpr int SHARE = SPLIT && RT == 1 ? 8 : 16;   // fragments requested at once by a wave
-  int waves_k = (KT + SHARE - 1) / SHARE;            // waves along K so that a share is one request
+  constexpr int SHARE = NT * RT == 1 ? (SPLIT ? 8 : 16) : 16;   // k-tiles a wave should at least own
+  // LDS reduction buffer (NW_K - 1) * NT * RT KiB must stay below 64 KiB
+  constexpr int MAX_NWK = NT * RT <= 2 ? 16 : (NT * RT <= 4 ? 8 : (NT * RT <= 20 ? 4 : 2));
+  int groups = (a.n_tiles + NT - 1) / NT;
+  int waves_k = (KT + SHARE - 1) / SHARE;
+  // want about 2048 waves when the matrix is large enough to give every wave >= 4 k-tiles
+  while ((long)groups * waves_k < 2048 && KT / (waves_k * 2) >= 4) waves_k *= 2;
   int nwk = 1, ks = 1;
-  const int max_nwk = RT == 8 ? 8 : 16;
   if (EPI == EPI_RESID) {
-    // the split-K slices are summed by the next norm kernel, so K may also be split over
-    // blocks: enough blocks to occupy every compute unit, at most a.max_parts slices
-    while (ks < a.max_parts && (a.n_tiles * ks < 256 || waves_k > max_nwk * ks)) ks *= 2;
+    // split-K slices are summed by the next norm kernel, so K may also be split over blocks
+    while (ks < a.max_parts && (groups * ks < 256 || waves_k > MAX_NWK * ks)) ks *= 2;
     waves_k = (waves_k + ks - 1) / ks;
   }
-  while (nwk < max_nwk && nwk < waves_k) nwk *= 2;
-  // plenty of column tiles: fewer, longer-lived waves are enough to keep HBM busy
-  if ((long)a.n_tiles * nwk > 16384 && nwk > 1) nwk /= 2;
-  dim3 grid(1, ks);
+  while (nwk < MAX_NWK && nwk < waves_k) nwk *= 2;
+  if ((long)groups * nwk > 16384 && nwk > 1) nwk /= 2;
+  dim3 grid(groups, ks);
+#define PD_LAUNCH(NWK)                                                                          \
+  hipLaunchKernelGGL((k_gemm<RT, NT, (NWK <= MAX_NWK ? NWK : MAX_NWK), EPI, SPLIT>), grid,       \
+                     dim3(64 * (NWK <= MAX_NWK ? NWK : MAX_NWK)), 0, s, a)
   switch (nwk) {
-    case 1: grid.x = (a.n_tiles + 3) / 4; hipLaunchKernelGGL((k_gemm<RT, 4, 1, EPI, SPLIT>), grid, dim3(256), 0, s, a); break;
-    case 2: grid.x = (a.n_tiles + 1) / 2; hipLaunchKernelGGL((k_gemm<RT, 2, 2, EPI, SPLIT>), grid, dim3(256), 0, s, a); break;
-    case 4: grid.x = a.n_tiles; hipLaunchKernelGGL((k_gemm<RT, 1, 4, EPI, SPLIT>), grid, dim3(256), 0, s, a); break;
-    case 8: grid.x = a.n_tiles; hipLaunchKernelGGL((k_gemm<RT, 1, 8, EPI, SPLIT>), grid, dim3(512), 0, s, a); break;
-    default:
-      grid.x = a.n_tiles;
-      if (RT < 8) hipLaunchKernelGGL((k_gemm<RT, 1, (RT < 8 ? 16 : 8), EPI, SPLIT>), grid, dim3(1024), 0, s, a);
-      break;
+    case 1: PD_LAUNCH(1); break;
+    case 2: PD_LAUNCH(2); break;
+    case 4: PD_LAUNCH(4); break;
+    case 8: PD_LAUNCH(8); break;
+    default: PD_LAUNCH(16); break;
   }
+#undef PD_LAUNCH
   PD_CHECK_HIP(hipGetLastError());
   if (EPI == EPI_RESID && a.parts_out) *a.parts_out = ks;
   return PD_OK;
@@ -428,26 +451,24 @@ static int launch_gemm_rt(const GemmArgs &a, hipStream_t s) {
 
 int mfma_gemm_row_tiles(int rows) {
   int rt = (rows + 15) / 16;
-  return (rt <= 1 ? 1 : rt <= 2 ? 2 : rt <= 4 ? 4 : 8) * 16;
+  return (rt <= 1 ? 1 : rt <= 2 ? 2 : rt <= 4 ? 4 : rt <= 5 ? 5 : 8) * 16;
+}
+
+template <int EPI, bool SPLIT>
+static int launch_gemm_split(const GemmArgs &a, int rows, hipStream_t s) {
+  switch (mfma_gemm_row_tiles(rows)) {
+    case 16: return launch_gemm_rt<1, 1, EPI, SPLIT>(a, s);
+    case 32: return launch_gemm_rt<2, 1, EPI, SPLIT>(a, s);
+    case 64: return launch_gemm_rt<4, 2, EPI, SPLIT>(a, s);
+    case 80: return launch_gemm_rt<5, 4, EPI, SPLIT>(a, s);
+    default: return launch_gemm_rt<8, 4, EPI, SPLIT>(a, s);
+  }
 }
 
 template <int EPI>
 static int launch_gemm(const GemmArgs &a, int rows, hipStream_t s) {
   PD_REQUIRE(rows <= 128, PD_EINVAL, "more than 128 rows per launch (%d)", rows);
-  if (a.xn_lo) {
-    switch (mfma_gemm_row_tiles(rows)) {
-      case 16: return launch_gemm_rt<1, EPI, true>(a, s);
-      case 32: return launch_gemm_rt<2, EPI, true>(a, s);
-      case 64: return launch_gemm_rt<4, EPI, true>(a, s);
-      default: return launch_gemm_rt<8, EPI, true>(a, s);
-    }
-  }
-  switch (mfma_gemm_row_tiles(rows)) {
-    case 16: return launch_gemm_rt<1, EPI, false>(a, s);
-    case 32: return launch_gemm_rt<2, EPI, false>(a, s);
-    case 64: return launch_gemm_rt<4, EPI, false>(a, s);
-    default: return launch_gemm_rt<8, EPI, false>(a, s);
-  }
+  return a.xn_lo ? launch_gemm_split<EPI, true>(a, rows, s) : launch_gemm_split<EPI, false>(a, rows, s);
 }
 
 int mfma_gemm(int epi, const GemmArgs &a, int rows, hipStream_t s) {
