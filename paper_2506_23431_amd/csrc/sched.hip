@@ -151,7 +151,7 @@ int launch_embed(pd_ctx *c, int R, hipStream_t s) {
 // copy of this step's logits to the caller's [B][S][V] buffer.
 // ---------------------------------------------------------------------------
 __global__ void k_commit(SchedState st, RowTables rt, const int32_t *row_argmax, int S, int M,
-                         int time_max, int eos, int B) {
+                         int time_max, int eos, int B, int V) {
   int b = blockIdx.x;
   if (threadIdx.x != 0) return;
   if (st.done[b]) return;
@@ -162,6 +162,9 @@ __global__ void k_commit(SchedState st, RowTables rt, const int32_t *row_argmax,
     if (r >= 0 && (rt.flags[r] & ROW_PRODUCE)) {
       int f = st.force[b * S + i];
       int tok = f >= 0 ? f : row_argmax[r];
+      // non-finite logits leave the argmax without a winner: keep the id inside the vocabulary so
+      // that the next embedding gather stays in bounds
+      if (tok < 0 || tok >= V) tok = 0;
       int nt = st.n_tok[b * S + i];
       st.grid[(size_t)(b * S + i) * (M + 1) + nt] = tok;
       st.n_tok[b * S + i] = nt + 1;
@@ -194,7 +197,7 @@ int launch_commit(pd_ctx *c, float *out_logits, hipStream_t s) {
     PD_CHECK_HIP(hipGetLastError());
   }
   hipLaunchKernelGGL(k_commit, dim3(c->B), dim3(64), 0, s, c->sch, c->rows, c->row_argmax, c->S,
-                     c->M, c->time_max, c->cfg.eos_id, c->B);
+                     c->M, c->time_max, c->cfg.eos_id, c->B, c->cfg.vocab);
   PD_CHECK_HIP(hipGetLastError());
   return PD_OK;
 }

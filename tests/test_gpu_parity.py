@@ -213,3 +213,34 @@ def test_full_size_first_iterations(name):
     stats = compare_teacher_forced(cfg, w, ctx, dec, outs, steps=steps, log=say)
     assert stats["rows"] > 0
     dec.close()
+
+
+def test_options_do_not_change_results():
+    """HIP-graph replay of the step, other split counts, the prefetching attention variant and
+    plain-bf16 activations: same tokens as the default path on a workload whose top-2 margins are
+    comfortably above the bf16 noise; the graph is replayed for every step of three runs with eager
+    work and synchronisations in between, and every replayed run is compared."""
+    import torch
+    from paper_2506_23431_amd import binding
+    cfg = CASES["mfma-hd64"]
+    w = pi.make_weights(cfg, threads=4)
+    ctx = pi.make_context(cfg)
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        dec = make_decoder(cfg, w)
+        args = (ctx, cfg.n_sub, cfg.delta_t, cfg.sub_tokens, cfg.time_steps)
+        base = dec.generate(*args)
+        for key, val in ((binding.PD_OPT_USE_GRAPH, 1), (binding.PD_OPT_ATTN_SPLITS, 3),
+                         (binding.PD_OPT_ATTN_SPLITS, 1), (binding.PD_OPT_ATTN_PREFETCH, 1)):
+            dec.set_option(key, val)
+            for rep in range(3 if key == binding.PD_OPT_USE_GRAPH else 1):
+                got = dec.generate(*args)
+                torch.cuda.synchronize()
+                for a, b in zip(base, got):
+                    assert np.array_equal(a, b), f"option {key}={val} (run {rep}) changed the result"
+            dec.set_option(key, 0)
+        # plain bf16 activations: larger rounding error, still within the logit tolerance
+        dec.set_option(binding.PD_OPT_SPLIT_ACT, 0)
+        outs = oracle_run(cfg, w, ctx)
+        compare_teacher_forced(cfg, w, ctx, dec, outs, log=say)
+        dec.close()
