@@ -142,15 +142,12 @@ int pd_reset_decode(pd_ctx *ctx, void *hip_stream);
  *                        multiply as a pair of bf16 values (about 16 mantissa bits) and runs two
  *                        matrix-core passes per weight / key / value fragment; 0 uses plain bf16
  *                        activations (half the matrix-core work, larger rounding error)
- *   PD_OPT_ATTN_PREFETCH 1: each attention wave keeps a second key/value block in flight
- *                        (more registers, fewer resident waves); 0 (default): one block per wave
  * The environment variable PD_IMPL=simple makes pd_create choose the fp32-activation kernels
  * for dtype 1 too (debugging aid).                                                     */
 #define PD_OPT_ATTN_SPLITS 1
 #define PD_OPT_USE_GRAPH   2
 #define PD_OPT_PROFILE     3
 #define PD_OPT_SPLIT_ACT   4
-#define PD_OPT_ATTN_PREFETCH 5
 int pd_set_option(pd_ctx *ctx, int key, int value);
 
 /* Average duration in microseconds of the attention-kernel launches bracketed since

@@ -17,103 +17,130 @@
 #include "mfma_common.h"
 
 #include <algorithm>
+#include <stdlib.h>
 
 struct AttnArgs {
   const f16_t *q, *q_lo;    // [rows][d] fp16 high / low parts (q_lo NULL: high part only)
   const f16_t *kc, *vc;     // packed fp16 caches of this layer
   bf16_t *out, *out_lo;     // [rows][d] high / low parts (out_lo NULL: high part only)
   RowTables rt;
-  const int32_t *kv_len, *gen_sub;
+  const int32_t *kv_len;
+  const uint16_t *gen_sub;  // subsequence tag of key slot j >= L at [req][j - (L & ~7)]
   int kv_override;          // >= 0: number of keys to consider (prefill), else kv_len[req]
   float *part;
-  int d, H, kv_cap, gen_cap, L, A, nqg, req0, nsplit, nblk_static;
+  int d, H, kv_cap, gen_stride, L, A, nqg, req0, nsplit, nblk_static;
   float scale_log2;         // log2(e) / sqrt(hd)
 };
 
-template <int HD>
-struct KVBlock {
-  Frag k[2][HD / 32];
-  Frag v[HD / 16];
-};
-
-template <int HD>
-__device__ __forceinline__ void load_block(KVBlock<HD> &b, const uint4 *Kp, const uint4 *Vp, int kb) {
-  constexpr int NC = HD / 32, NHB = HD / 16;
-#pragma unroll
-  for (int t = 0; t < 2; ++t)
-#pragma unroll
-    for (int c = 0; c < NC; ++c) b.k[t][c].u = Kp[((size_t)(kb * 2 + t) * NC + c) * 64];
-#pragma unroll
-  for (int i = 0; i < NHB; ++i) b.v[i].u = Vp[((size_t)kb * NHB + i) * 64];
-}
-
-template <int HD, bool SPLIT, bool DB>
-__global__ __launch_bounds__(256, DB ? 1 : 3) void k_attn_mfma(AttnArgs a) {
+template <int HD, bool SPLIT>
+__global__ __launch_bounds__(256, 3) void k_attn_mfma(AttnArgs a) {
   constexpr int NC = HD / 32, NHB = HD / 16, PSTR = HD + 2;   // partial: m, l, O[HD] per query
   __shared__ float sm_m[4][16], sm_l[4][16];
-  __shared__ float sm_o[4][HD][17];
+  __shared__ floatx4 sm_o[4][HD / 16][64];
+  __shared__ uint4 sm_q[(SPLIT ? 2 : 1) * NC][64];
   int split = blockIdx.x, h = blockIdx.y, z = blockIdx.z;
   int reqi = z / a.nqg, qg = z % a.nqg, req = a.req0 + reqi;
-  int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   int n = lane & 15, g = lane >> 4;
 
-  const uint4 *Kp = (const uint4 *)(a.kc + ((size_t)req * a.H + h) * a.kv_cap * HD) + lane;
-  const uint4 *Vp = (const uint4 *)(a.vc + ((size_t)req * a.H + h) * a.kv_cap * HD) + lane;
-  // 32-key blocks are dealt round-robin to the 4*nsplit waves that serve this (request, head):
-  // whatever the current key count, no wave gets more than one block above the average
-  const int stride = 4 * a.nsplit;
-  int kb = split * 4 + wave;
-  KVBlock<HD> A, B;
-  if (kb < a.nblk_static) load_block<HD>(A, Kp, Vp, kb);   // in flight while the row data is fetched
-
-  // everything the block needs to know about its queries, requested in one go: no load
-  // below depends on the result of another
+  // Everything the block needs to know about its queries is requested first (a few lines that sit
+  // in the L2 cache), then the first key/value block; no load below depends on the result of
+  // another, and the wait for the row data does not wait for the key/value block behind it.
   int qa = qg * 16 + n;                       // query index inside the request
   bool in_req = qa < a.A;
   int r = reqi * a.A + (in_req ? qa : 0);     // row (clamped: loads stay in bounds)
   int4 qi = a.rt.qinfo[r];                    // {flags, sub, lim, req}
   int n_keys = a.kv_override >= 0 ? a.kv_override : a.kv_len[req];
-  Frag qf[NC], ql[SPLIT ? NC : 1];
+  // Query fragments (high and low parts) go to LDS, in operand order: the four waves share them,
+  // and keeping them out of the registers leaves room for three waves per SIMD.  Rows without a
+  // token keep whatever finite numbers their q slots hold: all their keys are masked below, and
+  // their output is never written.
+  const size_t q_off = act_off(r, h * HD + g * 8, a.d);
+  constexpr int NQ = (NC + 3) / 4;            // fragments per wave
+  uint4 qh[NQ], qlo[SPLIT ? NQ : 1];
 #pragma unroll
-  for (int c = 0; c < NC; ++c) {
-    size_t off = act_off(r, h * HD + c * 32 + g * 8, a.d);
-    qf[c].u = *(const uint4 *)(a.q + off);
-    if (SPLIT) ql[c].u = *(const uint4 *)(a.q_lo + off);
+  for (int i = 0; i < NQ; ++i) {
+    int c = min(wave + 4 * i, NC - 1);
+    size_t off = q_off + (size_t)c * 512;     // the next 32 dims are the next fragment
+    qh[i] = *(const uint4 *)(a.q + off);
+    if (SPLIT) qlo[i] = *(const uint4 *)(a.q_lo + off);
   }
+
+  const uint4 *Kp = (const uint4 *)(a.kc + ((size_t)req * a.H + h) * a.kv_cap * HD) + lane;
+  const uint4 *Vp = (const uint4 *)(a.vc + ((size_t)req * a.H + h) * a.kv_cap * HD) + lane;
+  // subsequence tags of the generated-side slots, 8 keys (16 bytes) per lane group
+  const uint16_t *gs = a.gen_sub + (size_t)req * a.gen_stride;
+  const int L8 = a.L & ~7;
+  // 32-key blocks are dealt round-robin to the 4*nsplit waves that serve this (request, head):
+  // whatever the current key count, no wave gets more than one block above the average
+  const int stride = 4 * a.nsplit;
+  int kb = split * 4 + wave;
+  Frag kf[2][NC], vf[NHB];
+  union { uint4 u; uint16_t s[8]; } tg;
+  auto load_k = [&](int kbx) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int c = 0; c < NC; ++c) kf[t][c].u = Kp[((size_t)(kbx * 2 + t) * NC + c) * 64];
+  };
+  auto load_v = [&](int kbx) {
+    // tags of the lane's 8 keys (clamped: context blocks read entry 0 and never use it)
+    tg.u = *(const uint4 *)(gs + min(max(kbx * 32 + 8 * g - L8, 0), a.gen_stride - 8));
+#pragma unroll
+    for (int i = 0; i < NHB; ++i) vf[i].u = Vp[((size_t)kbx * NHB + i) * 64];
+  };
+  // requested unconditionally (a wave beyond the last block fetches that block and ignores it), so
+  // that the wait for the query rows above never has to wait for these
+  load_k(min(kb, a.nblk_static - 1));
+  load_v(min(kb, a.nblk_static - 1));
+  // (waves beyond the fragment count store a copy of the last fragment: same bytes, same place)
+#pragma unroll
+  for (int i = 0; i < NQ; ++i) {
+    int c = min(wave + 4 * i, NC - 1);
+    sm_q[c][lane] = qh[i];
+    if (SPLIT) sm_q[NC + c][lane] = qlo[i];
+  }
+  __syncthreads();
+
   bool qvalid = in_req && (qi.x & ROW_VALID);
   int q_sub = qvalid ? qi.y : -1, q_lim = qvalid ? qi.z : 0;
-  if (!qvalid) {
-#pragma unroll
-    for (int c = 0; c < NC; ++c) {
-      qf[c].u = make_uint4(0, 0, 0, 0);
-      if (SPLIT) ql[c].u = make_uint4(0, 0, 0, 0);
-    }
-  }
   // keys any query of this group can see
   int reach = qvalid ? (n_keys > a.L && q_sub >= 1 ? n_keys : min(q_lim, n_keys)) : 0;
   for (int o = 1; o < 16; o <<= 1) reach = max(reach, __shfl_xor(reach, o));
-  int end = min(a.nblk_static, (reach + 31) >> 5);
-  const int32_t *gs = a.gen_sub + (size_t)req * a.gen_cap;
+  const int end = __builtin_amdgcn_readfirstlane(min(a.nblk_static, (reach + 31) >> 5));
 
   float m_run = -INFINITY, l_run = 0.f;
   floatx4 o_acc[NHB];
 #pragma unroll
   for (int i = 0; i < NHB; ++i) o_acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-  auto compute = [&](const KVBlock<HD> &blk, int kbc) {
-    floatx4 s[2];
+  // One block per wave is resident in registers.  The key fragments of the wave's next block are
+  // requested as soon as the score products have consumed the current ones, the value fragments
+  // (and tags) as soon as the output products have: the loads of block i+1 overlap the softmax
+  // and the output products of block i without a second set of registers.
+  while (kb < end) {
+    floatx4 s[2] = {floatx4{0.f, 0.f, 0.f, 0.f}, floatx4{0.f, 0.f, 0.f, 0.f}};
+    // the query fragments are re-read from LDS for every block (the empty asm keeps the compiler
+    // from hoisting the reads out of the loop, which would put them back into 32 registers)
+    int ql_lane = lane;
+    asm volatile("" : "+v"(ql_lane));
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      s[t] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int c = 0; c < NC; ++c) s[t] = mfma16h(blk.k[t][c], qf[c], s[t]);
+    for (int c = 0; c < NC; ++c) {
+      Frag qf;
+      qf.u = sm_q[c][ql_lane];
+      s[0] = mfma16h(kf[0][c], qf, s[0]);
+      s[1] = mfma16h(kf[1][c], qf, s[1]);
       if (SPLIT) {
-#pragma unroll
-        for (int c = 0; c < NC; ++c) s[t] = mfma16h(blk.k[t][c], ql[c], s[t]);
+        qf.u = sm_q[NC + c][ql_lane];
+        s[0] = mfma16h(kf[0][c], qf, s[0]);
+        s[1] = mfma16h(kf[1][c], qf, s[1]);
       }
     }
-    // lane (n, g), tile t, register j  <->  key kbc*32 + 8g + 4t + j
-    int key0 = kbc * 32 + 8 * g;
+    const int kn = kb + stride;
+    const bool more = kn < end;
+    if (more) load_k(kn);
+    // lane (n, g), tile t, register j  <->  key kb*32 + 8g + 4t + j
+    int key0 = kb * 32 + 8 * g;
     float sv[8];
     bool tail = key0 + 8 > a.L || key0 + 8 > q_lim;     // needs the per-key test
     float mloc = -INFINITY;
@@ -121,10 +148,7 @@ __global__ __launch_bounds__(256, DB ? 1 : 3) void k_attn_mfma(AttnArgs a) {
     for (int e = 0; e < 8; ++e) {
       int key = key0 + e;
       bool vis = true;
-      if (tail) {
-        vis = key < q_lim;
-        if (!vis && key >= a.L && key < n_keys) vis = gs[key - a.L] <= q_sub;
-      }
+      if (tail) vis = key < q_lim || (key >= a.L && key < n_keys && (int)tg.s[e] <= q_sub);
       float v = vis ? s[e >> 2][e & 3] * a.scale_log2 : -INFINITY;
       sv[e] = v;
       mloc = fmaxf(mloc, v);
@@ -150,144 +174,113 @@ __global__ __launch_bounds__(256, DB ? 1 : 3) void k_attn_mfma(AttnArgs a) {
 #pragma unroll
     for (int i = 0; i < NHB; ++i) {
       o_acc[i] *= alpha;
-      o_acc[i] = mfma16h(blk.v[i], pf, o_acc[i]);
-      if (SPLIT) o_acc[i] = mfma16h(blk.v[i], pl, o_acc[i]);
+      o_acc[i] = mfma16h(vf[i], pf, o_acc[i]);
+      if (SPLIT) o_acc[i] = mfma16h(vf[i], pl, o_acc[i]);
     }
-  };
-
-  if (DB) {
-    // ping-pong over the wave's blocks kb, kb+4, ...: the next block is requested
-    // before the current one is consumed
-    while (kb < end) {
-      int kn = kb + stride;
-      if (kn < end) load_block<HD>(B, Kp, Vp, kn);
-      compute(A, kb);
-      if (kn >= end) break;
-      kb = kn;
-      kn = kb + stride;
-      if (kn < end) load_block<HD>(A, Kp, Vp, kn);
-      compute(B, kb);
-      kb = kn;
-    }
-  } else {
-    // one block in flight per wave; the resident waves of the compute unit overlap
-    while (kb < end) {
-      compute(A, kb);
-      kb += stride;
-      if (kb < end) load_block<HD>(A, Kp, Vp, kb);
-    }
+    if (more) load_v(kn);
+    kb = kn;
   }
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
 
   // ---- merge the 4 waves of the block (log-sum-exp) ----
+  // every wave stores its accumulators as 16-byte quads (lane order: conflict-free); after the
+  // barrier wave w owns the 16-dim blocks w, w + 4, ... and sums the four copies of each
   if (g == 0) { sm_m[wave][n] = m_run; sm_l[wave][n] = l_run; }
 #pragma unroll
-  for (int i = 0; i < NHB; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) sm_o[wave][i * 16 + 4 * g + j][n] = o_acc[i][j];
+  for (int i = 0; i < NHB; ++i) sm_o[wave][i][lane] = o_acc[i];
   __syncthreads();
-  // thread -> (query qn, dims dd, dd + 16, ...)
-  int qn = threadIdx.x & 15, dd = threadIdx.x >> 4;
   float mw[4], M = -INFINITY;
 #pragma unroll
-  for (int w = 0; w < 4; ++w) { mw[w] = sm_m[w][qn]; M = fmaxf(M, mw[w]); }
+  for (int w = 0; w < 4; ++w) { mw[w] = sm_m[w][n]; M = fmaxf(M, mw[w]); }
   float fw[4], lsum = 0.f;
 #pragma unroll
   for (int w = 0; w < 4; ++w) {
     fw[w] = mw[w] == -INFINITY ? 0.f : exp2f(mw[w] - M);
-    lsum += fw[w] * sm_l[w][qn];
+    lsum += fw[w] * sm_l[w][n];
   }
-  int out_qa = qg * 16 + qn, out_r = reqi * a.A + out_qa;
-  bool out_valid = out_qa < a.A && (__shfl(qi.x, qn) & ROW_VALID);
-  if (!out_valid) return;
-  if (a.nsplit == 1) {
-    float inv = 1.f / lsum;
-    for (int dim = dd; dim < HD; dim += 16) {
-      float o = 0.f;
-#pragma unroll
-      for (int w = 0; w < 4; ++w) o += fw[w] * sm_o[w][dim][qn];
-      bf16_t hi = f32_to_bf16(o * inv);
-      size_t off = act_off(out_r, h * HD + dim, a.d);
-      a.out[off] = hi;
-      if (a.out_lo) a.out_lo[off] = f32_to_bf16(bf16_residual(o * inv, hi));
-    }
-    return;
-  }
-  // partial of this block: rows m, l, O[0..HD) of 16 floats (one per query): stores of
-  // neighbouring lanes are contiguous
+  if (!qvalid) return;                        // lane (n, g) writes for query n only
+  // partial of this block: m[16], l[16], then O as [dim / 4][query][4 dims]: a wave's store of one
+  // 16-dim block is 1 KiB of consecutive bytes
   size_t unit = (size_t)z * a.H + h;
-  float *pp = a.part + (unit * a.nsplit + split) * (size_t)(PSTR * 16) + qn;
-  if (dd == 0) { pp[0] = M; pp[16] = lsum; }
-  for (int dim = dd; dim < HD; dim += 16) {
-    float o = 0.f;
+  float *pp = a.part + (unit * a.nsplit + split) * (size_t)(PSTR * 16);
+  if (a.nsplit > 1 && wave == 0 && g == 0) { pp[n] = M; pp[16 + n] = lsum; }
+  const float inv = 1.f / lsum;
+  for (int i = wave; i < NHB; i += 4) {
+    floatx4 o = fw[0] * sm_o[0][i][lane];
 #pragma unroll
-    for (int w = 0; w < 4; ++w) o += fw[w] * sm_o[w][dim][qn];
-    pp[(2 + dim) * 16] = o;
+    for (int w = 1; w < 4; ++w) o += fw[w] * sm_o[w][i][lane];
+    if (a.nsplit == 1) {
+      float y[4] = {o[0] * inv, o[1] * inv, o[2] * inv, o[3] * inv};
+      store4_split(a.out, a.out_lo, act_off(r, h * HD + i * 16 + 4 * g, a.d), y);
+    } else {
+      *(floatx4 *)(pp + 32 + ((i * 4 + g) * 16 + n) * 4) = o;
+    }
   }
 }
 
-// Merge of the split partials by log-sum-exp.  Block = (unit, 16 dims); thread = (query, dim).
-// The (max, sum) pairs of a query are read once, spread over the 4 lanes of a wave that share
-// the query, and reduced by shuffles; then every thread accumulates its dim over the splits with
-// 16 splits' loads in flight at a time.  Neighbouring lanes read neighbouring floats.
+// Merge of the split partials by log-sum-exp.  Block = (unit, 16-dim block), 4 waves; wave w merges
+// the splits w, w + 4, ... online (running max, sum and 4 output dims per lane), 8 splits' loads in
+// flight at a time; the four running states are then combined through LDS.
 template <int HD>
 __global__ __launch_bounds__(256) void k_attn_merge(AttnArgs a) {
-  constexpr int PSTR = HD + 2;
-  int unit = blockIdx.x, z = unit / a.H, h = unit % a.H;
+  constexpr int PSTR = HD + 2, U = 8;
+  __shared__ float sm_M[4][64], sm_L[4][64];
+  __shared__ floatx4 sm_O[4][64];
+  int unit = blockIdx.x, i = blockIdx.y, z = unit / a.H, h = unit % a.H;
   int reqi = z / a.nqg, qg = z % a.nqg;
-  int qn = threadIdx.x & 15, dg = (threadIdx.x >> 4) & 3, dim = blockIdx.y * 16 + (threadIdx.x >> 4);
-  int qa = qg * 16 + qn, r = reqi * a.A + min(qa, a.A - 1);
+  int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 15, g = lane >> 4;
+  int qa = qg * 16 + n, r = reqi * a.A + min(qa, a.A - 1);
   int fl = a.rt.flags[r];
-  const float *pb = a.part + (size_t)unit * a.nsplit * (PSTR * 16) + qn;
   const size_t sstr = (size_t)PSTR * 16;
-  // lane group dg takes splits dg, dg + 4, ...  (nsplit <= 256: at most 64 each, 16 per pass)
-  float M = -INFINITY, lg = 0.f;
-  for (int s0 = dg; s0 < a.nsplit; s0 += 64) {
-    float mv[16], lv[16];
+  const float *pb = a.part + (size_t)unit * a.nsplit * sstr;
+  const int o_off = 32 + ((i * 4 + g) * 16 + n) * 4;
+  float M = -INFINITY, l = 0.f;
+  floatx4 o = floatx4{0.f, 0.f, 0.f, 0.f};
+  for (int s0 = wave; s0 < a.nsplit; s0 += 4 * U) {
+    float mv[U], lv[U];
+    floatx4 ov[U];
 #pragma unroll
-    for (int u = 0; u < 16; ++u) {
-      int sp = s0 + 4 * u;
-      bool in = sp < a.nsplit;
-      mv[u] = in ? pb[sp * sstr] : -INFINITY;
-      lv[u] = in ? pb[sp * sstr + 16] : 0.f;
+    for (int u = 0; u < U; ++u) {
+      const float *ps = pb + (size_t)min(s0 + 4 * u, a.nsplit - 1) * sstr;   // clamped: masked below
+      mv[u] = ps[n];
+      lv[u] = ps[16 + n];
+      ov[u] = *(const floatx4 *)(ps + o_off);
     }
     float Mn = M;
 #pragma unroll
-    for (int u = 0; u < 16; ++u) Mn = fmaxf(Mn, mv[u]);
+    for (int u = 0; u < U; ++u) {
+      if (s0 + 4 * u >= a.nsplit) mv[u] = -INFINITY;
+      Mn = fmaxf(Mn, mv[u]);
+    }
     if (Mn != -INFINITY) {
-      lg *= exp2f(M - Mn);        // M == -inf: lg is 0 and stays 0
+      float sc = exp2f(M - Mn);               // M == -inf: 0, and l, o are 0 anyway
+      l *= sc; o *= sc;
 #pragma unroll
-      for (int u = 0; u < 16; ++u) lg += mv[u] == -INFINITY ? 0.f : exp2f(mv[u] - Mn) * lv[u];
+      for (int u = 0; u < U; ++u) {
+        float w = mv[u] == -INFINITY ? 0.f : exp2f(mv[u] - Mn);
+        l += w * lv[u];
+        o += w * ov[u];
+      }
       M = Mn;
     }
   }
+  sm_M[wave][lane] = M; sm_L[wave][lane] = l; sm_O[wave][lane] = o;
+  __syncthreads();
+  if (wave != 0) return;
+  float Mt = fmaxf(fmaxf(sm_M[0][lane], sm_M[1][lane]), fmaxf(sm_M[2][lane], sm_M[3][lane]));
+  float lt = 0.f;
+  floatx4 ot = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-  for (int off = 16; off <= 32; off <<= 1) {     // combine the 4 lane groups of the query
-    float Mo = __shfl_xor(M, off), lo = __shfl_xor(lg, off);
-    float Mn = fmaxf(M, Mo);
-    lg = (M == -INFINITY ? 0.f : lg * exp2f(M - Mn)) + (Mo == -INFINITY ? 0.f : lo * exp2f(Mo - Mn));
-    M = Mn;
-  }
-  float o = 0.f;
-  for (int s0 = 0; s0 < a.nsplit; s0 += 16) {
-    float mv[16], ov[16];
-#pragma unroll
-    for (int u = 0; u < 16; ++u) {
-      size_t sp = min(s0 + u, a.nsplit - 1);
-      mv[u] = pb[sp * sstr];
-      ov[u] = pb[sp * sstr + (2 + dim) * 16];
-    }
-#pragma unroll
-    for (int u = 0; u < 16; ++u)
-      o += (s0 + u < a.nsplit && mv[u] != -INFINITY) ? exp2f(mv[u] - M) * ov[u] : 0.f;
+  for (int w = 0; w < 4; ++w) {
+    float f = sm_M[w][lane] == -INFINITY ? 0.f : exp2f(sm_M[w][lane] - Mt);
+    lt += f * sm_L[w][lane];
+    ot += f * sm_O[w][lane];
   }
   if (qa >= a.A || !(fl & ROW_VALID)) return;
-  float y = o / lg;
-  bf16_t hi = f32_to_bf16(y);
-  size_t off = act_off(r, h * HD + dim, a.d);
-  a.out[off] = hi;
-  if (a.out_lo) a.out_lo[off] = f32_to_bf16(bf16_residual(y, hi));
+  float inv = 1.f / lt;
+  float y[4] = {ot[0] * inv, ot[1] * inv, ot[2] * inv, ot[3] * inv};
+  store4_split(a.out, a.out_lo, act_off(r, h * HD + i * 16 + 4 * g, a.d), y);
 }
 
 static int pick_splits(pd_ctx *c, int units, int nblk) {
@@ -307,9 +300,10 @@ int mfma_attention(pd_ctx *c, const LayerPtrs &lw, int A, int nreq, int req0, in
   a.out_lo = mfma_lo(c, c->att, g.d_model); a.kc = (const f16_t *)lw.kc; a.vc = (const f16_t *)lw.vc;
   a.out = (bf16_t *)c->att; a.rt = c->rows; a.kv_len = c->sch.kv_len; a.gen_sub = c->sch.gen_sub;
   a.kv_override = kv_override; a.part = c->att_part;
-  a.d = g.d_model; a.H = g.n_head; a.kv_cap = c->kv_cap; a.gen_cap = c->gen_cap; a.L = c->L;
+  a.d = g.d_model; a.H = g.n_head; a.kv_cap = c->kv_cap; a.gen_stride = c->gen_stride; a.L = c->L;
   a.A = A; a.nqg = (A + 15) / 16; a.req0 = req0;
   a.scale_log2 = 1.4426950408889634f / sqrtf((float)g.head_dim);
+  if (getenv("PD_ATTN_NOSPLIT")) a.q_lo = nullptr;   // TEMPORARY experiment switch
   int units = nreq * a.nqg * g.n_head;
   PD_REQUIRE(units <= 4096, PD_EINVAL, "too many (request, head, query group) units: %d", units);
   // the most keys this launch can meet: prefill knows it, decode takes the end of the run
@@ -328,10 +322,8 @@ int mfma_attention(pd_ctx *c, const LayerPtrs &lw, int A, int nreq, int req0, in
   }
 #define PD_ATTN(HDV)                                                                        \
   do {                                                                                      \
-    if (a.q_lo && c->opt_db) hipLaunchKernelGGL((k_attn_mfma<HDV, true, true>), grid, dim3(256), 0, s, a);   \
-    else if (a.q_lo) hipLaunchKernelGGL((k_attn_mfma<HDV, true, false>), grid, dim3(256), 0, s, a);          \
-    else if (c->opt_db) hipLaunchKernelGGL((k_attn_mfma<HDV, false, true>), grid, dim3(256), 0, s, a);       \
-    else hipLaunchKernelGGL((k_attn_mfma<HDV, false, false>), grid, dim3(256), 0, s, a);                     \
+    if (a.q_lo) hipLaunchKernelGGL((k_attn_mfma<HDV, true>), grid, dim3(256), 0, s, a);     \
+    else hipLaunchKernelGGL((k_attn_mfma<HDV, false>), grid, dim3(256), 0, s, a);           \
     if (a.nsplit > 1)                                                                       \
       hipLaunchKernelGGL(k_attn_merge<HDV>, dim3(units, HDV / 16), dim3(256), 0, s, a);            \
   } while (0)

@@ -74,6 +74,7 @@ static size_t carve(const pd_config *g, char *base, pd_ctx *c) {
     if (!strcmp(e, "simple")) x->impl = 0;
   }
   x->gen_cap = S * (M + 1);
+  x->gen_stride = (x->gen_cap + 8 + 7) / 8 * 8;
   x->kv_cap = (g->max_ctx + x->gen_cap + 63) / 64 * 64;
   x->prefill_chunk = 64;
   int a_max = std::min(S, M + 1);
@@ -119,7 +120,7 @@ static size_t carve(const pd_config *g, char *base, pd_ctx *c) {
   st.steps = cv.take<int32_t>(B); st.n_gen = cv.take<int32_t>(B); st.kv_len = cv.take<int32_t>(B);
   st.n_rows = cv.take<int32_t>(B);
   st.grid = cv.take<int32_t>((size_t)B * S * (M + 1));
-  st.gen_sub = cv.take<int32_t>((size_t)B * x->gen_cap);
+  st.gen_sub = cv.take<uint16_t>((size_t)B * x->gen_stride);
   st.step_tok = cv.take<int32_t>((size_t)B * S); st.force = cv.take<int32_t>((size_t)B * S);
   st.all_done = cv.take<int32_t>(1); st.row_of = cv.take<int32_t>((size_t)B * S);
   x->ctx_tok = cv.take<int32_t>((size_t)B * g->max_ctx);
@@ -185,7 +186,7 @@ extern "C" int pd_create(const pd_config *cfg, const pd_weights *w, void *dev_wo
     lp.n2b = cfg->norm_kind == 0 ? w->norm2_b[l] : nullptr;
   }
   c->prefilled = false; c->host_steps = 0;
-  c->opt_splits = 0; c->opt_graph = 0; c->opt_profile = 0; c->opt_split = 1; c->opt_db = 0;
+  c->opt_splits = 0; c->opt_graph = 0; c->opt_profile = 0; c->opt_split = 1;
   c->graph_exec = nullptr; c->graph_ready = false; c->ev_used = 0; c->h_pinned = nullptr;
   c->B = c->L = c->S = c->dt = c->M = c->time_max = c->A = c->R = 0;
   hipStream_t s = (hipStream_t)hip_stream;
@@ -232,8 +233,6 @@ extern "C" int pd_set_option(pd_ctx *c, int key, int value) {
       c->opt_graph = value ? 1 : 0; drop_graph(c); return PD_OK;
     case PD_OPT_SPLIT_ACT:
       c->opt_split = value ? 1 : 0; drop_graph(c); return PD_OK;
-    case PD_OPT_ATTN_PREFETCH:
-      c->opt_db = value ? 1 : 0; drop_graph(c); return PD_OK;
     case PD_OPT_PROFILE:
       c->opt_profile = value ? 1 : 0; drop_graph(c); c->ev_used = 0; return PD_OK;
     default:

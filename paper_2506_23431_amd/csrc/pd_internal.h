@@ -91,7 +91,8 @@ struct SchedState {
   int32_t *kv_len;    // [B]   L + n_gen
   int32_t *n_rows;    // [B]   rows this step
   int32_t *grid;      // [B][S][M+1] token grid, index 0 = <bos>
-  int32_t *gen_sub;   // [B][gen_cap] subsequence of each generated-side KV slot
+  uint16_t *gen_sub;  // [B][gen_stride] subsequence of each generated-side KV slot; the entry of key slot
+                      // j >= L is j - (L & ~7), so that groups of 8 keys are 16-byte aligned
   int32_t *step_tok;  // [B][S] token appended this step (-1 = none)
   int32_t *force;     // [B][S] teacher-forcing input (-1 = none)
   int32_t *all_done;  // [1]   number of requests that have terminated
@@ -114,7 +115,7 @@ struct pd_ctx {
   std::vector<LayerPtrs> layers;
   int impl;                 // 0: fp32-activation kernels; 1: bf16 MFMA kernels
   // capacities
-  int gen_cap, kv_cap, R_cap, R_pad, vocab_pad, prefill_chunk;
+  int gen_cap, gen_stride, kv_cap, R_cap, R_pad, vocab_pad, prefill_chunk;
   size_t kv_layer_bytes;    // bytes of one K (or V) cache of one layer
   // workspace carve-up
   char *ws; size_t ws_bytes;
@@ -138,7 +139,7 @@ struct pd_ctx {
   bool prefilled;
   int host_steps;           // decode steps enqueued since prefill/reset
   // options
-  int opt_splits, opt_graph, opt_profile, opt_split, opt_db;
+  int opt_splits, opt_graph, opt_profile, opt_split;
   hipGraphExec_t graph_exec; bool graph_ready;
   std::vector<hipEvent_t> ev_pool; size_t ev_used;
   int32_t *h_pinned;        // small pinned host staging buffer

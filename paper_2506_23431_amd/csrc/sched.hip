@@ -37,7 +37,7 @@ int launch_reset_state(pd_ctx *c, hipStream_t s) {
 // fed once more so that its last token enters the KV cache; that row selects no token.
 // ---------------------------------------------------------------------------
 __global__ void k_tick(SchedState st, RowTables rt, int S, int dt, int M, int L, int A,
-                       int time_max, int bos, int gen_cap) {
+                       int time_max, int bos, int gen_cap, int gen_stride) {
   int b = blockIdx.x;
   if (threadIdx.x != 0) return;
   for (int a = 0; a < A; ++a) { rt.flags[b * A + a] = 0; rt.qinfo[b * A + a] = make_int4(0, -1, 0, b); rt.kvinfo[b * A + a] = make_int4(0, b, 0, 0); }
@@ -71,7 +71,7 @@ __global__ void k_tick(SchedState st, RowTables rt, int S, int dt, int M, int L,
       rt.flags[r] = ROW_VALID | (st.fin[b * S + i] ? 0 : ROW_PRODUCE);
       rt.qinfo[r] = make_int4(rt.flags[r], i + 1, L, b);
       rt.kvinfo[r] = make_int4(rt.flags[r], b, L + ng + a, L + (t - 1) + i);
-      st.gen_sub[(size_t)b * gen_cap + ng + a] = i + 1;
+      st.gen_sub[(size_t)b * gen_stride + (L & 7) + ng + a] = (uint16_t)(i + 1);
       st.n_fed[b * S + i] = nt;
       st.row_of[b * S + i] = r;
       ++a;
@@ -82,7 +82,7 @@ __global__ void k_tick(SchedState st, RowTables rt, int S, int dt, int M, int L,
 
 int launch_tick(pd_ctx *c, hipStream_t s) {
   hipLaunchKernelGGL(k_tick, dim3(c->B), dim3(64), 0, s, c->sch, c->rows, c->S, c->dt, c->M, c->L,
-                     c->A, c->time_max, c->cfg.bos_id, c->gen_cap);
+                     c->A, c->time_max, c->cfg.bos_id, c->gen_cap, c->gen_stride);
   PD_CHECK_HIP(hipGetLastError());
   return PD_OK;
 }

@@ -144,8 +144,8 @@ __global__ void k_qkv_post(float *qkv, KT *kc, KT *vc, RowTables rt, const float
 // ---------------------------------------------------------------------------
 template <typename KT>
 __global__ void k_attn(float *out, const float *qkv, const KT *kc, const KT *vc, float *scores,
-                       RowTables rt, const int32_t *kv_len, const int32_t *gen_sub, int kv_override,
-                       int d, int H, int hd, int kv_cap, int gen_cap, int L, float scale) {
+                       RowTables rt, const int32_t *kv_len, const uint16_t *gen_sub, int kv_override,
+                       int d, int H, int hd, int kv_cap, int gen_stride, int L, float scale) {
   extern __shared__ float sm[];     // q[hd] | red[16] | o[blockDim.x]
   float *qs = sm, *red = sm + hd, *osum = sm + hd + 16;
   int r = blockIdx.x, h = blockIdx.y;
@@ -154,13 +154,14 @@ __global__ void k_attn(float *out, const float *qkv, const KT *kc, const KT *vc,
   int n = kv_override >= 0 ? kv_override : kv_len[req];
   const KT *K = kc + ((size_t)req * H + h) * kv_cap * hd;
   const KT *V = vc + ((size_t)req * H + h) * kv_cap * hd;
-  const int32_t *gs = gen_sub + (size_t)req * gen_cap;
+  const uint16_t *gs = gen_sub + (size_t)req * gen_stride;
+  const int L8 = L & ~7;            // entry of key slot j >= L is j - L8
   float *sc = scores + ((size_t)r * H + h) * kv_cap;
   for (int c = threadIdx.x; c < hd; c += blockDim.x) qs[c] = qkv[(size_t)r * 3 * d + h * hd + c];
   __syncthreads();
   float mx = -INFINITY;
   for (int j = threadIdx.x; j < n; j += blockDim.x) {
-    bool vis = j < lim || (j >= L && gs[j - L] <= sub);
+    bool vis = j < lim || (j >= L && (int)gs[j - L8] <= sub);
     float s = -INFINITY;
     if (vis) {
       s = 0.f;
@@ -248,14 +249,14 @@ int simple_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_over
                        (float *)lw.vc, c->rows, cs, d, H, hd, c->kv_cap);
     hipLaunchKernelGGL(k_attn<float>, dim3(R, H), dim3(256), shm, s, att, c->qkv32,
                        (const float *)lw.kc, (const float *)lw.vc, c->scores, c->rows,
-                       c->sch.kv_len, c->sch.gen_sub, kv_override, d, H, hd, c->kv_cap, c->gen_cap,
+                       c->sch.kv_len, c->sch.gen_sub, kv_override, d, H, hd, c->kv_cap, c->gen_stride,
                        c->L, scale);
   } else {
     hipLaunchKernelGGL(k_qkv_post<f16_t>, dim3(R), dim3(256), 0, s, c->qkv32, (f16_t *)lw.kc,
                        (f16_t *)lw.vc, c->rows, cs, d, H, hd, c->kv_cap);
     hipLaunchKernelGGL(k_attn<f16_t>, dim3(R, H), dim3(256), shm, s, att, c->qkv32,
                        (const f16_t *)lw.kc, (const f16_t *)lw.vc, c->scores, c->rows,
-                       c->sch.kv_len, c->sch.gen_sub, kv_override, d, H, hd, c->kv_cap, c->gen_cap,
+                       c->sch.kv_len, c->sch.gen_sub, kv_override, d, H, hd, c->kv_cap, c->gen_stride,
                        c->L, scale);
   }
   PD_CHECK_HIP(hipGetLastError());

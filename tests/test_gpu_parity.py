@@ -216,7 +216,7 @@ def test_full_size_first_iterations(name):
 
 
 def test_options_do_not_change_results():
-    """HIP-graph replay of the step, other split counts, the prefetching attention variant and
+    """HIP-graph replay of the step, other attention split counts and
     plain-bf16 activations: same tokens as the default path on a workload whose top-2 margins are
     comfortably above the bf16 noise; the graph is replayed for every step of three runs with eager
     work and synchronisations in between, and every replayed run is compared."""
@@ -231,7 +231,7 @@ def test_options_do_not_change_results():
         args = (ctx, cfg.n_sub, cfg.delta_t, cfg.sub_tokens, cfg.time_steps)
         base = dec.generate(*args)
         for key, val in ((binding.PD_OPT_USE_GRAPH, 1), (binding.PD_OPT_ATTN_SPLITS, 3),
-                         (binding.PD_OPT_ATTN_SPLITS, 1), (binding.PD_OPT_ATTN_PREFETCH, 1)):
+                         (binding.PD_OPT_ATTN_SPLITS, 1), (binding.PD_OPT_ATTN_SPLITS, 7)):
             dec.set_option(key, val)
             for rep in range(3 if key == binding.PD_OPT_USE_GRAPH else 1):
                 got = dec.generate(*args)
