@@ -17,7 +17,6 @@
 #include "mfma_common.h"
 
 #include <algorithm>
-#include <stdlib.h>
 
 struct AttnArgs {
   const f16_t *q, *q_lo;    // [rows][d] fp16 high / low parts (q_lo NULL: high part only)
@@ -303,7 +302,6 @@ int mfma_attention(pd_ctx *c, const LayerPtrs &lw, int A, int nreq, int req0, in
   a.d = g.d_model; a.H = g.n_head; a.kv_cap = c->kv_cap; a.gen_stride = c->gen_stride; a.L = c->L;
   a.A = A; a.nqg = (A + 15) / 16; a.req0 = req0;
   a.scale_log2 = 1.4426950408889634f / sqrtf((float)g.head_dim);
-  if (getenv("PD_ATTN_NOSPLIT")) a.q_lo = nullptr;   // TEMPORARY experiment switch
   int units = nreq * a.nqg * g.n_head;
   PD_REQUIRE(units <= 4096, PD_EINVAL, "too many (request, head, query group) units: %d", units);
   // the most keys this launch can meet: prefill knows it, decode takes the end of the run

@@ -373,6 +373,104 @@ __global__ __launch_bounds__(64 * NW_K) void k_gemm(GemmArgs a) {
     if (nt0 + t < a.n_tiles) gemm_epilogue<RT, EPI>(a, nt0 + t, acc[t], kvi, lane);
 }
 
+// ---------------------------------------------------------------------------
+// The same product for 1 or 2 row tiles (the decode step of a few requests), where the launch
+// lives for a few microseconds and every load must be in flight from the first cycle on.
+// A wave owns NT column tiles and a share of K (a.k_share k-tiles, normally one chunk of U).  Per
+// chunk it requests everything first: the weight fragments of its tiles and the high- and low-part
+// activation fragments of the row tiles, into registers of their own; only then the multiplies
+// run.  A share that is not a multiple of U ends with chunks of 4, 2 and 1 k-tiles, so that no
+// load is ever conditional.
+// ---------------------------------------------------------------------------
+template <int RT, int NT, int U, bool SPLIT>
+__device__ __forceinline__ void gemm_chunk(floatx4 (&acc)[NT][RT][2], const uint4 *wp, const uint4 *xp,
+                                           const uint4 *xl, size_t KT, const int (&tile)[NT], int kt) {
+  Frag wa[NT][U], xh[RT][U], xo[SPLIT ? RT : 1][U];
+#pragma unroll
+  for (int i = 0; i < RT; ++i)
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      xh[i][u].u = xp[((size_t)i * KT + kt + u) * 64];
+      if (SPLIT) xo[i][u].u = xl[((size_t)i * KT + kt + u) * 64];
+    }
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int u = 0; u < U; ++u) wa[t][u].u = wp[((size_t)tile[t] * KT + kt + u) * 64];
+  __builtin_amdgcn_sched_barrier(0);          // every request above is issued before the first multiply
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int i = 0; i < RT; ++i) {
+        // two accumulators per tile: the high- and low-part products do not wait for each other
+        acc[t][i][0] = mfma16(wa[t][u], xh[i][u], acc[t][i][0]);
+        if (SPLIT) acc[t][i][1] = mfma16(wa[t][u], xo[i][u], acc[t][i][1]);
+      }
+}
+
+template <int RT, int NT, int NW_K, int U, int EPI, bool SPLIT>
+__global__ __launch_bounds__(64 * NW_K) void k_gemm_s(GemmArgs a) {
+  __shared__ floatx4 red[NW_K > 1 ? NW_K * NT * RT * 64 : 1];
+  const int wk = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int nt0 = blockIdx.x * NT;
+  const int m = lane & 15;
+  const int KT = a.K >> 5;
+  // waves along K: NW_K in this block times gridDim.y blocks (EPI_RESID only)
+  const int gk = blockIdx.y * NW_K + wk;
+  const int kt0 = min(gk * a.k_share, KT), kt1 = min(kt0 + a.k_share, KT);
+  // row data of the KV-append epilogue, requested now so that it arrives with the weights
+  int4 kvi[(EPI == EPI_QKV || EPI == EPI_QKV_ROPE) ? RT : 1];
+  if (EPI == EPI_QKV || EPI == EPI_QKV_ROPE) {
+#pragma unroll
+    for (int i = 0; i < RT; ++i) kvi[i] = a.rt.kvinfo[i * 16 + m];
+  }
+  int tile[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) tile[t] = min(nt0 + t, a.n_tiles - 1);   // tiles past the end repeat the last one
+  floatx4 acc2[NT][RT][2];
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int i = 0; i < RT; ++i) acc2[t][i][0] = acc2[t][i][1] = floatx4{0.f, 0.f, 0.f, 0.f};
+  const uint4 *wp = (const uint4 *)a.W + lane;
+  const uint4 *xp = (const uint4 *)a.xn + lane;
+  const uint4 *xl = SPLIT ? (const uint4 *)a.xn_lo + lane : nullptr;
+  int kt = kt0;
+  while (kt + U <= kt1) { gemm_chunk<RT, NT, U, SPLIT>(acc2, wp, xp, xl, KT, tile, kt); kt += U; }
+  if (U > 4 && kt + 4 <= kt1) { gemm_chunk<RT, NT, 4, SPLIT>(acc2, wp, xp, xl, KT, tile, kt); kt += 4; }
+  if (U > 2 && kt + 2 <= kt1) { gemm_chunk<RT, NT, 2, SPLIT>(acc2, wp, xp, xl, KT, tile, kt); kt += 2; }
+  if (U > 1 && kt < kt1) gemm_chunk<RT, NT, 1, SPLIT>(acc2, wp, xp, xl, KT, tile, kt);
+  floatx4 acc[NT][RT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int i = 0; i < RT; ++i) acc[t][i] = SPLIT ? acc2[t][i][0] + acc2[t][i][1] : acc2[t][i][0];
+  if (NW_K > 1) {
+    // every wave leaves its partial tiles in LDS; wave t then sums and finishes column tile t
+    static_assert(NW_K == 1 || NW_K >= NT, "one finishing wave per column tile");
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int i = 0; i < RT; ++i) red[((wk * NT + t) * RT + i) * 64 + lane] = acc[t][i];
+    __syncthreads();
+    if (wk >= NT || nt0 + wk >= a.n_tiles) return;
+    floatx4 sum[RT];
+#pragma unroll
+    for (int i = 0; i < RT; ++i) sum[i] = red[((0 * NT + wk) * RT + i) * 64 + lane];
+#pragma unroll
+    for (int w = 1; w < NW_K; ++w)
+#pragma unroll
+      for (int i = 0; i < RT; ++i) sum[i] += red[((w * NT + wk) * RT + i) * 64 + lane];
+    gemm_epilogue<RT, EPI>(a, nt0 + wk, sum, kvi, lane);
+  } else {
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+      if (nt0 + t < a.n_tiles) gemm_epilogue<RT, EPI>(a, nt0 + t, acc[t], kvi, lane);
+  }
+}
+
 // second stage of the argmax: one block per row over the per-tile winners
 __global__ __launch_bounds__(256) void k_lm_reduce(int32_t *row_argmax, const float *part_val,
                                                    const int32_t *part_idx, int n_tiles, int rows,
@@ -449,6 +547,49 @@ static int launch_gemm_rt(const GemmArgs &a, hipStream_t s) {
   return PD_OK;
 }
 
+// 1 or 2 row tiles.  Two column tiles per wave when that still leaves 128 or more blocks: the
+// activation fragments (2 KiB per k-tile with the low parts) are then requested once for 2 KiB of
+// weights instead of 1 KiB, and the vector-memory pipeline of a compute unit, which every request
+// occupies for the same time whether it is served by HBM or by L2, has a third less to do.  A
+// wave's share of K is at most 8 k-tiles (two requests of 4), less when the launch would
+// otherwise have fewer than about 1500 waves; up to 16 waves along K per block are summed
+// through LDS and, for the residual projections, K is also cut into slices over blocks that the
+// next norm kernel sums.
+template <int RT, int NT, int EPI, bool SPLIT>
+static int launch_gemm_small_nt(GemmArgs a, int ks, hipStream_t s) {
+  constexpr int U = 4;
+  int KT = a.K / 32, groups = (a.n_tiles + NT - 1) / NT;
+  int per_block = (KT + ks - 1) / ks;          // k-tiles of one block
+  int nwk = NT;
+  while (nwk < 16 && (per_block + nwk - 1) / nwk > 8) nwk *= 2;
+  while (nwk < 16 && (long)groups * ks * nwk < 1500 && (per_block + nwk - 1) / nwk > 2) nwk *= 2;
+  a.k_share = (per_block + nwk - 1) / nwk;
+  dim3 grid(groups, ks);
+#define PD_LAUNCH(NWK) \
+  hipLaunchKernelGGL((k_gemm_s<RT, NT, (NWK < NT ? NT : NWK), U, EPI, SPLIT>), grid, \
+                     dim3(64 * (NWK < NT ? NT : NWK)), 0, s, a)
+  switch (nwk) {
+    case 1: PD_LAUNCH(1); break;
+    case 2: PD_LAUNCH(2); break;
+    case 4: PD_LAUNCH(4); break;
+    case 8: PD_LAUNCH(8); break;
+    default: PD_LAUNCH(16); break;
+  }
+#undef PD_LAUNCH
+  PD_CHECK_HIP(hipGetLastError());
+  if (EPI == EPI_RESID && a.parts_out) *a.parts_out = ks;
+  return PD_OK;
+}
+
+template <int RT, int EPI, bool SPLIT>
+static int launch_gemm_small(const GemmArgs &a, hipStream_t s) {
+  int KT = a.K / 32, ks = 1;
+  if (EPI == EPI_RESID)    // slices while the launch has fewer than 256 blocks and a slice keeps 8 k-tiles
+    while (ks < a.max_parts && ((a.n_tiles + 1) / 2) * ks < 256 && KT / (2 * ks) >= 8) ks *= 2;
+  if (RT == 1 && ((a.n_tiles + 1) / 2) * ks >= 128) return launch_gemm_small_nt<RT, 2, EPI, SPLIT>(a, ks, s);
+  return launch_gemm_small_nt<RT, 1, EPI, SPLIT>(a, ks, s);
+}
+
 int mfma_gemm_row_tiles(int rows) {
   int rt = (rows + 15) / 16;
   return (rt <= 1 ? 1 : rt <= 2 ? 2 : rt <= 4 ? 4 : rt <= 5 ? 5 : 8) * 16;
@@ -457,8 +598,8 @@ int mfma_gemm_row_tiles(int rows) {
 template <int EPI, bool SPLIT>
 static int launch_gemm_split(const GemmArgs &a, int rows, hipStream_t s) {
   switch (mfma_gemm_row_tiles(rows)) {
-    case 16: return launch_gemm_rt<1, 1, EPI, SPLIT>(a, s);
-    case 32: return launch_gemm_rt<2, 1, EPI, SPLIT>(a, s);
+    case 16: return launch_gemm_small<1, EPI, SPLIT>(a, s);
+    case 32: return launch_gemm_small<2, EPI, SPLIT>(a, s);
     case 64: return launch_gemm_rt<4, 2, EPI, SPLIT>(a, s);
     case 80: return launch_gemm_rt<5, 4, EPI, SPLIT>(a, s);
     default: return launch_gemm_rt<8, 4, EPI, SPLIT>(a, s);

@@ -103,6 +103,7 @@ struct GemmArgs {
   const bf16_t *xn;      // [16*RT][K] bf16, fragment-major: activations (high part)
   const bf16_t *xn_lo;   // same shape: bf16(x - high part), or NULL to use the high part only
   int K, n_tiles, R;
+  int k_share;           // k-tiles per wave along K (set by the launch)
   // epilogue
   float *x;              // EPI_RESID: split-K slices of y, [slices][part_stride], row-major [rows][ld]
   size_t part_stride; int max_parts; int *parts_out;   // EPI_RESID: slice stride, limit, slices written
