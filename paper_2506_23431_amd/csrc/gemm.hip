@@ -81,11 +81,11 @@ __device__ __forceinline__ float block_sum256(float v, float *sh) {
   return sh[0] + sh[1] + sh[2] + sh[3];
 }
 
-template <int NG>     // 8-value granules per thread: d <= 2048 * NG
+template <int NG, int NP>     // 8-value granules per thread: d <= 2048 * NG; NP pending slices
 __global__ __launch_bounds__(256) void k_norm_bf16(bf16_t *xn, bf16_t *xn_lo, const float *x, const float *g,
                                                    const float *b, int d, int kind, float eps,
                                                    const int32_t *flags, int R, float *xw,
-                                                   const float *ypart, int nparts, size_t part_stride) {
+                                                   const float *ypart, size_t part_stride) {
   __shared__ float sh[4];
   int r = blockIdx.x;
   int fl = r < R ? flags[r] : 0;
@@ -100,12 +100,15 @@ __global__ __launch_bounds__(256) void k_norm_bf16(bf16_t *xn, bf16_t *xn_lo, co
       float4 t = in ? *(const float4 *)(xr + c + 4 * h) : make_float4(0.f, 0.f, 0.f, 0.f);
       float4 tg = in ? *(const float4 *)(g + c + 4 * h) : make_float4(0.f, 0.f, 0.f, 0.f);
       float4 tb = (in && kind == 0 && b) ? *(const float4 *)(b + c + 4 * h) : make_float4(0.f, 0.f, 0.f, 0.f);
-      for (int pp = 0; pp < nparts; ++pp) {      // pending split-K slices of the last projection
-        float4 y = in ? *(const float4 *)(ypart + pp * part_stride + (size_t)r * d + c + 4 * h)
-                      : make_float4(0.f, 0.f, 0.f, 0.f);
-        t.x += y.x; t.y += y.y; t.z += y.z; t.w += y.w;
-      }
-      if (nparts > 0 && in && r < R) *(float4 *)(xw + (size_t)r * d + c + 4 * h) = t;
+      // pending split-K slices of the last projection: requested together with everything else
+      float4 y[NP > 0 ? NP : 1];
+#pragma unroll
+      for (int pp = 0; pp < NP; ++pp)
+        y[pp] = in ? *(const float4 *)(ypart + pp * part_stride + (size_t)r * d + c + 4 * h)
+                   : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+      for (int pp = 0; pp < NP; ++pp) { t.x += y[pp].x; t.y += y[pp].y; t.z += y[pp].z; t.w += y[pp].w; }
+      if (NP > 0 && in && r < R) *(float4 *)(xw + (size_t)r * d + c + 4 * h) = t;
       v[i][4 * h] = t.x; v[i][4 * h + 1] = t.y; v[i][4 * h + 2] = t.z; v[i][4 * h + 3] = t.w;
       gv[i][4 * h] = tg.x; gv[i][4 * h + 1] = tg.y; gv[i][4 * h + 2] = tg.z; gv[i][4 * h + 3] = tg.w;
       bv[i][4 * h] = tb.x; bv[i][4 * h + 1] = tb.y; bv[i][4 * h + 2] = tb.z; bv[i][4 * h + 3] = tb.w;
@@ -151,13 +154,19 @@ int mfma_norm(pd_ctx *c, const float *gain, const float *bias, int R, hipStream_
   bf16_t *xn = (bf16_t *)c->xn;
   const pd_config &g = c->cfg;
   PD_REQUIRE(d <= 2048 * 4, PD_EINVAL, "d_model %d too large for the norm kernel", d);
-#define PD_NORM(V)                                                                               \
-  hipLaunchKernelGGL(k_norm_bf16<V>, dim3(rows), dim3(256), 0, s, xn, mfma_lo(c, xn, d), c->x, gain, bias, d, \
-                     g.norm_kind, g.norm_eps, c->rows.flags, R, c->x, c->ypart, c->pend_parts,         \
-                     (size_t)c->R_pad * d)
-  if (d <= 2048) PD_NORM(1);
-  else if (d <= 4096) PD_NORM(2);
-  else PD_NORM(4);
+#define PD_NORM(V, P)                                                                            \
+  hipLaunchKernelGGL((k_norm_bf16<V, P>), dim3(rows), dim3(256), 0, s, xn, mfma_lo(c, xn, d), c->x, gain, bias, \
+                     d, g.norm_kind, g.norm_eps, c->rows.flags, R, c->x, c->ypart, (size_t)c->R_pad * d)
+#define PD_NORM_P(V)                                                                             \
+  switch (c->pend_parts) {                                                                       \
+    case 0: PD_NORM(V, 0); break;                                                                \
+    case 1: PD_NORM(V, 1); break;                                                                \
+    case 2: PD_NORM(V, 2); break;                                                                \
+    case 4: PD_NORM(V, 4); break;                                                                \
+    default: pd_set_error("unsupported number of pending slices: %d", c->pend_parts); return PD_EINVAL; \
+  }
+  if (d <= 2048) { PD_NORM_P(1) } else if (d <= 4096) { PD_NORM_P(2) } else { PD_NORM_P(4) }
+#undef PD_NORM_P
 #undef PD_NORM
   PD_CHECK_HIP(hipGetLastError());
   c->pend_parts = 0;
