@@ -107,6 +107,11 @@ __global__ __launch_bounds__(256, 3) void k_attn_mfma(AttnArgs a) {
   int reach = qvalid ? (n_keys > a.L && q_sub >= 1 ? n_keys : min(q_lim, n_keys)) : 0;
   for (int o = 1; o < 16; o <<= 1) reach = max(reach, __shfl_xor(reach, o));
   const int end = __builtin_amdgcn_readfirstlane(min(a.nblk_static, (reach + 31) >> 5));
+  // keys below lim_all are visible to every query of the group that has a token (the others are
+  // never written, whatever they compute): blocks below it skip the per-key test
+  int lim_q = qvalid ? min(q_lim, a.L) : 0x7fffffff;
+  for (int o = 1; o < 16; o <<= 1) lim_q = min(lim_q, __shfl_xor(lim_q, o));
+  const int lim_all = __builtin_amdgcn_readfirstlane(lim_q);
 
   float m_run = -INFINITY, l_run = 0.f;
   floatx4 o_acc[NHB];
@@ -139,43 +144,46 @@ __global__ __launch_bounds__(256, 3) void k_attn_mfma(AttnArgs a) {
     const bool more = kn < end;
     if (more) load_k(kn);
     // lane (n, g), tile t, register j  <->  key kb*32 + 8g + 4t + j
-    int key0 = kb * 32 + 8 * g;
+    const int key0 = kb * 32 + 8 * g;
     float sv[8];
-    bool tail = key0 + 8 > a.L || key0 + 8 > q_lim;     // needs the per-key test
-    float mloc = -INFINITY;
+    if (kb * 32 + 32 <= lim_all) {
+      // every query of the group sees the whole block (the same for all lanes of the wave)
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      int key = key0 + e;
-      bool vis = true;
-      if (tail) vis = key < q_lim || (key >= a.L && key < n_keys && (int)tg.s[e] <= q_sub);
-      float v = vis ? s[e >> 2][e & 3] * a.scale_log2 : -INFINITY;
-      sv[e] = v;
-      mloc = fmaxf(mloc, v);
+      for (int e = 0; e < 8; ++e) sv[e] = s[e >> 2][e & 3] * a.scale_log2;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        int key = key0 + e;
+        bool vis = (key < q_lim) | ((key >= a.L) & (key < n_keys) & ((int)tg.s[e] <= q_sub));
+        sv[e] = vis ? s[e >> 2][e & 3] * a.scale_log2 : -INFINITY;
+      }
     }
+    float mloc = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
     mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
     mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-    float m_new = fmaxf(m_run, mloc);
-    float alpha = m_new == -INFINITY ? 1.f : exp2f(m_run - m_new);
+    const float m_new = fmaxf(m_run, mloc);
+    // while nothing is visible yet the reference is 0 instead of -inf: every exponential below is
+    // then exp2(-inf) = 0 and never exp2(NaN)
+    const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_ref);
     float p[8], psum = 0.f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      p[e] = sv[e] == -INFINITY ? 0.f : exp2f(sv[e] - m_new);
+      p[e] = __builtin_amdgcn_exp2f(sv[e] - m_ref);
       psum += p[e];
     }
     l_run = l_run * alpha + psum;
     m_run = m_new;
-    Frag pf, pl;
+    // probabilities enter the matrix core as fp16 (the same 11 significant bits as the values they multiply)
+    Frag pf;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      pf.hh[e] = (f16_t)p[e];
-      if (SPLIT) pl.hh[e] = (f16_t)(p[e] - (float)pf.hh[e]);
+    for (int e = 0; e < 8; ++e) pf.hh[e] = (f16_t)p[e];
+    if (__any(alpha != 1.f)) {                // the running maximum of some query moved: rescale
+#pragma unroll
+      for (int i = 0; i < NHB; ++i) o_acc[i] *= alpha;
     }
 #pragma unroll
-    for (int i = 0; i < NHB; ++i) {
-      o_acc[i] *= alpha;
-      o_acc[i] = mfma16h(vf[i], pf, o_acc[i]);
-      if (SPLIT) o_acc[i] = mfma16h(vf[i], pl, o_acc[i]);
-    }
+    for (int i = 0; i < NHB; ++i) o_acc[i] = mfma16h(vf[i], pf, o_acc[i]);
     if (more) load_v(kn);
     kb = kn;
   }
