@@ -12,7 +12,8 @@ context pass (prefill) is outside the metric and reported separately.
 
 Prints ONE JSON line: generated tokens/s over exactly K steps, plus
   roofline      achieved HBM GB/s of the attention kernel (algorithmic bytes per launch /
-                average launch duration from HIP events on the launch stream) vs 8 TB/s
+                average launch duration from HIP events attached to its dispatches) vs 8 TB/s,
+                beside what a kernel that only reads the same bytes reaches
   cpu_baseline  the CPU oracle timed on the host cores on a bounded sample
 """
 
@@ -147,15 +148,30 @@ def main():
         dec.decode_steps(K)
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
-        # second pass over the same K iterations with HIP events around every attention launch
+        # second pass over the same K iterations with HIP events around every launch of the attention
+        # kernel (the one that streams the keys and values); third pass: around the kernel and the
+        # small kernel that merges its partial results
         dec.set_option(binding.PD_OPT_USE_GRAPH, 0)
         dec.set_option(binding.PD_OPT_PROFILE, 1)
         dec.reset_decode()
         dec.decode_steps(K)
         torch.cuda.synchronize()
         attn_us, attn_launches = dec.profile_read()
+        dec.set_option(binding.PD_OPT_PROFILE, 2)
+        dec.reset_decode()
+        dec.decode_steps(K)
+        torch.cuda.synchronize()
+        pair_us, _ = dec.profile_read()
         dec.set_option(binding.PD_OPT_PROFILE, 0)
         dec.close()
+        # what a kernel that only reads reaches on this device, at the size of one attention launch
+        buf = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        buf.fill_(1)
+        torch.cuda.synchronize()
+        chunk = int(attention_bytes(cfg, K)) // 4096 * 4096
+        read_gbs = binding.measure_read_bandwidth(buf.data_ptr(), buf.numel(), chunk, 200,
+                                                  torch.cuda.current_stream().cuda_stream)
+        del buf
 
     tokens = cfg.batch * sum(producing(cfg, t) for t in range(1, K + 1))
     abytes = attention_bytes(cfg, K)
@@ -177,12 +193,16 @@ def main():
                    "prefill_s": prefill_s, "hip_graph": bool(args.graph)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": "k_attn_mfma + k_attn_merge (masked multi-query attention, one launch pair "
+                     "kernel": "k_attn_mfma (masked multi-query attention over the KV cache, one launch "
                                "per layer per step)",
                      "algorithmic_bytes_per_launch": abytes, "avg_launch_us": attn_us,
                      "launches": attn_launches,
-                     "timing": "HIP events on the launch stream around every attention launch, in a second "
-                               "pass over the same K iterations"},
+                     "timing": "HIP start and stop events attached to every dispatch of the kernel on the "
+                               "launch stream, in a second pass over the same K iterations",
+                     "with_merge_kernel_us": pair_us,
+                     "plain_read_same_bytes": {"GB/s": read_gbs, "frac_of_peak": read_gbs / HBM_PEAK_GBS,
+                                               "note": "a kernel that only reads this many bytes, launched "
+                                                       "back to back on the same device"}},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, weights, ctx)

@@ -136,8 +136,10 @@ int pd_reset_decode(pd_ctx *ctx, void *hip_stream);
 /* Tunables and instrumentation.  Keys:
  *   PD_OPT_ATTN_SPLITS   work-groups per (request, head) in the attention kernel (0 = auto)
  *   PD_OPT_USE_GRAPH     1: replay each decode step from a captured HIP graph
- *   PD_OPT_PROFILE       1: bracket the attention kernel of every layer with HIP events
- *                        (adds event overhead to the step; for measurement only)
+ *   PD_OPT_PROFILE       1: bracket the attention kernel of every layer (the kernel that streams the
+ *                        keys and values; not the small kernel that merges its partial results) with
+ *                        HIP events;  2: bracket the pair of kernels  (adds event overhead to the
+ *                        step; for measurement only)
  *   PD_OPT_SPLIT_ACT     bf16 path: 1 (default) carries every activation that enters a matrix
  *                        multiply as a pair of bf16 values (about 16 mantissa bits) and runs two
  *                        matrix-core passes per weight / key / value fragment; 0 uses plain bf16
@@ -150,9 +152,18 @@ int pd_reset_decode(pd_ctx *ctx, void *hip_stream);
 #define PD_OPT_SPLIT_ACT   4
 int pd_set_option(pd_ctx *ctx, int key, int value);
 
-/* Average duration in microseconds of the attention-kernel launches bracketed since
- * the last call (PD_OPT_PROFILE), and how many there were.  Synchronises. */
+/* Average time in microseconds between the two events of the brackets recorded since the
+ * last call (PD_OPT_PROFILE), and how many brackets there were.  Synchronises. */
 int pd_profile_read(pd_ctx *ctx, double *attn_avg_us, int32_t *attn_launches);
+
+/* Measurement aid, independent of any pd_ctx: bandwidth in GB/s (1e9 bytes/s) of a kernel that only
+ * reads, the ceiling a memory-bound kernel of this size can reach on this device.  Reads `chunk_bytes`
+ * per launch from `dev_buf` (DEVICE, 16-byte aligned, `buf_bytes` long; a different chunk every
+ * launch, so make the buffer several times larger than the 256 MB last-level cache), `iters` launches
+ * back to back between two HIP events; the time includes the gaps between launches, as it does for
+ * the kernels of a decode step.  The last 256 bytes of the buffer may be written.  Synchronises. */
+int pd_measure_read_bandwidth(const void *dev_buf, size_t buf_bytes, size_t chunk_bytes, int iters,
+                              void *hip_stream, double *gb_per_s);
 
 /* Message for the last error on this thread (static storage, never NULL). */
 const char *pd_last_error(void);

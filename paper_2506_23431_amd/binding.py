@@ -16,7 +16,7 @@ PD_OPT_ATTN_SPLITS, PD_OPT_USE_GRAPH, PD_OPT_PROFILE, PD_OPT_SPLIT_ACT = 1, 2, 3
 
 EXPORTS = ["pd_workspace_bytes", "pd_create", "pd_destroy", "pd_prefill_context", "pd_decode_step",
            "pd_generate", "pd_decode_steps", "pd_reset_decode", "pd_set_option", "pd_profile_read",
-           "pd_last_error"]
+           "pd_measure_read_bandwidth", "pd_last_error"]
 
 
 class PdError(RuntimeError):
@@ -62,6 +62,7 @@ def load():
     lib.pd_reset_decode.argtypes = [vp, vp]
     lib.pd_set_option.argtypes = [vp, C.c_int, C.c_int]
     lib.pd_profile_read.argtypes = [vp, C.POINTER(C.c_double), i32p]
+    lib.pd_measure_read_bandwidth.argtypes = [vp, C.c_size_t, C.c_size_t, C.c_int, vp, C.POINTER(C.c_double)]
     lib.pd_last_error.restype = C.c_char_p
     for name in EXPORTS:
         getattr(lib, name)
@@ -208,3 +209,11 @@ class PipelinedDecoder:
         us, n = C.c_double(0), C.c_int32(0)
         _check(self.lib.pd_profile_read(self.ctx, C.byref(us), C.byref(n)))
         return us.value, n.value
+
+
+def measure_read_bandwidth(dev_ptr, buf_bytes, chunk_bytes, iters, stream=None):
+    """GB/s of a kernel that only reads `chunk_bytes` per launch from the device buffer at `dev_ptr`."""
+    out = C.c_double(0)
+    _check(load().pd_measure_read_bandwidth(C.c_void_p(dev_ptr), buf_bytes, chunk_bytes, iters,
+                                            C.c_void_p(stream or 0), C.byref(out)))
+    return out.value

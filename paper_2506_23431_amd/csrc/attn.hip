@@ -16,6 +16,8 @@
 // write (max, sum, O) partials that a second, tiny kernel merges by log-sum-exp.
 #include "mfma_common.h"
 
+#include <hip/hip_ext.h>
+
 #include <algorithm>
 
 struct AttnArgs {
@@ -317,18 +319,27 @@ int mfma_attention(pd_ctx *c, const LayerPtrs &lw, int A, int nreq, int req0, in
   a.nblk_static = std::min((n_keys + 31) / 32, c->kv_cap / 32);
   a.nsplit = pick_splits(c, units, a.nblk_static);
   dim3 grid(a.nsplit, g.n_head, nreq * a.nqg);
+  // measurement: mode 1 attaches a start and a stop event to the dispatch of the main kernel itself
+  // (their difference is the kernel's execution time), mode 2 records events before the main kernel
+  // and after the merge kernel
   bool prof = c->opt_profile && kv_override < 0;
+  hipEvent_t ev0 = nullptr, ev1 = nullptr;
   if (prof) {
     while (c->ev_pool.size() < c->ev_used + 2) {
       hipEvent_t ev;
       PD_CHECK_HIP(hipEventCreate(&ev));
       c->ev_pool.push_back(ev);
     }
-    PD_CHECK_HIP(hipEventRecord(c->ev_pool[c->ev_used], s));
+    ev0 = c->ev_pool[c->ev_used];
+    ev1 = c->ev_pool[c->ev_used + 1];
+    if (c->opt_profile == 2) PD_CHECK_HIP(hipEventRecord(ev0, s));
   }
+  const bool attach = prof && c->opt_profile == 1;
 #define PD_ATTN(HDV)                                                                        \
   do {                                                                                      \
-    if (a.q_lo) hipLaunchKernelGGL((k_attn_mfma<HDV, true>), grid, dim3(256), 0, s, a);     \
+    if (attach && a.q_lo) hipExtLaunchKernelGGL((k_attn_mfma<HDV, true>), grid, dim3(256), 0, s, ev0, ev1, 0, a);  \
+    else if (attach) hipExtLaunchKernelGGL((k_attn_mfma<HDV, false>), grid, dim3(256), 0, s, ev0, ev1, 0, a);      \
+    else if (a.q_lo) hipLaunchKernelGGL((k_attn_mfma<HDV, true>), grid, dim3(256), 0, s, a);  \
     else hipLaunchKernelGGL((k_attn_mfma<HDV, false>), grid, dim3(256), 0, s, a);           \
     if (a.nsplit > 1)                                                                       \
       hipLaunchKernelGGL(k_attn_merge<HDV>, dim3(units, HDV / 16), dim3(256), 0, s, a);            \
@@ -343,7 +354,7 @@ int mfma_attention(pd_ctx *c, const LayerPtrs &lw, int A, int nreq, int req0, in
 #undef PD_ATTN
   PD_CHECK_HIP(hipGetLastError());
   if (prof) {
-    PD_CHECK_HIP(hipEventRecord(c->ev_pool[c->ev_used + 1], s));
+    if (c->opt_profile != 1) PD_CHECK_HIP(hipEventRecord(c->ev_pool[c->ev_used + 1], s));
     c->ev_used += 2;
   }
   return PD_OK;

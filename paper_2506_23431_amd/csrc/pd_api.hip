@@ -234,7 +234,7 @@ extern "C" int pd_set_option(pd_ctx *c, int key, int value) {
     case PD_OPT_SPLIT_ACT:
       c->opt_split = value ? 1 : 0; drop_graph(c); return PD_OK;
     case PD_OPT_PROFILE:
-      c->opt_profile = value ? 1 : 0; drop_graph(c); c->ev_used = 0; return PD_OK;
+      c->opt_profile = value == 2 ? 2 : (value ? 1 : 0); drop_graph(c); c->ev_used = 0; return PD_OK;
     default:
       pd_set_error("unknown option key %d", key);
       return PD_EINVAL;
@@ -445,5 +445,54 @@ extern "C" int pd_generate(pd_ctx *c, const int32_t *ctx_tokens, int B, int L, i
         out_tokens[bi * M + j] = j < n ? grid[bi * (M + 1) + 1 + j] : -1;
     }
   }
+  return PD_OK;
+}
+
+// ---------------------------------------------------------------------------
+// plain streaming read: the bandwidth a kernel that does nothing but read can reach
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_stream_read(const uint4 *p, size_t n, unsigned *sink) {
+  size_t base = (size_t)blockIdx.x * 2048 + threadIdx.x;
+  uint4 v[8];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    size_t j = base + u * 256;
+    v[u] = p[j < n ? j : n - 1];
+  }
+  unsigned acc = 0;
+#pragma unroll
+  for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+  if (acc == 0x9e3779b9u) *sink = acc;       // keeps the loads alive; practically never taken
+}
+
+extern "C" int pd_measure_read_bandwidth(const void *dev_buf, size_t buf_bytes, size_t chunk_bytes, int iters,
+                                         void *hip_stream, double *gb_per_s) {
+  PD_REQUIRE(dev_buf && gb_per_s && iters >= 1, PD_EINVAL, "NULL buffer / result or iters < 1");
+  PD_REQUIRE(chunk_bytes >= 4096 && chunk_bytes % 16 == 0 && chunk_bytes + 256 <= buf_bytes, PD_EINVAL,
+             "chunk_bytes must be a multiple of 16, at least 4096 and smaller than the buffer");
+  PD_REQUIRE(((uintptr_t)dev_buf & 15) == 0, PD_EINVAL, "buffer must be 16-byte aligned");
+  hipStream_t s = (hipStream_t)hip_stream;
+  hipEvent_t e0, e1;
+  PD_CHECK_HIP(hipEventCreate(&e0));
+  PD_CHECK_HIP(hipEventCreate(&e1));
+  size_t n16 = chunk_bytes / 16, slots = (buf_bytes - 256) / chunk_bytes;
+  unsigned *sink = (unsigned *)((char *)dev_buf + (buf_bytes - 256) / 16 * 16);   // last bytes: never read
+  unsigned nb = (unsigned)((n16 + 2047) / 2048);
+  auto run = [&](int n) {
+    for (int i = 0; i < n; ++i)      // a different chunk every launch, so that no cache serves it
+      hipLaunchKernelGGL(k_stream_read, dim3(nb), dim3(256), 0, s,
+                         (const uint4 *)((const char *)dev_buf + (size_t)(i % slots) * chunk_bytes), n16, sink);
+  };
+  run(3);
+  PD_CHECK_HIP(hipEventRecord(e0, s));
+  run(iters);
+  PD_CHECK_HIP(hipEventRecord(e1, s));
+  PD_CHECK_HIP(hipEventSynchronize(e1));
+  float ms = 0.f;
+  PD_CHECK_HIP(hipEventElapsedTime(&ms, e0, e1));
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  PD_CHECK_HIP(hipGetLastError());
+  *gb_per_s = (double)chunk_bytes * iters / (ms * 1e-3) * 1e-9;
   return PD_OK;
 }
