@@ -81,23 +81,48 @@ __device__ __forceinline__ float block_sum256(float v, float *sh) {
   return sh[0] + sh[1] + sh[2] + sh[3];
 }
 
-template <int NG, int NP>     // 8-value granules per thread: d <= 2048 * NG; NP pending slices
+// EMB: the row is not read from x but gathered from the embedding tables (first norm of a step:
+// x = E_tok[token] (+ E_pos[position]), zero for rows without a token) and written to x.
+template <int NG, int NP, bool EMB>     // 8-value granules per thread: d <= 2048 * NG; NP pending slices
 __global__ __launch_bounds__(256) void k_norm_bf16(bf16_t *xn, bf16_t *xn_lo, const float *x, const float *g,
                                                    const float *b, int d, int kind, float eps,
                                                    const int32_t *flags, int R, float *xw,
-                                                   const float *ypart, size_t part_stride) {
+                                                   const float *ypart, size_t part_stride,
+                                                   const bf16_t *tok_emb, const bf16_t *pos_emb,
+                                                   const int32_t *tok, const int32_t *pos) {
   __shared__ float sh[4];
   int r = blockIdx.x;
   int fl = r < R ? flags[r] : 0;
   const float *xr = x + (size_t)r * d;
   float v[NG][8], gv[NG][8], bv[NG][8];
+  const bf16_t *te = nullptr, *pe = nullptr;
+  if (EMB) {
+    bool has = fl & ROW_VALID;
+    te = tok_emb + (has ? (size_t)tok[r] * d : 0);
+    pe = pos_emb ? pos_emb + (has ? (size_t)pos[r] * d : 0) : nullptr;
+  }
 #pragma unroll
   for (int i = 0; i < NG; ++i) {
     int c = (threadIdx.x + i * 256) * 8;
     bool in = c < d;
+    Frag et, ep;
+    if (EMB) {
+      et.u = in ? *(const uint4 *)(te + c) : make_uint4(0, 0, 0, 0);
+      ep.u = (in && pe) ? *(const uint4 *)(pe + c) : make_uint4(0, 0, 0, 0);
+    }
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      float4 t = in ? *(const float4 *)(xr + c + 4 * h) : make_float4(0.f, 0.f, 0.f, 0.f);
+      float4 t;
+      if (EMB) {
+        bool has = fl & ROW_VALID;
+        t.x = has ? bf16_to_f32(et.h[4 * h]) + bf16_to_f32(ep.h[4 * h]) : 0.f;
+        t.y = has ? bf16_to_f32(et.h[4 * h + 1]) + bf16_to_f32(ep.h[4 * h + 1]) : 0.f;
+        t.z = has ? bf16_to_f32(et.h[4 * h + 2]) + bf16_to_f32(ep.h[4 * h + 2]) : 0.f;
+        t.w = has ? bf16_to_f32(et.h[4 * h + 3]) + bf16_to_f32(ep.h[4 * h + 3]) : 0.f;
+        if (in && r < R) *(float4 *)(xw + (size_t)r * d + c + 4 * h) = t;
+      } else {
+        t = in ? *(const float4 *)(xr + c + 4 * h) : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
       float4 tg = in ? *(const float4 *)(g + c + 4 * h) : make_float4(0.f, 0.f, 0.f, 0.f);
       float4 tb = (in && kind == 0 && b) ? *(const float4 *)(b + c + 4 * h) : make_float4(0.f, 0.f, 0.f, 0.f);
       // pending split-K slices of the last projection: requested together with everything else
@@ -154,15 +179,17 @@ int mfma_norm(pd_ctx *c, const float *gain, const float *bias, int R, hipStream_
   bf16_t *xn = (bf16_t *)c->xn;
   const pd_config &g = c->cfg;
   PD_REQUIRE(d <= 2048 * 4, PD_EINVAL, "d_model %d too large for the norm kernel", d);
-#define PD_NORM(V, P)                                                                            \
-  hipLaunchKernelGGL((k_norm_bf16<V, P>), dim3(rows), dim3(256), 0, s, xn, mfma_lo(c, xn, d), c->x, gain, bias, \
-                     d, g.norm_kind, g.norm_eps, c->rows.flags, R, c->x, c->ypart, (size_t)c->R_pad * d)
+#define PD_NORM(V, P, E)                                                                         \
+  hipLaunchKernelGGL((k_norm_bf16<V, P, E>), dim3(rows), dim3(256), 0, s, xn, mfma_lo(c, xn, d), c->x, gain, bias, \
+                     d, g.norm_kind, g.norm_eps, c->rows.flags, R, c->x, c->ypart, (size_t)c->R_pad * d,   \
+                     (const bf16_t *)c->tok_emb, (const bf16_t *)c->pos_emb, c->rows.tok, c->rows.pos)
 #define PD_NORM_P(V)                                                                             \
-  switch (c->pend_parts) {                                                                       \
-    case 0: PD_NORM(V, 0); break;                                                                \
-    case 1: PD_NORM(V, 1); break;                                                                \
-    case 2: PD_NORM(V, 2); break;                                                                \
-    case 4: PD_NORM(V, 4); break;                                                                \
+  if (c->embed_pending) { PD_NORM(V, 0, true); }                                                 \
+  else switch (c->pend_parts) {                                                                  \
+    case 0: PD_NORM(V, 0, false); break;                                                         \
+    case 1: PD_NORM(V, 1, false); break;                                                         \
+    case 2: PD_NORM(V, 2, false); break;                                                         \
+    case 4: PD_NORM(V, 4, false); break;                                                         \
     default: pd_set_error("unsupported number of pending slices: %d", c->pend_parts); return PD_EINVAL; \
   }
   if (d <= 2048) { PD_NORM_P(1) } else if (d <= 4096) { PD_NORM_P(2) } else { PD_NORM_P(4) }
@@ -170,6 +197,7 @@ int mfma_norm(pd_ctx *c, const float *gain, const float *bias, int R, hipStream_
 #undef PD_NORM
   PD_CHECK_HIP(hipGetLastError());
   c->pend_parts = 0;
+  c->embed_pending = false;
   return PD_OK;
 }
 
@@ -289,9 +317,9 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int nt, const f
         int oi = __shfl_xor(bi, o);
         if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
       }
-      if (g == 0) {
-        a.part_val[(size_t)nt * (16 * RT) + r] = best;
-        a.part_idx[(size_t)nt * (16 * RT) + r] = bi;
+      if (g == 0) {      // row-major [row][tile]: the commit kernel reads a row's winners as one run
+        a.part_val[(size_t)r * a.n_tiles + nt] = best;
+        a.part_idx[(size_t)r * a.n_tiles + nt] = bi;
       }
     }
   }
@@ -478,42 +506,6 @@ __global__ __launch_bounds__(64 * NW_K) void k_gemm_s(GemmArgs a) {
     for (int t = 0; t < NT; ++t)
       if (nt0 + t < a.n_tiles) gemm_epilogue<RT, EPI>(a, nt0 + t, acc[t], kvi, lane);
   }
-}
-
-// second stage of the argmax: one block per row over the per-tile winners
-__global__ __launch_bounds__(256) void k_lm_reduce(int32_t *row_argmax, const float *part_val,
-                                                   const int32_t *part_idx, int n_tiles, int rows,
-                                                   const int32_t *flags) {
-  __shared__ float sv[256];
-  __shared__ int si[256];
-  int r = blockIdx.x;
-  if (!(flags[r] & ROW_VALID)) return;
-  float best = -INFINITY;
-  int bi = 0x7fffffff;
-  for (int t = threadIdx.x; t < n_tiles; t += 256) {
-    float v = part_val[(size_t)t * rows + r];
-    int ix = part_idx[(size_t)t * rows + r];
-    if (v > best || (v == best && ix < bi)) { best = v; bi = ix; }
-  }
-  sv[threadIdx.x] = best; si[threadIdx.x] = bi;
-  __syncthreads();
-  for (int o = 128; o > 0; o >>= 1) {
-    if ((int)threadIdx.x < o) {
-      float ov = sv[threadIdx.x + o]; int oi = si[threadIdx.x + o];
-      if (ov > sv[threadIdx.x] || (ov == sv[threadIdx.x] && oi < si[threadIdx.x])) {
-        sv[threadIdx.x] = ov; si[threadIdx.x] = oi;
-      }
-    }
-    __syncthreads();
-  }
-  if (threadIdx.x == 0) row_argmax[r] = si[0];
-}
-
-int mfma_lm_reduce(pd_ctx *c, int n_tiles, int R, hipStream_t s) {
-  hipLaunchKernelGGL(k_lm_reduce, dim3(R), dim3(256), 0, s, c->row_argmax, c->lm_part_val,
-                     c->lm_part_idx, n_tiles, mfma_gemm_row_tiles(R), c->rows.flags);
-  PD_CHECK_HIP(hipGetLastError());
-  return PD_OK;
 }
 
 // ---------------------------------------------------------------------------

@@ -50,6 +50,6 @@ int mfma_head(pd_ctx *c, int R, bool want_logits, hipStream_t s) {
   a.n_tiles = c->vocab_pad / 16; a.V = g.vocab;
   a.logits = want_logits ? c->logits : nullptr; a.ld_logits = g.vocab;
   a.part_val = c->lm_part_val; a.part_idx = c->lm_part_idx;
-  if ((rc = mfma_gemm(EPI_LM, a, R, s))) return rc;
-  return mfma_lm_reduce(c, a.n_tiles, R, s);
+  // leaves one winner per 16-column tile; the commit kernel picks the winner of each row
+  return mfma_gemm(EPI_LM, a, R, s);
 }

@@ -115,7 +115,7 @@ struct GemmArgs {
   const float *rope_cs;
   int d, H, hd, kv_cap;
   float *logits; int V, ld_logits;     // EPI_LM: optional logits [rows][ld_logits]
-  float *part_val; int32_t *part_idx;  // EPI_LM: [n_tiles][16*RT] best value / index per tile
+  float *part_val; int32_t *part_idx;  // EPI_LM: [16*RT][n_tiles] best value / index per tile
 };
 
 int mfma_gemm(int epi, const GemmArgs &a, int rows, hipStream_t s);
@@ -123,6 +123,5 @@ int mfma_gemm_row_tiles(int rows);            // rows a launch reads/writes: 16 
 int mfma_norm(pd_ctx *c, const float *gain, const float *bias, int R, hipStream_t s);
 // low-part twin of an activation buffer (NULL when the split is switched off)
 bf16_t *mfma_lo(pd_ctx *c, void *buf, size_t cols);
-int mfma_lm_reduce(pd_ctx *c, int n_tiles, int R, hipStream_t s);
 int mfma_attention(pd_ctx *c, const LayerPtrs &lw, int A, int nreq, int req0, int kv_override,
                    hipStream_t s);

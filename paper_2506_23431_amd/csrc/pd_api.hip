@@ -186,7 +186,7 @@ extern "C" int pd_create(const pd_config *cfg, const pd_weights *w, void *dev_wo
     lp.n2b = cfg->norm_kind == 0 ? w->norm2_b[l] : nullptr;
   }
   c->prefilled = false; c->host_steps = 0;
-  c->opt_splits = 0; c->opt_graph = 0; c->opt_profile = 0; c->opt_split = 1;
+  c->embed_pending = false; c->opt_splits = 0; c->opt_graph = 0; c->opt_profile = 0; c->opt_split = 1;
   c->graph_exec = nullptr; c->graph_ready = false; c->ev_used = 0; c->h_pinned = nullptr;
   c->B = c->L = c->S = c->dt = c->M = c->time_max = c->A = c->R = 0;
   hipStream_t s = (hipStream_t)hip_stream;
@@ -263,7 +263,9 @@ extern "C" int pd_profile_read(pd_ctx *c, double *attn_avg_us, int32_t *attn_lau
 static int run_layers(pd_ctx *c, int R, int A, int nreq, int req0, int kv_override,
                       hipStream_t s) {
   int rc;
-  if ((rc = launch_embed(c, R, s))) return rc;
+  // fp32 path: embedding kernel; matrix-core path: the first norm kernel gathers the rows itself
+  if (c->impl == 1) c->embed_pending = true;
+  else if ((rc = launch_embed(c, R, s))) return rc;
   c->pend_parts = 0;
   for (int l = 0; l < c->cfg.n_layer; ++l) {
     rc = c->impl == 1 ? mfma_layer(c, l, R, A, nreq, req0, kv_override, s)
@@ -297,6 +299,7 @@ extern "C" int pd_prefill_context(pd_ctx *c, const int32_t *ctx_tokens, int B, i
   c->B = B; c->L = L; c->S = n_sub; c->dt = delta_t; c->M = max_sub_tokens; c->time_max = time_max;
   c->A = std::min(n_sub, max_sub_tokens / delta_t + 1);
   c->R = B * c->A;
+  PD_REQUIRE(c->A <= 1024, PD_EINVAL, "%d rows per request exceed the 1024 one step supports", c->A);
   PD_REQUIRE(c->impl == 0 || c->R <= 128, PD_EINVAL,
              "B * rows-per-request = %d exceeds the 128 rows one bf16 step supports", c->R);
   PD_CHECK_HIP(hipMemcpyAsync(c->ctx_tok, ctx_tokens, sizeof(int32_t) * (size_t)B * L,

@@ -127,6 +127,7 @@ struct pd_ctx {
   float *att_part;          // split-K partials of the attention kernel
   float *ypart;             // [4][R_pad][d] split-K partial sums of the O / FFN2 projections
   int pend_parts;           // slices of ypart the next norm kernel has to add to x
+  bool embed_pending;       // matrix-core path: the next norm kernel gathers x from the embedding tables
   float *lm_part_val; int32_t *lm_part_idx; int lm_parts;
   int32_t *row_argmax;      // [R_cap] argmax of each row's logits
   float *rope_cs;           // [max_pos][hd/2][2] cos, sin

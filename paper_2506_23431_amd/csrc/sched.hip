@@ -1,7 +1,7 @@
 // Schedule and glue kernels: the integer bookkeeping of Algorithm 1 kept on the
 // device (so that a decode step never waits for the host), embedding gather,
 // rotary table.
-#include "pd_internal.h"
+#include "mfma_common.h"
 
 // ---------------------------------------------------------------------------
 // reset: t = 0, no subsequences, nothing generated (Algorithm 1, lines 1-2)
@@ -36,48 +36,75 @@ int launch_reset_state(pd_ctx *c, hipStream_t s) {
 // token (coordinate tau = t).  A subsequence that finished in the previous step is
 // fed once more so that its last token enters the KV cache; that row selects no token.
 // ---------------------------------------------------------------------------
-__global__ void k_tick(SchedState st, RowTables rt, int S, int dt, int M, int L, int A,
-                       int time_max, int bos, int gen_cap, int gen_stride) {
-  int b = blockIdx.x;
-  if (threadIdx.x != 0) return;
-  for (int a = 0; a < A; ++a) { rt.flags[b * A + a] = 0; rt.qinfo[b * A + a] = make_int4(0, -1, 0, b); rt.kvinfo[b * A + a] = make_int4(0, b, 0, 0); }
-  for (int i = 0; i < S; ++i) { st.row_of[b * S + i] = -1; st.step_tok[b * S + i] = -1; }
-  st.n_rows[b] = 0;
-  if (st.done[b]) return;
-  int t = st.step[b] + 1;
-  if (t > time_max) {            // only reachable with time_max == 0
-    st.done[b] = 1;
-    atomicAdd(st.all_done, 1);
-    return;
+__global__ __launch_bounds__(64) void k_tick(SchedState st, RowTables rt, int S, int dt, int M, int L, int A,
+                                             int time_max, int bos, int gen_cap, int gen_stride) {
+  // one wave per request: lane i looks after subsequences i, i + 64, ...
+  __shared__ int s_k, s_t;
+  const int b = blockIdx.x, lane = threadIdx.x;
+  for (int a = lane; a < A; a += 64) {
+    rt.flags[b * A + a] = 0;
+    rt.qinfo[b * A + a] = make_int4(0, -1, 0, b);
+    rt.kvinfo[b * A + a] = make_int4(0, b, 0, 0);
   }
-  st.step[b] = t;
-  int k = st.k_open[b];
-  if ((t - 1) % dt == 0 && k < S) {
-    st.grid[(size_t)(b * S + k) * (M + 1)] = bos;
-    st.n_tok[b * S + k] = 1; st.n_fed[b * S + k] = 0; st.fin[b * S + k] = 0;
-    ++k;
-    st.k_open[b] = k;
+  for (int i = lane; i < S; i += 64) { st.row_of[b * S + i] = -1; st.step_tok[b * S + i] = -1; }
+  if (lane == 0) {
+    st.n_rows[b] = 0;
+    int k = -1, t = 0;
+    if (!st.done[b]) {
+      t = st.step[b] + 1;
+      if (t > time_max) {          // only reachable with time_max == 0
+        st.done[b] = 1;
+        atomicAdd(st.all_done, 1);
+      } else {
+        st.step[b] = t;
+        k = st.k_open[b];
+        if ((t - 1) % dt == 0 && k < S) {      // Algorithm 1, lines 5-7: open subsequence k + 1
+          st.grid[(size_t)(b * S + k) * (M + 1)] = bos;
+          st.n_tok[b * S + k] = 1; st.n_fed[b * S + k] = 0; st.fin[b * S + k] = 0;
+          ++k;
+          st.k_open[b] = k;
+        }
+      }
+    }
+    s_k = k; s_t = t;
   }
-  int a = 0, ng = st.n_gen[b];
-  for (int i = 0; i < k; ++i) {
-    int nt = st.n_tok[b * S + i];
-    if (nt > st.n_fed[b * S + i] && a < A && ng + a < gen_cap) {
-      int r = b * A + a;
+  __syncthreads();
+  const int k = s_k, t = s_t;
+  if (k < 0) return;
+  // rows in subsequence order: the first min(A, free slots) subsequences that hold an unfed token
+  const int ng = st.n_gen[b];
+  int a_base = 0;
+  for (int i0 = 0; i0 < k; i0 += 64) {
+    int i = i0 + lane;
+    int nt = 0, fin = 0;
+    bool has = false;
+    if (i < k) {
+      nt = st.n_tok[b * S + i];
+      fin = st.fin[b * S + i];
+      has = nt > st.n_fed[b * S + i];
+    }
+    unsigned long long m = __ballot(has);
+    int a = a_base + __popcll(m & ((1ull << lane) - 1));
+    if (has && a < A && ng + a < gen_cap) {
+      int r = b * A + a, fl = ROW_VALID | (fin ? 0 : ROW_PRODUCE);
       rt.req[r] = b; rt.sub[r] = i + 1;
       rt.tok[r] = st.grid[(size_t)(b * S + i) * (M + 1) + nt - 1];
       rt.pos[r] = L + (t - 1) + i;
       rt.slot[r] = L + ng + a;
       rt.lim[r] = L;
-      rt.flags[r] = ROW_VALID | (st.fin[b * S + i] ? 0 : ROW_PRODUCE);
-      rt.qinfo[r] = make_int4(rt.flags[r], i + 1, L, b);
-      rt.kvinfo[r] = make_int4(rt.flags[r], b, L + ng + a, L + (t - 1) + i);
+      rt.flags[r] = fl;
+      rt.qinfo[r] = make_int4(fl, i + 1, L, b);
+      rt.kvinfo[r] = make_int4(fl, b, L + ng + a, L + (t - 1) + i);
       st.gen_sub[(size_t)b * gen_stride + (L & 7) + ng + a] = (uint16_t)(i + 1);
       st.n_fed[b * S + i] = nt;
       st.row_of[b * S + i] = r;
-      ++a;
     }
+    a_base += __popcll(m);
   }
-  st.n_gen[b] = ng + a; st.kv_len[b] = L + ng + a; st.n_rows[b] = a;
+  if (lane == 0) {
+    int a = min(a_base, min(A, max(gen_cap - ng, 0)));
+    st.n_gen[b] = ng + a; st.kv_len[b] = L + ng + a; st.n_rows[b] = a;
+  }
 }
 
 int launch_tick(pd_ctx *c, hipStream_t s) {
@@ -150,33 +177,81 @@ int launch_embed(pd_ctx *c, int R, hipStream_t s) {
 // commit: Algorithm 1 lines 9-13 for one request per block, plus the optional
 // copy of this step's logits to the caller's [B][S][V] buffer.
 // ---------------------------------------------------------------------------
-__global__ void k_commit(SchedState st, RowTables rt, const int32_t *row_argmax, int S, int M,
-                         int time_max, int eos, int B, int V) {
-  int b = blockIdx.x;
-  if (threadIdx.x != 0) return;
-  if (st.done[b]) return;
-  int t = st.step[b], k = st.k_open[b];
-  bool all_fin = k > 0;
-  for (int i = 0; i < k; ++i) {
-    int r = st.row_of[b * S + i];
-    if (r >= 0 && (rt.flags[r] & ROW_PRODUCE)) {
-      int f = st.force[b * S + i];
-      int tok = f >= 0 ? f : row_argmax[r];
-      // non-finite logits leave the argmax without a winner: keep the id inside the vocabulary so
-      // that the next embedding gather stays in bounds
-      if (tok < 0 || tok >= V) tok = 0;
-      int nt = st.n_tok[b * S + i];
-      st.grid[(size_t)(b * S + i) * (M + 1) + nt] = tok;
-      st.n_tok[b * S + i] = nt + 1;
-      st.step_tok[b * S + i] = tok;
-      if (eos >= 0 && tok == eos) st.fin[b * S + i] = 1;
-      else if (nt >= M) st.fin[b * S + i] = 2;       // nt generated tokens now held
+__global__ __launch_bounds__(1024) void k_commit(SchedState st, RowTables rt, int32_t *row_argmax,
+                                                 const float *part_val, const int32_t *part_idx, int n_tiles,
+                                                 int S, int M, int A, int time_max, int eos, int V) {
+  // Everything the block needs is requested at once, before the first use, so that the kernel costs
+  // about one memory round trip: the schedule state of the request, and (matrix-core path) the
+  // winners of the vocabulary tiles of every row, whether or not the row selects a token.
+  __shared__ int s_arg[1024];           // s_arg[a]: argmax of row a of this request (a < A <= 1024)
+  const int b = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwave = blockDim.x >> 6;
+  const int done = st.done[b], t = st.step[b], k = st.k_open[b];
+  const int i0 = threadIdx.x;           // subsequence of this thread in the first pass
+  int r0 = -1, fin0 = 0, f0 = -1, nt0 = 0;
+  if (i0 < S) {
+    r0 = st.row_of[b * S + i0]; fin0 = st.fin[b * S + i0]; f0 = st.force[b * S + i0];
+    nt0 = st.n_tok[b * S + i0];
+  }
+  // stage 1: second stage of the argmax, one wave per row; lowest index wins ties (Eq. 4)
+  for (int a = wave; a < A; a += nwave) {
+    int r = b * A + a;
+    int bi = 0x7fffffff;
+    if (part_val) {
+      const float *pv = part_val + (size_t)r * n_tiles;
+      const int32_t *pi = part_idx + (size_t)r * n_tiles;
+      float best = -INFINITY;
+      for (int t0 = lane; t0 < n_tiles; t0 += 64 * 8) {
+        float v[8]; int ix[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          int tt = min(t0 + 64 * u, n_tiles - 1);        // clamped: a repeated candidate changes nothing
+          v[u] = pv[tt];
+          ix[u] = pi[tt];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          if (v[u] > best || (v[u] == best && ix[u] < bi)) { best = v[u]; bi = ix[u]; }
+      }
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) {
+        float ov = __shfl_xor(best, o);
+        int oi = __shfl_xor(bi, o);
+        if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+      }
+    } else {
+      bi = row_argmax[r];               // fp32 path: the argmax kernel has decided
+    }
+    if (lane == 0) s_arg[a] = bi;
+  }
+  __syncthreads();
+  if (done) return;                     // the same for every thread of the block
+  // stage 2: Algorithm 1 lines 9-13, thread i for subsequence i.  A subsequence selects a token
+  // when it has a row and was unfinished when the rows were laid out.
+  int open_unfinished = 0;
+  for (int i = i0; i < S; i += blockDim.x) {
+    int r = r0, fin = fin0, f = f0, nt = nt0;
+    if (i != i0) {
+      r = st.row_of[b * S + i]; fin = st.fin[b * S + i]; f = st.force[b * S + i]; nt = st.n_tok[b * S + i];
+    }
+    if (i < k) {
+      if (r >= 0 && fin == 0) {
+        int tok = f >= 0 ? f : s_arg[r - b * A];
+        // non-finite logits leave the argmax without a winner: keep the id inside the vocabulary so
+        // that the next embedding gather stays in bounds
+        if (tok < 0 || tok >= V) tok = 0;
+        st.grid[(size_t)(b * S + i) * (M + 1) + nt] = tok;
+        st.n_tok[b * S + i] = nt + 1;
+        st.step_tok[b * S + i] = tok;
+        if (eos >= 0 && tok == eos) fin = 1;
+        else if (nt >= M) fin = 2;                     // nt generated tokens now held
+        st.fin[b * S + i] = fin;
+      }
+      if (fin == 0) open_unfinished = 1;
     }
     st.force[b * S + i] = -1;
-    all_fin = all_fin && st.fin[b * S + i] != 0;
   }
-  for (int i = k; i < S; ++i) st.force[b * S + i] = -1;
-  if (all_fin || t >= time_max) {
+  int any_unfinished = __syncthreads_or(open_unfinished);
+  if (threadIdx.x == 0 && ((k > 0 && !any_unfinished) || t >= time_max)) {
     st.done[b] = 1; st.steps[b] = t;
     atomicAdd(st.all_done, 1);
   }
@@ -196,8 +271,11 @@ int launch_commit(pd_ctx *c, float *out_logits, hipStream_t s) {
                        c->rows, c->S, c->cfg.vocab);
     PD_CHECK_HIP(hipGetLastError());
   }
-  hipLaunchKernelGGL(k_commit, dim3(c->B), dim3(64), 0, s, c->sch, c->rows, c->row_argmax, c->S,
-                     c->M, c->time_max, c->cfg.eos_id, c->B, c->cfg.vocab);
+  // matrix-core path: the vocabulary projection left one winner per tile; fp32 path: row_argmax is final
+  const bool tiles = c->impl == 1;
+  hipLaunchKernelGGL(k_commit, dim3(c->B), dim3(tiles ? 1024 : 256), 0, s, c->sch, c->rows, c->row_argmax,
+                     tiles ? c->lm_part_val : nullptr, tiles ? c->lm_part_idx : nullptr, c->vocab_pad / 16,
+                     c->S, c->M, c->A, c->time_max, c->cfg.eos_id, c->cfg.vocab);
   PD_CHECK_HIP(hipGetLastError());
   return PD_OK;
 }
