@@ -175,7 +175,8 @@ __global__ __launch_bounds__(256) void k_norm_bf16(bf16_t *xn, bf16_t *xn_lo, co
 }
 
 int mfma_norm(pd_ctx *c, const float *gain, const float *bias, int R, hipStream_t s) {
-  int rows = (R + 15) / 16 * 16, d = c->cfg.d_model;
+  // packed pairs: rows 8-15 of the fragments belong to the low parts of rows 0-7
+  int rows = c->packed ? 8 : (R + 15) / 16 * 16, d = c->cfg.d_model;
   bf16_t *xn = (bf16_t *)c->xn;
   const pd_config &g = c->cfg;
   PD_REQUIRE(d <= 2048 * 4, PD_EINVAL, "d_model %d too large for the norm kernel", d);
@@ -219,12 +220,15 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int nt, const f
                                               const int4 *kvi, int lane) {
   int m = lane & 15, g = lane >> 4;
   int n0 = nt * 16 + 4 * g;
+  // rows at and beyond a.R are never stored: nobody reads them, and with packed activations their
+  // slots hold the low parts of rows 0-7
   if (EPI == EPI_RESID) {
     // split-K slice blockIdx.y of y; the following norm kernel adds the slices to x
     float *yp = a.x + (size_t)blockIdx.y * a.part_stride;
 #pragma unroll
     for (int i = 0; i < RT; ++i) {
       int r = i * 16 + m;
+      if (r >= a.R) continue;
       *(float4 *)(yp + (size_t)r * a.ld + n0) = make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
     }
   } else if (EPI == EPI_GELU) {
@@ -237,7 +241,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int nt, const f
         float t = acc[i][j];
         y[j] = 0.5f * t * (1.f + erff(t * 0.70710678118654752f));
       }
-      store4_split(a.out_bf, a.out_lo, act_off(r, n0, a.ld), y);
+      if (r < a.R) store4_split(a.out_bf, a.out_lo, act_off(r, n0, a.ld), y);
     }
   } else if (EPI == EPI_SWIGLU) {
     // groups 0,1: gate of features nt*8 + 4g + j; groups 2,3: up of nt*8 + 4(g-2) + j
@@ -251,7 +255,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int nt, const f
         float other = __shfl_xor(mine, 32);
         y[j] = mine / (1.f + __expf(-mine)) * other;     // meaningful on groups 0,1
       }
-      if (g < 2) store4_split(a.out_bf, a.out_lo, act_off(r, nt * 8 + 4 * g, a.ld), y);
+      if (g < 2 && r < a.R) store4_split(a.out_bf, a.out_lo, act_off(r, nt * 8 + 4 * g, a.ld), y);
     }
   } else if (EPI == EPI_QKV || EPI == EPI_QKV_ROPE) {
     int sec = n0 / a.d, nl = n0 % a.d, h = nl / a.hd;
@@ -317,7 +321,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int nt, const f
         int oi = __shfl_xor(bi, o);
         if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
       }
-      if (g == 0) {      // row-major [row][tile]: the commit kernel reads a row's winners as one run
+      if (g == 0 && r < a.R) {      // row-major [row][tile]: the commit kernel reads a row's winners as one run
         a.part_val[(size_t)r * a.n_tiles + nt] = best;
         a.part_idx[(size_t)r * a.n_tiles + nt] = bi;
       }
@@ -447,8 +451,12 @@ __device__ __forceinline__ void gemm_chunk(floatx4 (&acc)[NT][RT][2], const uint
       }
 }
 
-template <int RT, int NT, int NW_K, int U, int EPI, bool SPLIT>
+// PACK (one row tile, at most 8 rows): the activation fragment carries the high parts in rows 0-7
+// and the low parts of the same 8 rows in rows 8-15, so one fragment and one multiply per k-tile
+// do the work of two; the two halves of the output tile are added before the epilogue.
+template <int RT, int NT, int NW_K, int U, int EPI, bool SPLIT, bool PACK>
 __global__ __launch_bounds__(64 * NW_K) void k_gemm_s(GemmArgs a) {
+  static_assert(!PACK || (RT == 1 && !SPLIT), "packed activations: one row tile, one fragment");
   __shared__ floatx4 red[NW_K > 1 ? NW_K * NT * RT * 64 : 1];
   const int wk = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int nt0 = blockIdx.x * NT;
@@ -484,6 +492,13 @@ __global__ __launch_bounds__(64 * NW_K) void k_gemm_s(GemmArgs a) {
   for (int t = 0; t < NT; ++t)
 #pragma unroll
     for (int i = 0; i < RT; ++i) acc[t][i] = SPLIT ? acc2[t][i][0] + acc2[t][i][1] : acc2[t][i][0];
+  if (PACK) {
+    // output row m + 8 holds the product with the low parts of row m
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[t][0][j] += __shfl_xor(acc[t][0][j], 8);
+  }
   if (NW_K > 1) {
     // every wave leaves its partial tiles in LDS; wave t then sums and finishes column tile t
     static_assert(NW_K == 1 || NW_K >= NT, "one finishing wave per column tile");
@@ -556,7 +571,7 @@ static int launch_gemm_rt(const GemmArgs &a, hipStream_t s) {
 // otherwise have fewer than about 1500 waves; up to 16 waves along K per block are summed
 // through LDS and, for the residual projections, K is also cut into slices over blocks that the
 // next norm kernel sums.
-template <int RT, int NT, int EPI, bool SPLIT>
+template <int RT, int NT, int EPI, bool SPLIT, bool PACK>
 static int launch_gemm_small_nt(GemmArgs a, int ks, hipStream_t s) {
   constexpr int U = 4;
   int KT = a.K / 32, groups = (a.n_tiles + NT - 1) / NT;
@@ -567,7 +582,7 @@ static int launch_gemm_small_nt(GemmArgs a, int ks, hipStream_t s) {
   a.k_share = (per_block + nwk - 1) / nwk;
   dim3 grid(groups, ks);
 #define PD_LAUNCH(NWK) \
-  hipLaunchKernelGGL((k_gemm_s<RT, NT, (NWK < NT ? NT : NWK), U, EPI, SPLIT>), grid, \
+  hipLaunchKernelGGL((k_gemm_s<RT, NT, (NWK < NT ? NT : NWK), U, EPI, SPLIT, PACK>), grid, \
                      dim3(64 * (NWK < NT ? NT : NWK)), 0, s, a)
   switch (nwk) {
     case 1: PD_LAUNCH(1); break;
@@ -582,13 +597,13 @@ static int launch_gemm_small_nt(GemmArgs a, int ks, hipStream_t s) {
   return PD_OK;
 }
 
-template <int RT, int EPI, bool SPLIT>
+template <int RT, int EPI, bool SPLIT, bool PACK>
 static int launch_gemm_small(const GemmArgs &a, hipStream_t s) {
   int KT = a.K / 32, ks = 1;
   if (EPI == EPI_RESID)    // slices while the launch has fewer than 256 blocks and a slice keeps 8 k-tiles
     while (ks < a.max_parts && ((a.n_tiles + 1) / 2) * ks < 256 && KT / (2 * ks) >= 8) ks *= 2;
-  if (RT == 1 && ((a.n_tiles + 1) / 2) * ks >= 128) return launch_gemm_small_nt<RT, 2, EPI, SPLIT>(a, ks, s);
-  return launch_gemm_small_nt<RT, 1, EPI, SPLIT>(a, ks, s);
+  if (RT == 1 && ((a.n_tiles + 1) / 2) * ks >= 128) return launch_gemm_small_nt<RT, 2, EPI, SPLIT, PACK>(a, ks, s);
+  return launch_gemm_small_nt<RT, 1, EPI, SPLIT, PACK>(a, ks, s);
 }
 
 int mfma_gemm_row_tiles(int rows) {
@@ -599,8 +614,8 @@ int mfma_gemm_row_tiles(int rows) {
 template <int EPI, bool SPLIT>
 static int launch_gemm_split(const GemmArgs &a, int rows, hipStream_t s) {
   switch (mfma_gemm_row_tiles(rows)) {
-    case 16: return launch_gemm_small<1, EPI, SPLIT>(a, s);
-    case 32: return launch_gemm_small<2, EPI, SPLIT>(a, s);
+    case 16: return launch_gemm_small<1, EPI, SPLIT, false>(a, s);
+    case 32: return launch_gemm_small<2, EPI, SPLIT, false>(a, s);
     case 64: return launch_gemm_rt<4, 2, EPI, SPLIT>(a, s);
     case 80: return launch_gemm_rt<5, 4, EPI, SPLIT>(a, s);
     default: return launch_gemm_rt<8, 4, EPI, SPLIT>(a, s);
@@ -610,6 +625,10 @@ static int launch_gemm_split(const GemmArgs &a, int rows, hipStream_t s) {
 template <int EPI>
 static int launch_gemm(const GemmArgs &a, int rows, hipStream_t s) {
   PD_REQUIRE(rows <= 128, PD_EINVAL, "more than 128 rows per launch (%d)", rows);
+  if (a.packed) {
+    PD_REQUIRE(rows <= 8 && a.R <= 8, PD_EINVAL, "packed activations hold at most 8 rows (%d)", rows);
+    return launch_gemm_small<1, EPI, false, true>(a, s);
+  }
   return a.xn_lo ? launch_gemm_split<EPI, true>(a, rows, s) : launch_gemm_split<EPI, false>(a, rows, s);
 }
 

@@ -2,8 +2,10 @@
 #include "mfma_common.h"
 
 bf16_t *mfma_lo(pd_ctx *c, void *buf, size_t cols) {
-  // every activation buffer is sized for fp32 rows; the low parts live in its second half
-  return c->opt_split ? (bf16_t *)buf + (size_t)c->R_pad * cols : nullptr;
+  // every activation buffer is sized for fp32 rows; the low parts live in its second half or, for
+  // packed pairs, 8 rows further down the same fragment (64 elements: 8 rows of 8-element granules)
+  if (!c->opt_split) return nullptr;
+  return c->packed ? (bf16_t *)buf + 64 : (bf16_t *)buf + (size_t)c->R_pad * cols;
 }
 
 int mfma_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_override, hipStream_t s) {
@@ -14,6 +16,7 @@ int mfma_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_overri
   GemmArgs a;
   memset(&a, 0, sizeof(a));
   a.R = R; a.rt = c->rows; a.d = d; a.H = g.n_head; a.hd = g.head_dim; a.kv_cap = c->kv_cap;
+  a.packed = c->packed;
   // QKV projection (+ rotary) + KV append
   a.W = lw.p_wqkv; a.xn = (const bf16_t *)c->xn; a.xn_lo = mfma_lo(c, c->xn, d); a.K = d;
   a.n_tiles = 3 * d / 16; a.out_bf = (bf16_t *)c->q; a.out_lo = mfma_lo(c, c->q, d); a.kc = (f16_t *)lw.kc; a.vc = (f16_t *)lw.vc; a.rope_cs = c->rope_cs;
@@ -45,7 +48,7 @@ int mfma_head(pd_ctx *c, int R, bool want_logits, hipStream_t s) {
   if ((rc = mfma_norm(c, c->fng, c->fnb, R, s))) return rc;
   GemmArgs a;
   memset(&a, 0, sizeof(a));
-  a.R = R; a.rt = c->rows; a.W = c->p_lm_head; a.xn = (const bf16_t *)c->xn;
+  a.R = R; a.rt = c->rows; a.W = c->p_lm_head; a.xn = (const bf16_t *)c->xn; a.packed = c->packed;
   a.xn_lo = mfma_lo(c, c->xn, g.d_model); a.K = g.d_model;
   a.n_tiles = c->vocab_pad / 16; a.V = g.vocab;
   a.logits = want_logits ? c->logits : nullptr; a.ld_logits = g.vocab;

@@ -104,6 +104,7 @@ struct GemmArgs {
   const bf16_t *xn_lo;   // same shape: bf16(x - high part), or NULL to use the high part only
   int K, n_tiles, R;
   int k_share;           // k-tiles per wave along K (set by the launch)
+  int packed;            // 1: xn holds high parts in rows 0-7 and low parts in rows 8-15 (R <= 8); xn_lo unused
   // epilogue
   float *x;              // EPI_RESID: split-K slices of y, [slices][part_stride], row-major [rows][ld]
   size_t part_stride; int max_parts; int *parts_out;   // EPI_RESID: slice stride, limit, slices written

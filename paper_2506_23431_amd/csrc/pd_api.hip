@@ -186,7 +186,7 @@ extern "C" int pd_create(const pd_config *cfg, const pd_weights *w, void *dev_wo
     lp.n2b = cfg->norm_kind == 0 ? w->norm2_b[l] : nullptr;
   }
   c->prefilled = false; c->host_steps = 0;
-  c->embed_pending = false; c->opt_splits = 0; c->opt_graph = 0; c->opt_profile = 0; c->opt_split = 1;
+  c->embed_pending = false; c->packed = false; c->opt_splits = 0; c->opt_graph = 0; c->opt_profile = 0; c->opt_split = 1;
   c->graph_exec = nullptr; c->graph_ready = false; c->ev_used = 0; c->h_pinned = nullptr;
   c->B = c->L = c->S = c->dt = c->M = c->time_max = c->A = c->R = 0;
   hipStream_t s = (hipStream_t)hip_stream;
@@ -331,11 +331,32 @@ extern "C" int pd_reset_decode(pd_ctx *c, void *hip_stream) {
 // ---------------------------------------------------------------------------
 // decode step
 // ---------------------------------------------------------------------------
+// Rows of request 0 that step t can have at most: subsequence i has a row from the step that opens
+// it to the step after its last token, (i-1) dt < t <= (i-1) dt + M + 1 (an earlier <eos> only takes
+// rows away, and rows are numbered without gaps).
+static int rows_bound(const pd_ctx *c, int64_t t) {
+  int n = 0;
+  for (int i = 0; i < c->S; ++i) {
+    int64_t first = (int64_t)i * c->dt + 1;
+    if (t >= first && t <= first + c->M) ++n;
+  }
+  return std::min(n, c->A);
+}
+
 static int enqueue_step(pd_ctx *c, float *out_logits, hipStream_t s) {
   int rc;
   if ((rc = launch_tick(c, s))) return rc;
-  if ((rc = run_layers(c, c->R, c->A, c->B, 0, -1, s))) return rc;
-  rc = c->impl == 1 ? mfma_head(c, c->R, out_logits != nullptr, s) : simple_head(c, c->R, s);
+  // Row indices in use this step: b * A + a.  When they all stay below 8 the matrix-core path keeps
+  // every activation as a packed pair (half the fragments and multiplies in the projections).  A
+  // captured graph is replayed for every step, so it keeps the general layout.
+  int R = c->R;
+  if (c->impl == 1 && c->opt_split && !c->opt_graph) {
+    int r_used = c->B == 1 ? rows_bound(c, (int64_t)c->host_steps + 1) : c->R;
+    if (r_used <= 8) { c->packed = true; R = std::min(R, std::max(r_used, 1)); }
+  }
+  rc = run_layers(c, R, c->A, c->B, 0, -1, s);
+  if (!rc) rc = c->impl == 1 ? mfma_head(c, R, out_logits != nullptr, s) : simple_head(c, R, s);
+  c->packed = false;
   if (rc) return rc;
   return launch_commit(c, out_logits, s);
 }

@@ -127,6 +127,8 @@ struct pd_ctx {
   float *att_part;          // split-K partials of the attention kernel
   float *ypart;             // [4][R_pad][d] split-K partial sums of the O / FFN2 projections
   int pend_parts;           // slices of ypart the next norm kernel has to add to x
+  bool packed;              // this launch sequence keeps activations as packed pairs (at most 8 rows):
+                            // high parts in rows 0-7 of a 16-row fragment, low parts in rows 8-15
   bool embed_pending;       // matrix-core path: the next norm kernel gathers x from the embedding tables
   float *lm_part_val; int32_t *lm_part_idx; int lm_parts;
   int32_t *row_argmax;      // [R_cap] argmax of each row's logits
