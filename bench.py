@@ -102,6 +102,12 @@ def main():
     ap.add_argument("--graph", type=int, default=0, help="replay each step from a captured HIP graph")
     ap.add_argument("--attn-splits", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sync-every", type=int, default=0,
+                    help="synchronise after every N iterations of the timed pass (0: never; a counter-collecting "
+                         "profiler cannot queue tens of thousands of launches)")
+    ap.add_argument("--no-event-passes", action="store_true",
+                    help="skip the passes that time the attention kernel with HIP events and the plain-read "
+                         "measurement (for runs under a counter-collecting profiler)")
     ap.add_argument("--calibrate-copy-mb", type=int, default=0,
                     help="also run plain device-to-device copies of this many MiB (a kernel of known "
                          "traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -145,33 +151,41 @@ def main():
         torch.cuda.synchronize()
         # timed region: exactly K iterations
         t0 = time.perf_counter()
-        dec.decode_steps(K)
+        if args.sync_every > 0:
+            for k0 in range(0, K, args.sync_every):
+                dec.decode_steps(min(args.sync_every, K - k0))
+                torch.cuda.synchronize()
+        else:
+            dec.decode_steps(K)
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
-        # second pass over the same K iterations with HIP events around every launch of the attention
-        # kernel (the one that streams the keys and values); third pass: around the kernel and the
-        # small kernel that merges its partial results
-        dec.set_option(binding.PD_OPT_USE_GRAPH, 0)
-        dec.set_option(binding.PD_OPT_PROFILE, 1)
-        dec.reset_decode()
-        dec.decode_steps(K)
-        torch.cuda.synchronize()
-        attn_us, attn_launches = dec.profile_read()
-        dec.set_option(binding.PD_OPT_PROFILE, 2)
-        dec.reset_decode()
-        dec.decode_steps(K)
-        torch.cuda.synchronize()
-        pair_us, _ = dec.profile_read()
-        dec.set_option(binding.PD_OPT_PROFILE, 0)
+        attn_us, attn_launches, pair_us, read_gbs = 0.0, 0, 0.0, 0.0
+        if not args.no_event_passes:
+            # second pass over the same K iterations with HIP events around every launch of the attention
+            # kernel (the one that streams the keys and values); third pass: around the kernel and the
+            # small kernel that merges its partial results
+            dec.set_option(binding.PD_OPT_USE_GRAPH, 0)
+            dec.set_option(binding.PD_OPT_PROFILE, 1)
+            dec.reset_decode()
+            dec.decode_steps(K)
+            torch.cuda.synchronize()
+            attn_us, attn_launches = dec.profile_read()
+            dec.set_option(binding.PD_OPT_PROFILE, 2)
+            dec.reset_decode()
+            dec.decode_steps(K)
+            torch.cuda.synchronize()
+            pair_us, _ = dec.profile_read()
+            dec.set_option(binding.PD_OPT_PROFILE, 0)
+            # what a kernel that only reads reaches on this device, at the size of one attention launch
+            buf = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+            buf.fill_(1)
+            torch.cuda.synchronize()
+            chunk = int(attention_bytes(cfg, K)) // 4096 * 4096
+            read_gbs = binding.measure_read_bandwidth(buf.data_ptr(), buf.numel(), chunk, 200,
+                                                      torch.cuda.current_stream().cuda_stream)
+            del buf
+
         dec.close()
-        # what a kernel that only reads reaches on this device, at the size of one attention launch
-        buf = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
-        buf.fill_(1)
-        torch.cuda.synchronize()
-        chunk = int(attention_bytes(cfg, K)) // 4096 * 4096
-        read_gbs = binding.measure_read_bandwidth(buf.data_ptr(), buf.numel(), chunk, 200,
-                                                  torch.cuda.current_stream().cuda_stream)
-        del buf
 
     tokens = cfg.batch * sum(producing(cfg, t) for t in range(1, K + 1))
     abytes = attention_bytes(cfg, K)
