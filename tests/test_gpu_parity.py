@@ -53,6 +53,14 @@ CASES = {
     "mfma-manyrows": small("mfma-manyrows", seed=28, dtype=DTYPE_BF16, d_model=128, n_head=2,
                            head_dim=64, d_ff=256, vocab=640, ctx_len=97, n_sub=20, delta_t=1,
                            sub_tokens=24, batch=2, n_layer=1),
+    # one request, at most 5 rows: every step keeps its activations as packed pairs (rotary, SwiGLU, RMSNorm)
+    "mfma-llama-packed": small("mfma-llama-packed", seed=30, dtype=DTYPE_BF16, d_model=256, n_head=2,
+                               head_dim=128, d_ff=352, vocab=777, ctx_len=131, n_sub=6, delta_t=2,
+                               sub_tokens=9, batch=1, **LLAMA),
+    # S = 1: ordinary sequential greedy decoding through the same kernels
+    "mfma-sequential": small("mfma-sequential", seed=31, dtype=DTYPE_BF16, d_model=128, n_head=2,
+                             head_dim=64, d_ff=256, vocab=1003, ctx_len=90, n_sub=1, delta_t=1,
+                             sub_tokens=14, batch=2),
     "mfma-flat": small("mfma-flat", seed=29, dtype=DTYPE_BF16, d_model=128, n_head=2, head_dim=64,
                        d_ff=256, vocab=1000, ctx_len=600, n_sub=4, delta_t=3, sub_tokens=8, batch=1,
                        qkv_std=0.02, norm_init="identity"),
@@ -244,3 +252,17 @@ def test_options_do_not_change_results():
         outs = oracle_run(cfg, w, ctx)
         compare_teacher_forced(cfg, w, ctx, dec, outs, log=say)
         dec.close()
+
+
+def test_sweep_runs_sequential_and_pipelined():
+    """The sweep tool (sequential S = 1 against pipelined schedules with the same token count) runs on
+    a two-layer variant of cfg2 and reports the step counts of the schedule's closed form."""
+    from paper_2506_23431_amd import sweep
+    rows = sweep.main(["--workload", "cfg2", "--layers", "2", "--tokens", "64", "--s-list", "1,4,8",
+                       "--dt-list", "1,4"])
+    got = {(r["S"], r["dt"]): r for r in rows}
+    assert set(got) == {(1, 1), (4, 1), (4, 4), (8, 1), (8, 4)}
+    for (S, dt), r in got.items():
+        assert r["steps"] == (S - 1) * dt + 64 // S
+        assert r["tokens_per_s"] > 0
+    assert got[(1, 1)]["speedup_vs_sequential"] == 1.0
