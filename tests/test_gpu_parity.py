@@ -129,6 +129,58 @@ def test_generate_matches_oracle_until_a_close_call(name):
     dec.close()
 
 
+MF = dict(dtype=DTYPE_BF16, d_model=128, n_head=2, head_dim=64, d_ff=256, vocab=1003)
+DEGENERATE = {
+    # one context token, one subsequence, one token
+    "f32-minimal": (small("f32-minimal", seed=40, ctx_len=1, n_sub=1, delta_t=1, sub_tokens=1, batch=1), None),
+    "mfma-minimal": (small("mfma-minimal", seed=41, ctx_len=1, n_sub=1, delta_t=1, sub_tokens=1, batch=1, **MF), None),
+    # delay not shorter than a subsequence: Algorithm 1 stops when the first subsequence has
+    # finished and the second was never opened (3 of the 13 scheduled steps)
+    "f32-delay-longer-than-subsequence": (small("f32-late", seed=42, n_sub=3, delta_t=5, sub_tokens=3), None),
+    "mfma-delay-longer-than-subsequence": (small("mfma-late", seed=43, n_sub=3, delta_t=5, sub_tokens=3, **MF), None),
+    # time_max cuts the run short: 4 of 14 steps
+    "f32-time-max": (small("f32-tmax", seed=44), 4),
+    "mfma-time-max": (small("mfma-tmax", seed=45, **MF), 4),
+    # one-token subsequences opened every step: every row is a <bos> row or a draining row
+    "mfma-one-token-subsequences": (small("mfma-m1", seed=46, n_sub=7, delta_t=1, sub_tokens=1, ctx_len=33, **MF), None),
+    # context of exactly one and exactly two 32-key blocks; 8 rows (packed pairs) then more
+    "mfma-context-32": (small("mfma-l32", seed=47, ctx_len=32, n_sub=9, delta_t=1, sub_tokens=10, batch=1, **MF), None),
+    "mfma-context-64": (small("mfma-l64", seed=48, ctx_len=64, n_sub=3, delta_t=2, sub_tokens=5, batch=1, **MF), None),
+    # the largest step the matrix-core path takes: 8 requests x 16 rows = 128 rows
+    "mfma-128-rows": (small("mfma-r128", seed=49, n_sub=16, delta_t=1, sub_tokens=15, batch=8, ctx_len=40,
+                            n_layer=1, **MF), 20),
+}
+
+
+@pytest.mark.parametrize("name", list(DEGENERATE))
+def test_degenerate_and_extreme_schedules(name):
+    cfg, steps = DEGENERATE[name]
+    say(f"[case] {name}: {cfg}, steps {steps}")
+    w = pi.make_weights(cfg, threads=4)
+    ctx = pi.make_context(cfg)
+    outs = oracle_run(cfg, w, ctx, steps=steps)
+    if name.endswith("delay-longer-than-subsequence"):
+        assert all(o["steps"] == cfg.sub_tokens and len(o["result"]) == 1 for o in outs)
+    dec = make_decoder(cfg, w)
+    stats = compare_teacher_forced(cfg, w, ctx, dec, outs, steps=steps, log=say)
+    assert stats["rows"] > 0
+    if steps is not None:
+        # the run is over after time_max steps: one more step produces nothing and reports all done
+        toks, _, done = dec.decode_step(want_done=True)
+        assert done and np.all(toks == -1)
+    dec.close()
+
+
+def test_more_than_128_rows_is_an_error_on_the_matrix_core_path():
+    from paper_2506_23431_amd import PdError
+    cfg = small("mfma-r144", seed=50, n_sub=16, delta_t=1, sub_tokens=15, batch=9, ctx_len=40, n_layer=1, **MF)
+    w = pi.make_weights(cfg, threads=4)
+    dec = make_decoder(cfg, w)
+    with pytest.raises(PdError, match="128 rows"):
+        dec.prefill_context(pi.make_context(cfg), cfg.n_sub, cfg.delta_t, cfg.sub_tokens, cfg.time_steps)
+    dec.close()
+
+
 def test_boundary_errors():
     from paper_2506_23431_amd import PdError
     cfg = CASES["cfg1"]
