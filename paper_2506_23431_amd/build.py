@@ -8,7 +8,11 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpd.so")
-SOURCES = ["pd_api.hip", "sched.hip", "simple.hip", "mfma.hip", "gemm.hip", "attn.hip"]
+# (source, extra defines, object name); gemm.hip is compiled once per epilogue (its kernels are many
+# template instances) and once for the parts all epilogues share
+SOURCES = [("pd_api.hip", [], "pd_api.o"), ("sched.hip", [], "sched.o"), ("simple.hip", [], "simple.o"),
+           ("mfma.hip", [], "mfma.o"), ("attn.hip", [], "attn.o"), ("gemm.hip", [], "gemm.o")] + \
+          [("gemm.hip", [f"-DPD_GEMM_EPI={e}"], f"gemm_epi{e}.o") for e in range(6)]
 
 
 def hipcc():
@@ -27,12 +31,12 @@ def build(verbose=True):
     build_dir = os.path.join(HERE, "_build")
     os.makedirs(build_dir, exist_ok=True)
     procs = []
-    for src in SOURCES:
-        obj = os.path.join(build_dir, src.replace(".hip", ".o"))
-        cmd = [hipcc()] + flags + ["-c", os.path.join(CSRC, src), "-o", obj]
+    for src, defines, oname in SOURCES:
+        obj = os.path.join(build_dir, oname)
+        cmd = [hipcc()] + flags + defines + ["-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
-        procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)))
+        procs.append((oname, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)))
         objs.append(obj)
     failed = False
     for src, p in procs:

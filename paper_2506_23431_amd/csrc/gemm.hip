@@ -2,6 +2,8 @@
 // (QKV + rotary + KV append, residual add, GELU, SwiGLU, vocabulary argmax).
 #include "mfma_common.h"
 
+#ifndef PD_GEMM_EPI   // ---- common part: weight packing, norm kernel -------------------------------
+
 // ---------------------------------------------------------------------------
 // weight re-packing (runs once, in pd_create)
 //   mode 0: row(n) = n
@@ -202,17 +204,28 @@ int mfma_norm(pd_ctx *c, const float *gain, const float *bias, int R, hipStream_
   return PD_OK;
 }
 
+#endif
+
+#ifdef PD_GEMM_EPI
+#define PD_GEMM_CAT2(a, b) a##b
+#define PD_GEMM_CAT(a, b) PD_GEMM_CAT2(a, b)
+#define PD_GEMM_ENTRY PD_GEMM_CAT(mfma_gemm_epi, PD_GEMM_EPI)
+
 // ---------------------------------------------------------------------------
-// skinny GEMM  y[r][n] = sum_k xn[r][k] W[n][k],  r < 16*RT rows; weights and
+// skinny GEMM  y[r][n] = sum_k xn[r][k] W[n][k],  r < 16*RT rows (RT = 1, 2, 4, 5, 8); weights and
 // activations both fragment-major.
-// The matrix core computes the transposed tile: A = weight fragment (16 output
-// columns x 32 k), B = activations (32 k x 16 rows), D[4g+j][r] = y[r][n0+4g+j].
-// A block has NW_N x NW_K waves: wave (wn, wk) streams the fragments of n-tile
-// blockIdx.x*NW_N + wn over its 1/NW_K share of K; shares are summed through LDS.
-// The launch picks NW_K so that a wave's share is at most 16 fragments: a wave
-// then requests its whole share (16 KiB of weights) before the first multiply,
-// which is what a kernel that lives for a few microseconds needs to pull HBM
-// bandwidth from the first cycle on.
+// The matrix core computes the transposed tile: A = weight fragment (16 output columns x 32 k),
+// B = activations (32 k x 16 rows), D[4g+j][r] = y[r][n0+4g+j].
+// A block has NW_K waves that cut K between them; every wave owns the same NT column tiles and all
+// RT row tiles, so the block requests every activation fragment of its K range exactly once and
+// uses it for NT weight fragments.  The waves' partial tiles are summed through LDS.  The launch
+// lives for a few microseconds up to a few tens: every load must be in flight from the first cycle
+// on.  Per chunk of U k-tiles a wave requests everything first (the high- and low-part activation
+// fragments of the row tiles, then the weight fragments of its tiles) into registers of their own;
+// only then the multiplies run.  A share that is not a multiple of U ends with chunks of 4, 2 and
+// 1 k-tiles, so that no load is ever conditional.
+// This file is compiled once per epilogue (PD_GEMM_EPI = 0..5: kernels and launch code of that
+// epilogue) and once without (weight packing, norm kernel, dispatcher).
 // ---------------------------------------------------------------------------
 // epilogue of one 16-column tile: lane holds y[r][n0 + j], r = i*16 + m, n0 = nt*16 + 4g, j = 0..3
 template <int RT, int EPI>
@@ -329,102 +342,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int nt, const f
   }
 }
 
-template <int RT, int NT, int NW_K, int EPI, bool SPLIT>
-__global__ __launch_bounds__(64 * NW_K) void k_gemm(GemmArgs a) {
-  // A wave owns NT column tiles x RT row tiles x a share of K: every activation fragment it
-  // loads is used for NT weight fragments, every weight fragment for RT (x2) activation fragments.
-  __shared__ floatx4 red[NW_K > 1 ? (NW_K - 1) * NT * RT * 64 : 1];
-  int wk = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  int nt0 = blockIdx.x * NT;
-  int m = lane & 15;
-  int KT = a.K >> 5;
-  // waves along K: NW_K in this block times gridDim.y blocks (EPI_RESID only)
-  int gk = blockIdx.y * NW_K + wk, nk = gridDim.y * NW_K;
-  int kt0 = (int)((long)gk * KT / nk), kt1 = (int)((long)(gk + 1) * KT / nk);
-  // row data of the KV-append epilogue, requested now so that it arrives with the weights
-  int4 kvi[(EPI == EPI_QKV || EPI == EPI_QKV_ROPE) ? RT : 1];
-  if (EPI == EPI_QKV || EPI == EPI_QKV_ROPE) {
-#pragma unroll
-    for (int i = 0; i < RT; ++i) kvi[i] = a.rt.kvinfo[i * 16 + m];
-  }
-  floatx4 acc[NT][RT];
-#pragma unroll
-  for (int t = 0; t < NT; ++t)
-#pragma unroll
-    for (int i = 0; i < RT; ++i) acc[t][i] = floatx4{0.f, 0.f, 0.f, 0.f};
-  if (kt1 > kt0) {
-    const uint4 *wp = (const uint4 *)a.W + lane;
-    const uint4 *xp = (const uint4 *)a.xn + lane;
-    const uint4 *xl = SPLIT ? (const uint4 *)a.xn_lo + lane : nullptr;
-    // k-tiles per request (1024-thread blocks have 128 registers per lane)
-    constexpr int TILE = NT * RT;
-    constexpr int U0 = TILE == 1 ? (SPLIT ? 8 : 16) : (TILE == 2 ? 8 : (TILE <= 8 ? 4 : 2));
-    constexpr int U = (NW_K == 16 && U0 > (TILE == 1 ? 8 : 4)) ? (TILE == 1 ? 8 : 4) : U0;
-    // request a chunk (weights of NT tiles x U k-tiles, then per row tile the hi and lo activation
-    // fragments), multiply, repeat; for small tiles the share of a wave is a single chunk
-    for (int kt = kt0; kt < kt1; kt += U) {
-      Frag wa[NT][U];
-#pragma unroll
-      for (int t = 0; t < NT; ++t) {
-        int nt = min(nt0 + t, a.n_tiles - 1);          // tiles past the end repeat the last one
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          uint4 v = wp[((size_t)nt * KT + min(kt + u, kt1 - 1)) * 64];
-          wa[t][u].u = kt + u < kt1 ? v : make_uint4(0, 0, 0, 0);
-        }
-      }
-#pragma unroll
-      for (int i = 0; i < RT; ++i) {
-        Frag xb[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) xb[u].u = xp[((size_t)i * KT + min(kt + u, kt1 - 1)) * 64];
-#pragma unroll
-        for (int t = 0; t < NT; ++t)
-#pragma unroll
-          for (int u = 0; u < U; ++u) acc[t][i] = mfma16(wa[t][u], xb[u], acc[t][i]);
-        if (SPLIT) {
-#pragma unroll
-          for (int u = 0; u < U; ++u) xb[u].u = xl[((size_t)i * KT + min(kt + u, kt1 - 1)) * 64];
-#pragma unroll
-          for (int t = 0; t < NT; ++t)
-#pragma unroll
-            for (int u = 0; u < U; ++u) acc[t][i] = mfma16(wa[t][u], xb[u], acc[t][i]);
-        }
-      }
-    }
-  }
-  if (NW_K > 1) {
-    if (wk > 0) {
-#pragma unroll
-      for (int t = 0; t < NT; ++t)
-#pragma unroll
-        for (int i = 0; i < RT; ++i) red[(((wk - 1) * NT + t) * RT + i) * 64 + lane] = acc[t][i];
-    }
-    __syncthreads();
-    if (wk > 0) return;
-#pragma unroll
-    for (int w = 0; w < NW_K - 1; ++w)
-#pragma unroll
-      for (int t = 0; t < NT; ++t)
-#pragma unroll
-        for (int i = 0; i < RT; ++i) acc[t][i] += red[((w * NT + t) * RT + i) * 64 + lane];
-  }
-#pragma unroll
-  for (int t = 0; t < NT; ++t)
-    if (nt0 + t < a.n_tiles) gemm_epilogue<RT, EPI>(a, nt0 + t, acc[t], kvi, lane);
-}
-
-// ---------------------------------------------------------------------------
-// The same product for 1 or 2 row tiles (the decode step of a few requests), where the launch
-// lives for a few microseconds and every load must be in flight from the first cycle on.
-// A wave owns NT column tiles and a share of K (a.k_share k-tiles, normally one chunk of U).  Per
-// chunk it requests everything first: the weight fragments of its tiles and the high- and low-part
-// activation fragments of the row tiles, into registers of their own; only then the multiplies
-// run.  A share that is not a multiple of U ends with chunks of 4, 2 and 1 k-tiles, so that no
-// load is ever conditional.
-// ---------------------------------------------------------------------------
-template <int RT, int NT, int U, bool SPLIT>
-__device__ __forceinline__ void gemm_chunk(floatx4 (&acc)[NT][RT][2], const uint4 *wp, const uint4 *xp,
+template <int RT, int NT, int U, bool SPLIT, int NA>
+__device__ __forceinline__ void gemm_chunk(floatx4 (&acc)[NT][RT][NA], const uint4 *wp, const uint4 *xp,
                                            const uint4 *xl, size_t KT, const int (&tile)[NT], int kt) {
   Frag wa[NT][U], xh[RT][U], xo[SPLIT ? RT : 1][U];
 #pragma unroll
@@ -445,9 +364,10 @@ __device__ __forceinline__ void gemm_chunk(floatx4 (&acc)[NT][RT][2], const uint
     for (int t = 0; t < NT; ++t)
 #pragma unroll
       for (int i = 0; i < RT; ++i) {
-        // two accumulators per tile: the high- and low-part products do not wait for each other
+        // small tiles keep two accumulators per tile (NA = 2) so that the high- and low-part products
+        // do not wait for each other; large tiles have enough independent accumulators anyway
         acc[t][i][0] = mfma16(wa[t][u], xh[i][u], acc[t][i][0]);
-        if (SPLIT) acc[t][i][1] = mfma16(wa[t][u], xo[i][u], acc[t][i][1]);
+        if (SPLIT) acc[t][i][NA - 1] = mfma16(wa[t][u], xo[i][u], acc[t][i][NA - 1]);
       }
 }
 
@@ -474,24 +394,25 @@ __global__ __launch_bounds__(64 * NW_K) void k_gemm_s(GemmArgs a) {
   int tile[NT];
 #pragma unroll
   for (int t = 0; t < NT; ++t) tile[t] = min(nt0 + t, a.n_tiles - 1);   // tiles past the end repeat the last one
-  floatx4 acc2[NT][RT][2];
+  constexpr int NA = (SPLIT && NT * RT <= 2) ? 2 : 1;
+  floatx4 acc2[NT][RT][NA];
 #pragma unroll
   for (int t = 0; t < NT; ++t)
 #pragma unroll
-    for (int i = 0; i < RT; ++i) acc2[t][i][0] = acc2[t][i][1] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < RT; ++i) acc2[t][i][0] = acc2[t][i][NA - 1] = floatx4{0.f, 0.f, 0.f, 0.f};
   const uint4 *wp = (const uint4 *)a.W + lane;
   const uint4 *xp = (const uint4 *)a.xn + lane;
   const uint4 *xl = SPLIT ? (const uint4 *)a.xn_lo + lane : nullptr;
   int kt = kt0;
-  while (kt + U <= kt1) { gemm_chunk<RT, NT, U, SPLIT>(acc2, wp, xp, xl, KT, tile, kt); kt += U; }
-  if (U > 4 && kt + 4 <= kt1) { gemm_chunk<RT, NT, 4, SPLIT>(acc2, wp, xp, xl, KT, tile, kt); kt += 4; }
-  if (U > 2 && kt + 2 <= kt1) { gemm_chunk<RT, NT, 2, SPLIT>(acc2, wp, xp, xl, KT, tile, kt); kt += 2; }
-  if (U > 1 && kt < kt1) gemm_chunk<RT, NT, 1, SPLIT>(acc2, wp, xp, xl, KT, tile, kt);
+  while (kt + U <= kt1) { gemm_chunk<RT, NT, U, SPLIT, NA>(acc2, wp, xp, xl, KT, tile, kt); kt += U; }
+  if (U > 4 && kt + 4 <= kt1) { gemm_chunk<RT, NT, 4, SPLIT, NA>(acc2, wp, xp, xl, KT, tile, kt); kt += 4; }
+  if (U > 2 && kt + 2 <= kt1) { gemm_chunk<RT, NT, 2, SPLIT, NA>(acc2, wp, xp, xl, KT, tile, kt); kt += 2; }
+  if (U > 1 && kt < kt1) gemm_chunk<RT, NT, 1, SPLIT, NA>(acc2, wp, xp, xl, KT, tile, kt);
   floatx4 acc[NT][RT];
 #pragma unroll
   for (int t = 0; t < NT; ++t)
 #pragma unroll
-    for (int i = 0; i < RT; ++i) acc[t][i] = SPLIT ? acc2[t][i][0] + acc2[t][i][1] : acc2[t][i][0];
+    for (int i = 0; i < RT; ++i) acc[t][i] = NA == 2 ? acc2[t][i][0] + acc2[t][i][1] : acc2[t][i][0];
   if (PACK) {
     // output row m + 8 holds the product with the low parts of row m
 #pragma unroll
@@ -500,22 +421,22 @@ __global__ __launch_bounds__(64 * NW_K) void k_gemm_s(GemmArgs a) {
       for (int j = 0; j < 4; ++j) acc[t][0][j] += __shfl_xor(acc[t][0][j], 8);
   }
   if (NW_K > 1) {
-    // every wave leaves its partial tiles in LDS; wave t then sums and finishes column tile t
-    static_assert(NW_K == 1 || NW_K >= NT, "one finishing wave per column tile");
+    // every wave leaves its partial tiles in LDS; wave w then sums and finishes column tiles w, w + NW_K, ...
 #pragma unroll
     for (int t = 0; t < NT; ++t)
 #pragma unroll
       for (int i = 0; i < RT; ++i) red[((wk * NT + t) * RT + i) * 64 + lane] = acc[t][i];
     __syncthreads();
-    if (wk >= NT || nt0 + wk >= a.n_tiles) return;
-    floatx4 sum[RT];
+    for (int t = wk; t < NT && nt0 + t < a.n_tiles; t += NW_K) {
+      floatx4 sum[RT];
 #pragma unroll
-    for (int i = 0; i < RT; ++i) sum[i] = red[((0 * NT + wk) * RT + i) * 64 + lane];
+      for (int i = 0; i < RT; ++i) sum[i] = red[((0 * NT + t) * RT + i) * 64 + lane];
 #pragma unroll
-    for (int w = 1; w < NW_K; ++w)
+      for (int w = 1; w < NW_K; ++w)
 #pragma unroll
-      for (int i = 0; i < RT; ++i) sum[i] += red[((w * NT + wk) * RT + i) * 64 + lane];
-    gemm_epilogue<RT, EPI>(a, nt0 + wk, sum, kvi, lane);
+        for (int i = 0; i < RT; ++i) sum[i] += red[((w * NT + t) * RT + i) * 64 + lane];
+      gemm_epilogue<RT, EPI>(a, nt0 + t, sum, kvi, lane);
+    }
   } else {
 #pragma unroll
     for (int t = 0; t < NT; ++t)
@@ -524,45 +445,8 @@ __global__ __launch_bounds__(64 * NW_K) void k_gemm_s(GemmArgs a) {
 }
 
 // ---------------------------------------------------------------------------
-// launch.  Row tiles RT in {1,2,4,5,8}; column tiles per wave NT = 1 (RT <= 2) or 4 (RT >= 4) so
-// that the activation fragments, which come from L2, stay at ~2-4 KiB per KiB of weights; waves along K so that a wave's share is a few requests at most and there are enough
-// waves for every SIMD.
+// launch
 // ---------------------------------------------------------------------------
-template <int RT, int NT, int EPI, bool SPLIT>
-static int launch_gemm_rt(const GemmArgs &a, hipStream_t s) {
-  int KT = a.K / 32;
-  constexpr int SHARE = NT * RT == 1 ? (SPLIT ? 8 : 16) : 16;   // k-tiles a wave should at least own
-  // LDS reduction buffer (NW_K - 1) * NT * RT KiB must stay below 64 KiB
-  constexpr int MAX_NWK = NT * RT <= 2 ? 16 : (NT * RT <= 4 ? 8 : (NT * RT <= 20 ? 4 : 2));
-  int groups = (a.n_tiles + NT - 1) / NT;
-  int waves_k = (KT + SHARE - 1) / SHARE;
-  // want about 2048 waves when the matrix is large enough to give every wave >= 4 k-tiles
-  while ((long)groups * waves_k < 2048 && KT / (waves_k * 2) >= 4) waves_k *= 2;
-  int nwk = 1, ks = 1;
-  if (EPI == EPI_RESID) {
-    // split-K slices are summed by the next norm kernel, so K may also be split over blocks
-    while (ks < a.max_parts && (groups * ks < 256 || waves_k > MAX_NWK * ks)) ks *= 2;
-    waves_k = (waves_k + ks - 1) / ks;
-  }
-  while (nwk < MAX_NWK && nwk < waves_k) nwk *= 2;
-  if ((long)groups * nwk > 16384 && nwk > 1) nwk /= 2;
-  dim3 grid(groups, ks);
-#define PD_LAUNCH(NWK)                                                                          \
-  hipLaunchKernelGGL((k_gemm<RT, NT, (NWK <= MAX_NWK ? NWK : MAX_NWK), EPI, SPLIT>), grid,       \
-                     dim3(64 * (NWK <= MAX_NWK ? NWK : MAX_NWK)), 0, s, a)
-  switch (nwk) {
-    case 1: PD_LAUNCH(1); break;
-    case 2: PD_LAUNCH(2); break;
-    case 4: PD_LAUNCH(4); break;
-    case 8: PD_LAUNCH(8); break;
-    default: PD_LAUNCH(16); break;
-  }
-#undef PD_LAUNCH
-  PD_CHECK_HIP(hipGetLastError());
-  if (EPI == EPI_RESID && a.parts_out) *a.parts_out = ks;
-  return PD_OK;
-}
-
 // 1 or 2 row tiles.  Two column tiles per wave when that still leaves 128 or more blocks: the
 // activation fragments (2 KiB per k-tile with the low parts) are then requested once for 2 KiB of
 // weights instead of 1 KiB, and the vector-memory pipeline of a compute unit, which every request
@@ -606,9 +490,51 @@ static int launch_gemm_small(const GemmArgs &a, hipStream_t s) {
   return launch_gemm_small_nt<RT, 1, EPI, SPLIT, PACK>(a, ks, s);
 }
 
-int mfma_gemm_row_tiles(int rows) {
-  int rt = (rows + 15) / 16;
-  return (rt <= 1 ? 1 : rt <= 2 ? 2 : rt <= 4 ? 4 : rt <= 5 ? 5 : 8) * 16;
+// 4, 5 or 8 row tiles (many requests at once, prefill chunks).  Here the activation fragments of a
+// block (32-128 rows x K, high and low parts) outweigh its weights, every block has to request all
+// of them, and a compute unit's vector-memory pipeline is the limit, so what counts is how many
+// requests the busiest compute unit issues: rounds of 256 blocks x k-tiles per block x (NT weight
+// + 2 RT activation requests per k-tile).  The launch takes the column tiles per wave NT (and, for
+// the residual projections, the K slices over blocks) that minimise this count -- typically the
+// pair that makes exactly 256 blocks, one per compute unit: measured 29 us against 42 us for the
+// QKV projection of cfg5 with 256 instead of 384 blocks.  Blocks are 4 waves along K (one wave per
+// SIMD: registers for up to 8 x 4 accumulator tiles) and keep the compute unit to themselves.
+template <int RT, int NT, int EPI, bool SPLIT>
+static int launch_gemm_wide_nt(GemmArgs a, int ks, hipStream_t s) {
+  constexpr int NWK = 4;
+  constexpr int U = (NT + 2 * RT) <= 10 ? 4 : 2;
+  int KT = a.K / 32, groups = (a.n_tiles + NT - 1) / NT;
+  a.k_share = ((KT + ks - 1) / ks + NWK - 1) / NWK;
+  hipLaunchKernelGGL((k_gemm_s<RT, NT, NWK, U, EPI, SPLIT, false>), dim3(groups, ks), dim3(64 * NWK), 0, s, a);
+  PD_CHECK_HIP(hipGetLastError());
+  if (EPI == EPI_RESID && a.parts_out) *a.parts_out = ks;
+  return PD_OK;
+}
+
+template <int RT, int EPI, bool SPLIT>
+static int launch_gemm_wide(const GemmArgs &a, hipStream_t s) {
+  constexpr int NT_MAX = RT <= 4 ? 8 : (RT == 5 ? 6 : 4);     // 4 * NT * RT KiB of LDS, at most 128-160
+  static const int nts[] = {1, 2, 3, 4, 6, 8};
+  int KT = a.K / 32, best_nt = 1, best_ks = 1;
+  long best = -1;
+  for (int ks = 1; ks <= (EPI == EPI_RESID ? a.max_parts : 1); ks *= 2) {
+    if (ks > 1 && KT / ks < 8) break;
+    for (int nt : nts) {
+      if (nt > NT_MAX) break;
+      long blocks = (long)((a.n_tiles + nt - 1) / nt) * ks;
+      long rounds = (blocks + 255) / 256;
+      long cost = rounds * ((KT + ks - 1) / ks) * (nt + 2 * RT);
+      if (best < 0 || cost < best) { best = cost; best_nt = nt; best_ks = ks; }
+    }
+  }
+  switch (best_nt) {
+    case 1: return launch_gemm_wide_nt<RT, 1, EPI, SPLIT>(a, best_ks, s);
+    case 2: return launch_gemm_wide_nt<RT, 2, EPI, SPLIT>(a, best_ks, s);
+    case 3: return launch_gemm_wide_nt<RT, 3, EPI, SPLIT>(a, best_ks, s);
+    case 4: return launch_gemm_wide_nt<RT, 4, EPI, SPLIT>(a, best_ks, s);
+    case 6: return launch_gemm_wide_nt<RT, (NT_MAX >= 6 ? 6 : NT_MAX), EPI, SPLIT>(a, best_ks, s);
+    default: return launch_gemm_wide_nt<RT, (NT_MAX >= 8 ? 8 : NT_MAX), EPI, SPLIT>(a, best_ks, s);
+  }
 }
 
 template <int EPI, bool SPLIT>
@@ -616,9 +542,9 @@ static int launch_gemm_split(const GemmArgs &a, int rows, hipStream_t s) {
   switch (mfma_gemm_row_tiles(rows)) {
     case 16: return launch_gemm_small<1, EPI, SPLIT, false>(a, s);
     case 32: return launch_gemm_small<2, EPI, SPLIT, false>(a, s);
-    case 64: return launch_gemm_rt<4, 2, EPI, SPLIT>(a, s);
-    case 80: return launch_gemm_rt<5, 4, EPI, SPLIT>(a, s);
-    default: return launch_gemm_rt<8, 4, EPI, SPLIT>(a, s);
+    case 64: return launch_gemm_wide<4, EPI, SPLIT>(a, s);
+    case 80: return launch_gemm_wide<5, EPI, SPLIT>(a, s);
+    default: return launch_gemm_wide<8, EPI, SPLIT>(a, s);
   }
 }
 
@@ -632,15 +558,34 @@ static int launch_gemm(const GemmArgs &a, int rows, hipStream_t s) {
   return a.xn_lo ? launch_gemm_split<EPI, true>(a, rows, s) : launch_gemm_split<EPI, false>(a, rows, s);
 }
 
+// one translation unit per epilogue
+int PD_GEMM_ENTRY(const GemmArgs &a, int rows, hipStream_t s) { return launch_gemm<PD_GEMM_EPI>(a, rows, s); }
+
+#else   // ---- common part: dispatcher ----------------------------------------------------------
+
+int mfma_gemm_row_tiles(int rows) {
+  int rt = (rows + 15) / 16;
+  return (rt <= 1 ? 1 : rt <= 2 ? 2 : rt <= 4 ? 4 : rt <= 5 ? 5 : 8) * 16;
+}
+
+int mfma_gemm_epi0(const GemmArgs &a, int rows, hipStream_t s);
+int mfma_gemm_epi1(const GemmArgs &a, int rows, hipStream_t s);
+int mfma_gemm_epi2(const GemmArgs &a, int rows, hipStream_t s);
+int mfma_gemm_epi3(const GemmArgs &a, int rows, hipStream_t s);
+int mfma_gemm_epi4(const GemmArgs &a, int rows, hipStream_t s);
+int mfma_gemm_epi5(const GemmArgs &a, int rows, hipStream_t s);
+
 int mfma_gemm(int epi, const GemmArgs &a, int rows, hipStream_t s) {
   switch (epi) {
-    case EPI_QKV: return launch_gemm<EPI_QKV>(a, rows, s);
-    case EPI_QKV_ROPE: return launch_gemm<EPI_QKV_ROPE>(a, rows, s);
-    case EPI_RESID: return launch_gemm<EPI_RESID>(a, rows, s);
-    case EPI_GELU: return launch_gemm<EPI_GELU>(a, rows, s);
-    case EPI_SWIGLU: return launch_gemm<EPI_SWIGLU>(a, rows, s);
-    case EPI_LM: return launch_gemm<EPI_LM>(a, rows, s);
+    case EPI_QKV: return mfma_gemm_epi0(a, rows, s);
+    case EPI_QKV_ROPE: return mfma_gemm_epi1(a, rows, s);
+    case EPI_RESID: return mfma_gemm_epi2(a, rows, s);
+    case EPI_GELU: return mfma_gemm_epi3(a, rows, s);
+    case EPI_SWIGLU: return mfma_gemm_epi4(a, rows, s);
+    case EPI_LM: return mfma_gemm_epi5(a, rows, s);
   }
   pd_set_error("unknown epilogue %d", epi);
   return PD_EINVAL;
 }
+
+#endif
