@@ -295,11 +295,10 @@ __global__ __launch_bounds__(256) void k_attn_merge(AttnArgs a) {
 static int pick_splits(pd_ctx *c, int units, int nblk) {
   int cap = std::max(1, 4096 / units);
   if (c->opt_splits > 0) return std::min(c->opt_splits, cap);
-  // Few (request, head) units (a single long context): one block per compute unit, every wave
-  // streams several key blocks back to back (measured at 16 heads x 8k keys: 16.2 us with 256
-  // blocks, 17.2 with 512 or 768, 18.7 with 320).  Many units: about 3 blocks per compute unit.
-  // Always at least one key block per wave.
-  int want = std::max(1, (units <= 32 ? 256 : 768) / units);
+  // One block per compute unit, every wave streaming several key blocks back to back (measured at
+  // 16 heads x 8k keys: 16.2 us with 256 blocks, 17.2 with 512 or 768, 18.7 with 320; at 4 x 32 heads
+  // x 4k keys 256 blocks are 4 us per launch faster than 768).  Always at least one key block per wave.
+  int want = std::max(1, 256 / units);
   int by_keys = std::max(1, nblk / 4);
   return std::max(1, std::min(std::min(want, by_keys), cap));
 }
