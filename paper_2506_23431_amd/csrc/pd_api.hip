@@ -76,7 +76,7 @@ static size_t carve(const pd_config *g, char *base, pd_ctx *c) {
   x->gen_cap = S * (M + 1);
   x->gen_stride = (x->gen_cap + 8 + 7) / 8 * 8;
   x->kv_cap = (g->max_ctx + x->gen_cap + 63) / 64 * 64;
-  x->prefill_chunk = 64;
+  x->prefill_chunk = 128;
   int a_max = std::min(S, M + 1);
   x->R_cap = std::max(B * a_max, x->prefill_chunk);
   // row buffers are read in tiles of 16 rows, 1/2/4/8 tiles per launch
