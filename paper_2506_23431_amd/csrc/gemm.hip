@@ -447,7 +447,7 @@ __global__ __launch_bounds__(64 * NW_K) void k_gemm_s(GemmArgs a) {
 // ---------------------------------------------------------------------------
 // launch
 // ---------------------------------------------------------------------------
-// 1 or 2 row tiles.  Two column tiles per wave when that still leaves 128 or more blocks: the
+// 1 row tile.  Two column tiles per wave when that still leaves 128 or more blocks: the
 // activation fragments (2 KiB per k-tile with the low parts) are then requested once for 2 KiB of
 // weights instead of 1 KiB, and the vector-memory pipeline of a compute unit, which every request
 // occupies for the same time whether it is served by HBM or by L2, has a third less to do.  A
@@ -490,7 +490,7 @@ static int launch_gemm_small(const GemmArgs &a, hipStream_t s) {
   return launch_gemm_small_nt<RT, 1, EPI, SPLIT, PACK>(a, ks, s);
 }
 
-// 4, 5 or 8 row tiles (many requests at once, prefill chunks).  Here the activation fragments of a
+// 2, 4, 5 or 8 row tiles (many rows per request, many requests at once, prefill chunks).  Here the activation fragments of a
 // block (32-128 rows x K, high and low parts) outweigh its weights, every block has to request all
 // of them, and a compute unit's vector-memory pipeline is the limit, so what counts is how many
 // requests the busiest compute unit issues: rounds of 256 blocks x k-tiles per block x (NT weight
@@ -513,7 +513,8 @@ static int launch_gemm_wide_nt(GemmArgs a, int ks, hipStream_t s) {
 
 template <int RT, int EPI, bool SPLIT>
 static int launch_gemm_wide(const GemmArgs &a, hipStream_t s) {
-  constexpr int NT_MAX = RT <= 4 ? 8 : (RT == 5 ? 6 : 4);     // 4 * NT * RT KiB of LDS, at most 128-160
+  // 4 * NT * RT KiB of LDS, at most 128-160; with 2 row tiles more than 4 column tiles measured slower
+  constexpr int NT_MAX = RT <= 2 ? 4 : (RT <= 4 ? 8 : (RT == 5 ? 6 : 4));
   static const int nts[] = {1, 2, 3, 4, 6, 8};
   int KT = a.K / 32, best_nt = 1, best_ks = 1;
   long best = -1;
@@ -541,7 +542,7 @@ template <int EPI, bool SPLIT>
 static int launch_gemm_split(const GemmArgs &a, int rows, hipStream_t s) {
   switch (mfma_gemm_row_tiles(rows)) {
     case 16: return launch_gemm_small<1, EPI, SPLIT, false>(a, s);
-    case 32: return launch_gemm_small<2, EPI, SPLIT, false>(a, s);
+    case 32: return launch_gemm_wide<2, EPI, SPLIT>(a, s);
     case 64: return launch_gemm_wide<4, EPI, SPLIT>(a, s);
     case 80: return launch_gemm_wide<5, EPI, SPLIT>(a, s);
     default: return launch_gemm_wide<8, EPI, SPLIT>(a, s);
