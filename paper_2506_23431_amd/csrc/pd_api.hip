@@ -45,6 +45,8 @@ static int check_config(const pd_config *g) {
   PD_REQUIRE(g->eos_id < g->vocab, PD_EINVAL, "eos_id out of range");
   PD_REQUIRE((int64_t)g->max_sub * (g->max_sub_tokens + 1) + g->max_ctx < (1 << 24), PD_EINVAL,
              "KV capacity too large");
+  PD_REQUIRE(g->max_sub <= 65535, PD_EINVAL, "max_sub = %d exceeds 65535 (subsequence tags are 16 bit)",
+             g->max_sub);
   return PD_OK;
 }
 

@@ -64,7 +64,7 @@ def test_workspace_sizes(lib):
 
 @pytest.mark.parametrize("bad", [dict(n_head=3), dict(head_dim=7, n_head=1, d_model=7), dict(dtype=2),
                                  dict(ffn_kind=5), dict(max_batch=0), dict(bos_id=-1), dict(norm_eps=0.0),
-                                 dict(eos_id=10 ** 6)])
+                                 dict(eos_id=10 ** 6), dict(max_sub=70000, max_sub_tokens=1)])
 def test_invalid_configurations_are_rejected(lib, bad):
     cfg = pi.get_config("cfg1")
     assert lib.pd_workspace_bytes(C.byref(config_struct(cfg, **bad))) == 0
