@@ -318,3 +318,18 @@ def test_sweep_runs_sequential_and_pipelined():
         assert r["steps"] == (S - 1) * dt + 64 // S
         assert r["tokens_per_s"] > 0
     assert got[(1, 1)]["speedup_vs_sequential"] == 1.0
+
+
+def test_plain_read_bandwidth_measurement():
+    """pd_measure_read_bandwidth: sane figure for a 64 MB chunk out of a 1 GiB buffer, errors for bad arguments."""
+    import torch
+    from paper_2506_23431_amd import binding, PdError
+    buf = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    gbs = binding.measure_read_bandwidth(buf.data_ptr(), buf.numel(), 64 << 20, 50)
+    say(f"[read] 64 MiB chunks: {gbs:.0f} GB/s")
+    assert 1000 < gbs < 8000          # below the 8 TB/s peak, far above anything a broken kernel would show
+    with pytest.raises(PdError, match="chunk_bytes"):
+        binding.measure_read_bandwidth(buf.data_ptr(), buf.numel(), buf.numel(), 1)
+    with pytest.raises(PdError, match="aligned"):
+        binding.measure_read_bandwidth(buf.data_ptr() + 4, buf.numel() - 4, 1 << 20, 1)
