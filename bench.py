@@ -20,6 +20,7 @@ Prints ONE JSON line: generated tokens/s over exactly K steps, plus
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -190,10 +191,12 @@ def main():
     tokens = cfg.batch * sum(producing(cfg, t) for t in range(1, K + 1))
     abytes = attention_bytes(cfg, K)
     achieved = abytes / (attn_us * 1e-6) / 1e9 if attn_us > 0 else 0.0
+    # HBM bytes per launch from the rocprofv3 counter runs summarised under profiles/ (null if none)
     traffic = None
-    pmc = os.path.join(ROOT, "profiles", f"attention_{cfg.name}_hbm_traffic.json")
+    pmc = os.path.join(ROOT, "profiles", f"attention_{cfg.name}_hbm_traffic.md")
     if os.path.exists(pmc):
-        traffic = json.load(open(pmc)).get("bytes_per_launch")
+        m = re.search(r"bytes_per_launch\s*=\s*(\d+)", open(pmc).read())
+        traffic = float(m.group(1)) if m else None
     out = {
         "metric": "pipelined_decode_generated_tokens_per_s", "value": tokens / elapsed, "unit": "tokens/s",
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": elapsed / K * 1e3,
