@@ -47,6 +47,8 @@ CASES = {
                        d_ff=256, vocab=1003, ctx_len=150, n_sub=5, delta_t=2, sub_tokens=7),
     "mfma-hd32": small("mfma-hd32", seed=26, dtype=DTYPE_BF16, d_model=96, n_head=3, head_dim=32,
                        d_ff=160, vocab=517, ctx_len=75, n_sub=4, delta_t=1, sub_tokens=5, batch=3),
+    "mfma-hd96": small("mfma-hd96", seed=32, dtype=DTYPE_BF16, d_model=192, n_head=2, head_dim=96,
+                       d_ff=224, vocab=611, ctx_len=110, n_sub=5, delta_t=2, sub_tokens=8, batch=2),
     "mfma-hd128-llama": small("mfma-hd128-llama", seed=27, dtype=DTYPE_BF16, d_model=256, n_head=2,
                               head_dim=128, d_ff=352, vocab=777, ctx_len=200, n_sub=6, delta_t=2,
                               sub_tokens=9, batch=2, **LLAMA),
