@@ -173,6 +173,35 @@ def test_degenerate_and_extreme_schedules(name):
     dec.close()
 
 
+def _random_case(k):
+    """Seeded random small workload k: widths, schedule and batch drawn so that the cases cover one
+    to five row tiles, packed and general activation layouts, ragged contexts and early stops."""
+    rng = np.random.default_rng(1000 + k)
+    hd = int(rng.choice([32, 64, 96, 128]))
+    nh = int(rng.integers(1, 4))
+    llama = bool(rng.integers(0, 2))
+    kw = dict(seed=60 + k, dtype=DTYPE_BF16, d_model=hd * nh, n_head=nh, head_dim=hd,
+              d_ff=int(rng.choice([96, 160, 224, 320])), vocab=int(rng.integers(130, 900)),
+              ctx_len=int(rng.integers(1, 300)), n_sub=int(rng.integers(1, 12)), delta_t=int(rng.integers(1, 6)),
+              sub_tokens=int(rng.integers(1, 10)), batch=int(rng.integers(1, 6)), n_layer=int(rng.integers(1, 3)))
+    if llama:
+        kw.update(LLAMA)
+    return small(f"mfma-random-{k}", **kw)
+
+
+@pytest.mark.parametrize("k", range(12))
+def test_random_small_workloads(k):
+    cfg = _random_case(k)
+    say(f"[case] {cfg}")
+    w = pi.make_weights(cfg, threads=4)
+    ctx = pi.make_context(cfg)
+    outs = oracle_run(cfg, w, ctx)
+    dec = make_decoder(cfg, w)
+    stats = compare_teacher_forced(cfg, w, ctx, dec, outs, log=say)
+    assert stats["rows"] > 0
+    dec.close()
+
+
 def test_more_than_128_rows_is_an_error_on_the_matrix_core_path():
     from paper_2506_23431_amd import PdError
     cfg = small("mfma-r144", seed=50, n_sub=16, delta_t=1, sub_tokens=15, batch=9, ctx_len=40, n_layer=1, **MF)
