@@ -102,6 +102,9 @@ def main():
     ap.add_argument("--workload", default="cfg4")
     ap.add_argument("--graph", type=int, default=0, help="replay each step from a captured HIP graph")
     ap.add_argument("--attn-splits", type=int, default=0)
+    ap.add_argument("--kv-pair-layers", type=int, default=0,
+                    help="leading layers whose cache keeps keys and values as pairs of halves (cfg5 needs 1 "
+                         "to stay inside the logit tolerance; cfg1-cfg4 do not)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sync-every", type=int, default=0,
                     help="synchronise after every N iterations of the timed pass (0: never; a counter-collecting "
@@ -132,7 +135,8 @@ def main():
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
         dec = PipelinedDecoder(cfg, weights, max_batch=cfg.batch, max_ctx=cfg.ctx_len, max_sub=cfg.n_sub,
-                               max_sub_tokens=cfg.sub_tokens, max_pos=max_positions(cfg))
+                               max_sub_tokens=cfg.sub_tokens, max_pos=max_positions(cfg),
+                               kv_pair_layers=args.kv_pair_layers)
         dec.set_option(binding.PD_OPT_USE_GRAPH, args.graph)
         dec.set_option(binding.PD_OPT_ATTN_SPLITS, args.attn_splits)
         if args.calibrate_copy_mb > 0:
@@ -189,7 +193,8 @@ def main():
         dec.close()
 
     tokens = cfg.batch * sum(producing(cfg, t) for t in range(1, K + 1))
-    abytes = attention_bytes(cfg, K)
+    # a pair layer reads every key and value twice (high and low halves)
+    abytes = attention_bytes(cfg, K) * (1.0 + args.kv_pair_layers / cfg.n_layer)
     achieved = abytes / (attn_us * 1e-6) / 1e9 if attn_us > 0 else 0.0
     # HBM bytes per launch from the rocprofv3 counter runs summarised under profiles/ (null if none)
     traffic = None
@@ -207,7 +212,8 @@ def main():
                                f"batch {cfg.batch}, context {cfg.ctx_len}, S={cfg.n_sub}, dt={cfg.delta_t}, "
                                f"M={cfg.sub_tokens}",
                    "tokens_generated": tokens, "time_steps_full_run": cfg.time_steps,
-                   "prefill_s": prefill_s, "hip_graph": bool(args.graph)},
+                   "prefill_s": prefill_s, "hip_graph": bool(args.graph),
+                   "kv_pair_layers": args.kv_pair_layers},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "kernel": "k_attn_mfma (masked multi-query attention over the KV cache, one launch "

@@ -55,6 +55,12 @@ typedef struct {
   int32_t bos_id, eos_id;   /* eos_id < 0 disables end-of-sequence termination             */
   int32_t max_batch, max_ctx, max_sub, max_sub_tokens;   /* capacity (workspace sizing)    */
   int32_t max_pos;     /* rows of the learned position table (ignored for rotary)          */
+  int32_t kv_pair_layers;   /* dtype 1: the first kv_pair_layers layers keep every key and value as
+                             * a pair of halves (value = high + low, about 22 significant bits; twice
+                             * the cache bytes and attention traffic of those layers).  0: none.
+                             * The first layer's attention output is the whole residual stream
+                             * behind it, so its cache rounding reaches the logits undiluted; with
+                             * 32 layers of width 4096 that alone is 2e-2.  Ignored for dtype 0.   */
 } pd_config;
 
 /* Device pointers to the weights; per-layer entries are HOST arrays of n_layer

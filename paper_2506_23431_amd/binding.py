@@ -28,7 +28,7 @@ class PdConfig(C.Structure):
                                          "ffn_kind", "norm_kind", "pos_kind")] + \
                [("rope_base", C.c_float), ("norm_eps", C.c_float)] + \
                [(n, C.c_int32) for n in ("dtype", "bos_id", "eos_id", "max_batch", "max_ctx", "max_sub",
-                                         "max_sub_tokens", "max_pos")]
+                                         "max_sub_tokens", "max_pos", "kv_pair_layers")]
 
 
 class PdWeights(C.Structure):
@@ -86,10 +86,11 @@ class PipelinedDecoder:
     shape: object with the model fields of pd_config (n_layer, d_model, ...),
     weights: dict of numpy arrays as produced by pd_inputs.make_weights
     (uint16 = bf16 bit patterns, float32 otherwise).
+    kv_pair_layers: number of leading layers whose cache keeps keys and values as pairs of halves.
     """
 
     def __init__(self, shape, weights, max_batch, max_ctx, max_sub, max_sub_tokens, max_pos,
-                 device="cuda:0"):
+                 device="cuda:0", kv_pair_layers=0):
         import torch
         self.torch = torch
         self.lib = load()
@@ -100,7 +101,8 @@ class PipelinedDecoder:
             d_ff=shape.d_ff, vocab=shape.vocab, ffn_kind=shape.ffn_kind, norm_kind=shape.norm_kind,
             pos_kind=shape.pos_kind, rope_base=shape.rope_base, norm_eps=shape.norm_eps,
             dtype=shape.dtype, bos_id=shape.bos_id, eos_id=shape.eos_id, max_batch=max_batch,
-            max_ctx=max_ctx, max_sub=max_sub, max_sub_tokens=max_sub_tokens, max_pos=max_pos)
+            max_ctx=max_ctx, max_sub=max_sub, max_sub_tokens=max_sub_tokens, max_pos=max_pos,
+            kv_pair_layers=kv_pair_layers)
         self.vocab = shape.vocab
         self._keep = []          # device tensors referenced by the library
 

@@ -23,6 +23,7 @@
 struct AttnArgs {
   const f16_t *q, *q_lo;    // [rows][d] fp16 high / low parts (q_lo NULL: high part only)
   const f16_t *kc, *vc;     // packed fp16 caches of this layer
+  const f16_t *kc_lo, *vc_lo;   // low halves of the same layout (PAIR kernels only)
   bf16_t *out, *out_lo;     // [rows][d] high / low parts (out_lo NULL: high part only)
   RowTables rt;
   const int32_t *kv_len;
@@ -33,8 +34,11 @@ struct AttnArgs {
   float scale_log2;         // log2(e) / sqrt(hd)
 };
 
-template <int HD, bool SPLIT>
-__global__ __launch_bounds__(256, 3) void k_attn_mfma(AttnArgs a) {
+// PAIR: the layer keeps keys and values as high + low halves.  Scores add q_hi K_lo (q_lo K_lo is
+// below the rounding of everything else), outputs add P V_lo; the kernel holds twice the fragments
+// and is built for one block per compute unit.
+template <int HD, bool SPLIT, bool PAIR>
+__global__ __launch_bounds__(256, PAIR ? 1 : 3) void k_attn_mfma(AttnArgs a) {
   constexpr int NC = HD / 32, NHB = HD / 16, PSTR = HD + 2;   // partial: m, l, O[HD] per query
   __shared__ float sm_m[4][16], sm_l[4][16];
   __shared__ floatx4 sm_o[4][HD / 16][64];
@@ -69,6 +73,8 @@ __global__ __launch_bounds__(256, 3) void k_attn_mfma(AttnArgs a) {
 
   const uint4 *Kp = (const uint4 *)(a.kc + ((size_t)req * a.H + h) * a.kv_cap * HD) + lane;
   const uint4 *Vp = (const uint4 *)(a.vc + ((size_t)req * a.H + h) * a.kv_cap * HD) + lane;
+  const uint4 *Kl = PAIR ? (const uint4 *)(a.kc_lo + ((size_t)req * a.H + h) * a.kv_cap * HD) + lane : nullptr;
+  const uint4 *Vl = PAIR ? (const uint4 *)(a.vc_lo + ((size_t)req * a.H + h) * a.kv_cap * HD) + lane : nullptr;
   // subsequence tags of the generated-side slots, 8 keys (16 bytes) per lane group
   const uint16_t *gs = a.gen_sub + (size_t)req * a.gen_stride;
   const int L8 = a.L & ~7;
@@ -77,18 +83,25 @@ __global__ __launch_bounds__(256, 3) void k_attn_mfma(AttnArgs a) {
   const int stride = 4 * a.nsplit;
   int kb = split * 4 + wave;
   Frag kf[2][NC], vf[NHB];
+  Frag kl[PAIR ? 2 : 1][PAIR ? NC : 1], vl[PAIR ? NHB : 1];
   union { uint4 u; uint16_t s[8]; } tg;
   auto load_k = [&](int kbx) {
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
-      for (int c = 0; c < NC; ++c) kf[t][c].u = Kp[((size_t)(kbx * 2 + t) * NC + c) * 64];
+      for (int c = 0; c < NC; ++c) {
+        kf[t][c].u = Kp[((size_t)(kbx * 2 + t) * NC + c) * 64];
+        if (PAIR) kl[t][c].u = Kl[((size_t)(kbx * 2 + t) * NC + c) * 64];
+      }
   };
   auto load_v = [&](int kbx) {
     // tags of the lane's 8 keys (clamped: context blocks read entry 0 and never use it)
     tg.u = *(const uint4 *)(gs + min(max(kbx * 32 + 8 * g - L8, 0), a.gen_stride - 8));
 #pragma unroll
-    for (int i = 0; i < NHB; ++i) vf[i].u = Vp[((size_t)kbx * NHB + i) * 64];
+    for (int i = 0; i < NHB; ++i) {
+      vf[i].u = Vp[((size_t)kbx * NHB + i) * 64];
+      if (PAIR) vl[i].u = Vl[((size_t)kbx * NHB + i) * 64];
+    }
   };
   // requested unconditionally (a wave beyond the last block fetches that block and ignores it), so
   // that the wait for the query rows above never has to wait for these
@@ -136,6 +149,10 @@ __global__ __launch_bounds__(256, 3) void k_attn_mfma(AttnArgs a) {
       qf.u = sm_q[c][ql_lane];
       s[0] = mfma16h(kf[0][c], qf, s[0]);
       s[1] = mfma16h(kf[1][c], qf, s[1]);
+      if (PAIR) {
+        s[0] = mfma16h(kl[0][c], qf, s[0]);
+        s[1] = mfma16h(kl[1][c], qf, s[1]);
+      }
       if (SPLIT) {
         qf.u = sm_q[NC + c][ql_lane];
         s[0] = mfma16h(kf[0][c], qf, s[0]);
@@ -177,15 +194,24 @@ __global__ __launch_bounds__(256, 3) void k_attn_mfma(AttnArgs a) {
     l_run = l_run * alpha + psum;
     m_run = m_new;
     // probabilities enter the matrix core as fp16 (the same 11 significant bits as the values they multiply)
-    Frag pf;
+    Frag pf, pl;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) pf.hh[e] = (f16_t)p[e];
+    for (int e = 0; e < 8; ++e) {
+      pf.hh[e] = (f16_t)p[e];
+      if (PAIR) pl.hh[e] = (f16_t)(p[e] - (float)pf.hh[e]);
+    }
     if (__any(alpha != 1.f)) {                // the running maximum of some query moved: rescale
 #pragma unroll
       for (int i = 0; i < NHB; ++i) o_acc[i] *= alpha;
     }
 #pragma unroll
-    for (int i = 0; i < NHB; ++i) o_acc[i] = mfma16h(vf[i], pf, o_acc[i]);
+    for (int i = 0; i < NHB; ++i) {
+      o_acc[i] = mfma16h(vf[i], pf, o_acc[i]);
+      if (PAIR) {
+        o_acc[i] = mfma16h(vl[i], pf, o_acc[i]);
+        o_acc[i] = mfma16h(vf[i], pl, o_acc[i]);
+      }
+    }
     if (more) load_v(kn);
     kb = kn;
   }
@@ -309,6 +335,7 @@ int mfma_attention(pd_ctx *c, const LayerPtrs &lw, int A, int nreq, int req0, in
   AttnArgs a;
   a.q = (const f16_t *)c->q; a.q_lo = (const f16_t *)mfma_lo(c, c->q, g.d_model);
   a.out_lo = mfma_lo(c, c->att, g.d_model); a.kc = (const f16_t *)lw.kc; a.vc = (const f16_t *)lw.vc;
+  a.kc_lo = (const f16_t *)lw.kc_lo; a.vc_lo = (const f16_t *)lw.vc_lo;
   a.out = (bf16_t *)c->att; a.rt = c->rows; a.kv_len = c->sch.kv_len; a.gen_sub = c->sch.gen_sub;
   a.kv_override = kv_override; a.part = c->att_part;
   a.d = g.d_model; a.H = g.n_head; a.kv_cap = c->kv_cap; a.gen_stride = c->gen_stride; a.L = c->L;
@@ -337,12 +364,15 @@ int mfma_attention(pd_ctx *c, const LayerPtrs &lw, int A, int nreq, int req0, in
     if (c->opt_profile == 2) PD_CHECK_HIP(hipEventRecord(ev0, s));
   }
   const bool attach = prof && c->opt_profile == 1;
+  hipEvent_t pe0 = attach ? ev0 : nullptr, pe1 = attach ? ev1 : nullptr;
 #define PD_ATTN(HDV)                                                                        \
   do {                                                                                      \
-    if (attach && a.q_lo) hipExtLaunchKernelGGL((k_attn_mfma<HDV, true>), grid, dim3(256), 0, s, ev0, ev1, 0, a);  \
-    else if (attach) hipExtLaunchKernelGGL((k_attn_mfma<HDV, false>), grid, dim3(256), 0, s, ev0, ev1, 0, a);      \
-    else if (a.q_lo) hipLaunchKernelGGL((k_attn_mfma<HDV, true>), grid, dim3(256), 0, s, a);  \
-    else hipLaunchKernelGGL((k_attn_mfma<HDV, false>), grid, dim3(256), 0, s, a);           \
+    if (a.kc_lo && a.q_lo) hipExtLaunchKernelGGL((k_attn_mfma<HDV, true, true>), grid, dim3(256), 0, s, pe0, pe1, 0, a);  \
+    else if (a.kc_lo) hipExtLaunchKernelGGL((k_attn_mfma<HDV, false, true>), grid, dim3(256), 0, s, pe0, pe1, 0, a);    \
+    else if (attach && a.q_lo) hipExtLaunchKernelGGL((k_attn_mfma<HDV, true, false>), grid, dim3(256), 0, s, ev0, ev1, 0, a);  \
+    else if (attach) hipExtLaunchKernelGGL((k_attn_mfma<HDV, false, false>), grid, dim3(256), 0, s, ev0, ev1, 0, a);      \
+    else if (a.q_lo) hipLaunchKernelGGL((k_attn_mfma<HDV, true, false>), grid, dim3(256), 0, s, a);  \
+    else hipLaunchKernelGGL((k_attn_mfma<HDV, false, false>), grid, dim3(256), 0, s, a);           \
     if (a.nsplit > 1)                                                                       \
       hipLaunchKernelGGL(k_attn_merge<HDV>, dim3(units, HDV / 16), dim3(256), 0, s, a);            \
   } while (0)

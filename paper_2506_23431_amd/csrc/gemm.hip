@@ -304,11 +304,15 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int nt, const f
         size_t head_base = ((size_t)kvi[i].y * a.H + h) * a.kv_cap * a.hd;
         int slot = kvi[i].z;
         if (sec == 1) {
-          store4_split_h(a.kc, nullptr, head_base + k_cache_off(slot, dim0, a.hd), y);
+          store4_split_h(a.kc, a.kc_lo, head_base + k_cache_off(slot, dim0, a.hd), y);
         } else {
 #pragma unroll
-          for (int j = 0; j < 4; ++j)
-            a.vc[head_base + v_cache_off(slot, dim0 + j, a.hd)] = f32_to_f16_sat(y[j]);
+          for (int j = 0; j < 4; ++j) {
+            size_t o = head_base + v_cache_off(slot, dim0 + j, a.hd);
+            f16_t hi = f32_to_f16_sat(y[j]);
+            a.vc[o] = hi;
+            if (a.vc_lo) a.vc_lo[o] = (f16_t)(y[j] - (float)hi);
+          }
         }
       }
     }

@@ -112,6 +112,7 @@ struct GemmArgs {
   bf16_t *out_lo;        // low parts of out_bf (written when not NULL)
   int ld;
   f16_t *kc, *vc;        // EPI_QKV*: caches of this layer (fp16)
+  f16_t *kc_lo, *vc_lo;  // their low halves, or NULL
   RowTables rt;
   const float *rope_cs;
   int d, H, hd, kv_cap;

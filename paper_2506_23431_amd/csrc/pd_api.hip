@@ -41,6 +41,8 @@ static int check_config(const pd_config *g) {
   PD_REQUIRE(g->max_batch >= 1 && g->max_ctx >= 1 && g->max_sub >= 1 && g->max_sub_tokens >= 1,
              PD_EINVAL, "capacities (max_batch, max_ctx, max_sub, max_sub_tokens) must be >= 1");
   PD_REQUIRE(g->max_pos >= 1, PD_EINVAL, "max_pos must be >= 1");
+  PD_REQUIRE(g->kv_pair_layers >= 0 && g->kv_pair_layers <= g->n_layer, PD_EINVAL,
+             "kv_pair_layers = %d outside [0, n_layer]", g->kv_pair_layers);
   PD_REQUIRE(g->bos_id >= 0 && g->bos_id < g->vocab, PD_EINVAL, "bos_id out of range");
   PD_REQUIRE(g->eos_id < g->vocab, PD_EINVAL, "eos_id out of range");
   PD_REQUIRE((int64_t)g->max_sub * (g->max_sub_tokens + 1) + g->max_ctx < (1 << 24), PD_EINVAL,
@@ -93,6 +95,9 @@ static size_t carve(const pd_config *g, char *base, pd_ctx *c) {
   for (int l = 0; l < g->n_layer; ++l) {
     x->layers[l].kc = cv.take<char>(x->kv_layer_bytes);
     x->layers[l].vc = cv.take<char>(x->kv_layer_bytes);
+    bool pair = g->dtype == 1 && l < g->kv_pair_layers;
+    x->layers[l].kc_lo = pair ? cv.take<char>(x->kv_layer_bytes) : nullptr;
+    x->layers[l].vc_lo = pair ? cv.take<char>(x->kv_layer_bytes) : nullptr;
   }
   size_t Rp = x->R_pad;
   x->x = cv.take<float>(Rp * d);

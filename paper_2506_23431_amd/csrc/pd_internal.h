@@ -105,6 +105,7 @@ struct LayerPtrs {
   // MFMA path: re-packed copies inside the workspace
   bf16_t *p_wqkv, *p_wo, *p_w1, *p_w2;
   void *kc, *vc;                                   // KV caches of this layer
+  void *kc_lo, *vc_lo;                             // low halves (layers below kv_pair_layers), else NULL
 };
 
 struct pd_ctx {

@@ -109,8 +109,8 @@ static int linear(pd_ctx *c, float *out, const float *x, const void *W, const vo
 // written to the row's slot of the request's cache.
 // ---------------------------------------------------------------------------
 template <typename KT>
-__global__ void k_qkv_post(float *qkv, KT *kc, KT *vc, RowTables rt, const float *rope_cs, int d,
-                           int H, int hd, int kv_cap) {
+__global__ void k_qkv_post(float *qkv, KT *kc, KT *vc, KT *kc_lo, KT *vc_lo, RowTables rt,
+                           const float *rope_cs, int d, int H, int hd, int kv_cap) {
   int r = blockIdx.x;
   if (!(rt.flags[r] & ROW_VALID)) return;
   float *row = qkv + (size_t)r * 3 * d;
@@ -130,9 +130,13 @@ __global__ void k_qkv_post(float *qkv, KT *kc, KT *vc, RowTables rt, const float
       row[h * hd + j] = q1; row[h * hd + j + half] = q2;
     }
     size_t o = base + (size_t)h * kv_cap * hd;
+    float v1 = row[2 * d + h * hd + j], v2 = row[2 * d + h * hd + j + half];
     st_f32(kc, o + j, k1); st_f32(kc, o + j + half, k2);
-    st_f32(vc, o + j, row[2 * d + h * hd + j]);
-    st_f32(vc, o + j + half, row[2 * d + h * hd + j + half]);
+    st_f32(vc, o + j, v1); st_f32(vc, o + j + half, v2);
+    if (kc_lo) {      // low halves: what the rounding of the stores above left out
+      st_f32(kc_lo, o + j, k1 - ld_f32(kc, o + j)); st_f32(kc_lo, o + j + half, k2 - ld_f32(kc, o + j + half));
+      st_f32(vc_lo, o + j, v1 - ld_f32(vc, o + j)); st_f32(vc_lo, o + j + half, v2 - ld_f32(vc, o + j + half));
+    }
   }
 }
 
@@ -143,7 +147,8 @@ __global__ void k_qkv_post(float *qkv, KT *kc, KT *vc, RowTables rt, const float
 // Three passes over a score scratch in global memory.
 // ---------------------------------------------------------------------------
 template <typename KT>
-__global__ void k_attn(float *out, const float *qkv, const KT *kc, const KT *vc, float *scores,
+__global__ void k_attn(float *out, const float *qkv, const KT *kc, const KT *vc, const KT *kc_lo,
+                       const KT *vc_lo, float *scores,
                        RowTables rt, const int32_t *kv_len, const uint16_t *gen_sub, int kv_override,
                        int d, int H, int hd, int kv_cap, int gen_stride, int L, float scale) {
   extern __shared__ float sm[];     // q[hd] | red[16] | o[blockDim.x]
@@ -154,6 +159,8 @@ __global__ void k_attn(float *out, const float *qkv, const KT *kc, const KT *vc,
   int n = kv_override >= 0 ? kv_override : kv_len[req];
   const KT *K = kc + ((size_t)req * H + h) * kv_cap * hd;
   const KT *V = vc + ((size_t)req * H + h) * kv_cap * hd;
+  const KT *Kl = kc_lo ? kc_lo + ((size_t)req * H + h) * kv_cap * hd : nullptr;
+  const KT *Vl = vc_lo ? vc_lo + ((size_t)req * H + h) * kv_cap * hd : nullptr;
   const uint16_t *gs = gen_sub + (size_t)req * gen_stride;
   const int L8 = L & ~7;            // entry of key slot j >= L is j - L8
   float *sc = scores + ((size_t)r * H + h) * kv_cap;
@@ -165,7 +172,11 @@ __global__ void k_attn(float *out, const float *qkv, const KT *kc, const KT *vc,
     float s = -INFINITY;
     if (vis) {
       s = 0.f;
-      for (int c = 0; c < hd; ++c) s = fmaf(qs[c], ld_f32(K, (size_t)j * hd + c), s);
+      for (int c = 0; c < hd; ++c) {
+        float kv = ld_f32(K, (size_t)j * hd + c);
+        if (Kl) kv += ld_f32(Kl, (size_t)j * hd + c);
+        s = fmaf(qs[c], kv, s);
+      }
       s *= scale;
     }
     sc[j] = s;
@@ -187,7 +198,11 @@ __global__ void k_attn(float *out, const float *qkv, const KT *kc, const KT *vc,
   int G = blockDim.x / hd, g = threadIdx.x / hd, c = threadIdx.x % hd;
   float acc = 0.f;
   if (g < G)
-    for (int j = g; j < n; j += G) acc = fmaf(sc[j], ld_f32(V, (size_t)j * hd + c), acc);
+    for (int j = g; j < n; j += G) {
+      float vv = ld_f32(V, (size_t)j * hd + c);
+      if (Vl) vv += ld_f32(Vl, (size_t)j * hd + c);
+      acc = fmaf(sc[j], vv, acc);
+    }
   osum[threadIdx.x] = acc;
   __syncthreads();
   if (threadIdx.x < hd) {
@@ -246,16 +261,20 @@ int simple_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_over
   size_t shm = (hd + 16 + 256) * sizeof(float);
   if (g.dtype == 0) {
     hipLaunchKernelGGL(k_qkv_post<float>, dim3(R), dim3(256), 0, s, c->qkv32, (float *)lw.kc,
-                       (float *)lw.vc, c->rows, cs, d, H, hd, c->kv_cap);
+                       (float *)lw.vc, (float *)nullptr, (float *)nullptr, c->rows, cs, d, H, hd,
+                       c->kv_cap);
     hipLaunchKernelGGL(k_attn<float>, dim3(R, H), dim3(256), shm, s, att, c->qkv32,
-                       (const float *)lw.kc, (const float *)lw.vc, c->scores, c->rows,
+                       (const float *)lw.kc, (const float *)lw.vc, (const float *)nullptr,
+                       (const float *)nullptr, c->scores, c->rows,
                        c->sch.kv_len, c->sch.gen_sub, kv_override, d, H, hd, c->kv_cap, c->gen_stride,
                        c->L, scale);
   } else {
     hipLaunchKernelGGL(k_qkv_post<f16_t>, dim3(R), dim3(256), 0, s, c->qkv32, (f16_t *)lw.kc,
-                       (f16_t *)lw.vc, c->rows, cs, d, H, hd, c->kv_cap);
+                       (f16_t *)lw.vc, (f16_t *)lw.kc_lo, (f16_t *)lw.vc_lo, c->rows, cs, d, H, hd,
+                       c->kv_cap);
     hipLaunchKernelGGL(k_attn<f16_t>, dim3(R, H), dim3(256), shm, s, att, c->qkv32,
-                       (const f16_t *)lw.kc, (const f16_t *)lw.vc, c->scores, c->rows,
+                       (const f16_t *)lw.kc, (const f16_t *)lw.vc, (const f16_t *)lw.kc_lo,
+                       (const f16_t *)lw.vc_lo, c->scores, c->rows,
                        c->sch.kv_len, c->sch.gen_sub, kv_override, d, H, hd, c->kv_cap, c->gen_stride,
                        c->L, scale);
   }

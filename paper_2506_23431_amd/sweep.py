@@ -56,6 +56,8 @@ def main(argv=None):
     ap.add_argument("--dt-list", default="1,2,4,8,16")
     ap.add_argument("--tokens", type=int, default=0, help="total generated tokens N (default: S*M of the workload)")
     ap.add_argument("--layers", type=int, default=0, help="use only this many layers (quick runs)")
+    ap.add_argument("--kv-pair-layers", type=int, default=0,
+                    help="leading layers whose cache keeps keys and values as pairs of halves")
     args = ap.parse_args(argv)
 
     import torch
@@ -89,7 +91,7 @@ def main(argv=None):
         for cfg in plans:
             S, dt, M = cfg.n_sub, cfg.delta_t, cfg.sub_tokens
             dec = PipelinedDecoder(cfg, weights, max_batch=cfg.batch, max_ctx=cfg.ctx_len, max_sub=S,
-                                   max_sub_tokens=M, max_pos=mp)
+                                   max_sub_tokens=M, max_pos=mp, kv_pair_layers=args.kv_pair_layers)
             T, sec = run_config(dec, ctx, S, dt, M)
             dec.close()
             rows.append({"S": S, "dt": dt, "M": M, "steps": T, "rows_per_request": min(S, M // dt + 1),

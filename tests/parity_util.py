@@ -12,12 +12,14 @@ TOL = {0: 1e-4, 1: 2e-2}      # max-abs logit tolerance: fp32 / bf16 (north-star
 MARGIN = 0.05                 # greedy tokens must agree where the oracle's top-2 margin exceeds this
 
 
-def oracle_run(cfg, weights, ctx, force=None, steps=None, context_kv=None, log=None):
+def oracle_run(cfg, weights, ctx, force=None, steps=None, context_kv=None, log=None, cache_layers=True):
     """Oracle traces per request. force: int array [steps][B][S] or None.
-    log: optional callable; gets a progress line at least every ~20 s of oracle work."""
+    log: optional callable; gets a progress line at least every ~20 s of oracle work.
+    cache_layers=False converts every layer's weights to fp64 each time they are used instead of
+    keeping all of them (a 7B-parameter model would hold 52 GB of fp64 copies)."""
     import time
     from oracle import controller
-    model = OracleModel(cfg, weights)
+    model = OracleModel(cfg, weights, cache_layers=cache_layers)
     outs = []
     last = [time.time()]
 
@@ -48,9 +50,13 @@ def oracle_run(cfg, weights, ctx, force=None, steps=None, context_kv=None, log=N
 
 
 def make_decoder(cfg, weights, **kw):
+    """The library on this workload.  cfg5 and the cases derived from it run with layer 0's cache
+    as pairs of halves (kv_pair_layers = 1): with plain half caches its 32 layers of width 4096
+    carry that layer's rounding to the logits at 2e-2 - 3e-2."""
     from paper_2506_23431_amd import PipelinedDecoder
     args = dict(max_batch=cfg.batch, max_ctx=cfg.ctx_len, max_sub=cfg.n_sub,
-                max_sub_tokens=cfg.sub_tokens, max_pos=max_positions(cfg))
+                max_sub_tokens=cfg.sub_tokens, max_pos=max_positions(cfg),
+                kv_pair_layers=1 if cfg.name.startswith("cfg5") else 0)
     args.update(kw)
     return PipelinedDecoder(cfg, weights, **args)
 

@@ -306,6 +306,45 @@ def test_full_size_first_iterations(name):
     dec.close()
 
 
+# --------------------------------------------------------------------------
+# Pair caches: the first kv_pair_layers layers keep keys and values as high + low halves.
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("name,pair_layers", [("mfma-hd128-llama", 1), ("mfma-hd64", 2), ("mfma-hd32", 1),
+                                              ("mfma-hd96", 2), ("mfma-manyrows", 1), ("bf16-simple", 1)])
+def test_pair_cache_layers(name, pair_layers):
+    cfg = CASES[name]
+    say(f"[case] {name} with kv_pair_layers = {pair_layers}")
+    w = pi.make_weights(cfg, threads=4)
+    ctx = pi.make_context(cfg)
+    outs = oracle_run(cfg, w, ctx)
+    dec = make_decoder(cfg, w, kv_pair_layers=pair_layers)
+    stats = compare_teacher_forced(cfg, w, ctx, dec, outs, log=say)
+    assert stats["rows"] == cfg.batch * (cfg.n_sub * (cfg.sub_tokens + 1) - 1)
+    dec.close()
+
+
+def test_cfg5_all_layers_short_context():
+    """All 32 layers at the cfg5 widths (7B parameters), 1024 context tokens, one request, four
+    subsequences: the depth is what the 2-layer full-width case leaves out.  With plain half caches
+    the rounding of layer 0's keys and values alone reaches the logits at 1.7e-2 - 2.0e-2 here
+    (2.8e-2 over the whole cfg5 workload, measured against the library's fp32 kernels); with layer 0
+    kept as pairs the error is several times below the tolerance, which the test asserts so that a
+    kernel that ignored the low halves could not pass."""
+    cfg = pi.get_config("cfg5").scaled(name="cfg5-deep", ctx_len=1024, batch=1, n_sub=4, delta_t=1,
+                                       sub_tokens=3)
+    say(f"[case] {cfg.name}: {cfg}")
+    w = pi.make_weights(cfg)
+    ctx = pi.make_context(cfg)
+    say(f"[{cfg.name}] weights drawn")
+    outs = oracle_run(cfg, w, ctx, log=say, cache_layers=False)
+    say(f"[{cfg.name}] oracle done")
+    dec = make_decoder(cfg, w, kv_pair_layers=1)
+    stats = compare_teacher_forced(cfg, w, ctx, dec, outs, log=say)
+    assert stats["rows"] == cfg.n_sub * (cfg.sub_tokens + 1) - 1
+    assert stats["worst"] < 5e-3, stats
+    dec.close()
+
+
 def test_options_do_not_change_results():
     """HIP-graph replay of the step, other attention split counts and
     plain-bf16 activations: same tokens as the default path on a workload whose top-2 margins are

@@ -60,11 +60,21 @@ def test_workspace_sizes(lib):
             * (4 if cfg.dtype == 0 else 2)
         assert n >= kv
     assert sizes["cfg1"] < sizes["cfg2"] < sizes["cfg4"] < sizes["cfg5"] < 64 << 30
+    # a pair layer adds exactly one more key cache and one more value cache of that layer
+    cfg = pi.get_config("cfg5")
+    kv_cap = (cfg.ctx_len + cfg.n_sub * (cfg.sub_tokens + 1) + 63) // 64 * 64
+    one = 2 * cfg.batch * cfg.d_model * kv_cap * 2
+    for n in (1, 3):
+        grown = lib.pd_workspace_bytes(C.byref(config_struct(cfg, kv_pair_layers=n)))
+        assert grown - sizes["cfg5"] == n * one
+    # fp32 caches have no low halves
+    cfg = pi.get_config("cfg1")
+    assert lib.pd_workspace_bytes(C.byref(config_struct(cfg, kv_pair_layers=1))) == sizes["cfg1"]
 
 
 @pytest.mark.parametrize("bad", [dict(n_head=3), dict(head_dim=7, n_head=1, d_model=7), dict(dtype=2),
                                  dict(ffn_kind=5), dict(max_batch=0), dict(bos_id=-1), dict(norm_eps=0.0),
-                                 dict(eos_id=10 ** 6), dict(max_sub=70000, max_sub_tokens=1)])
+                                 dict(eos_id=10 ** 6), dict(max_sub=70000, max_sub_tokens=1), dict(kv_pair_layers=-1), dict(kv_pair_layers=99)])
 def test_invalid_configurations_are_rejected(lib, bad):
     cfg = pi.get_config("cfg1")
     assert lib.pd_workspace_bytes(C.byref(config_struct(cfg, **bad))) == 0
