@@ -451,6 +451,50 @@ def test_sweep_runs_sequential_and_pipelined():
     assert got[(1, 1)]["speedup_vs_sequential"] == 1.0
 
 
+def test_ragged_targets_with_eos_match_the_oracle():
+    """Targets of uneven shape, drawn the way the ragged sweep draws them (Table 1 averages): every
+    subsequence ends with a forced <eos> at its drawn length, later subsequences come back empty,
+    requests finish at different times.  Oracle and library get the same forced decisions; every
+    logit row and the per-request step counts must agree."""
+    from paper_2506_23431_amd import sweep
+    dt = 2
+    lens = sweep.draw_ragged("cnndm", 3, dt, seed=3)
+    lens = [[max(dt, n // 3) for n in l] for l in lens]    # a third of the length: a short oracle run
+    assert lens == [[7], [4, 4], [7, 5, 8, 6, 5, 5]]
+    S, M, T = sweep.ragged_plan(lens, dt)
+    cfg = small("mfma-ragged", seed=33, dtype=DTYPE_BF16, d_model=128, n_head=2, head_dim=64, d_ff=256,
+                vocab=1003, ctx_len=70, batch=3, n_sub=S, delta_t=dt, sub_tokens=M, eos_id=1)
+    say(f"[case] {cfg.name}: lengths {lens}, S={S} M={M} T={T}")
+    w = pi.make_weights(cfg, threads=4)
+    ctx = pi.make_context(cfg)
+    # forced decisions: <eos> as token number len + 1 of a drawn subsequence and as the first token
+    # of every other one; a fixed non-<eos> token everywhere else, so that the lengths are exact
+    force = np.full((T, cfg.batch, S), -1, dtype=np.int64)
+    for b in range(cfg.batch):
+        for i in range(S):
+            n = lens[b][i] if i < len(lens[b]) else 0
+            t0 = i * dt                                       # 0-based iteration of the first token
+            for j in range(n + 1):
+                if t0 + j < T:
+                    force[t0 + j, b, i] = cfg.eos_id if j == n else 8 + (7 * b + 3 * i + j) % 900
+    outs = oracle_run(cfg, w, ctx, force=force)
+    for b, o in enumerate(outs):
+        assert [len(r) for r in o["result"]][:len(lens[b])] == lens[b]
+    assert len({o["steps"] for o in outs}) > 1, "requests should finish at different times"
+    dec = make_decoder(cfg, w)
+    compare_teacher_forced(cfg, w, ctx, dec, outs, force=force, log=say)
+    dec.close()
+
+
+def test_ragged_sweep_runs():
+    from paper_2506_23431_amd import sweep
+    rows = sweep.main(["--workload", "cfg2", "--layers", "2", "--ragged", "cnndm", "--dt-list", "2,4",
+                       "--targets", "3"])
+    assert [r["mode"] for r in rows] == ["sequential", "pipelined", "pipelined"]
+    assert all(r["lengths_as_drawn"] for r in rows)
+    assert all(r["tokens_per_s"] > 0 for r in rows)
+
+
 def test_plain_read_bandwidth_measurement():
     """pd_measure_read_bandwidth: sane figure for a 64 MB chunk out of a 1 GiB buffer, errors for bad arguments."""
     import torch
