@@ -230,7 +230,7 @@ int mfma_norm(pd_ctx *c, const float *gain, const float *bias, int R, hipStream_
 // epilogue of one 16-column tile: lane holds y[r][n0 + j], r = i*16 + m, n0 = nt*16 + 4g, j = 0..3
 template <int RT, int EPI>
 __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int nt, const floatx4 (&acc)[RT],
-                                              const int4 *kvi, int lane) {
+                                              const int4 *kvi, int lane, int r0 = 0) {
   int m = lane & 15, g = lane >> 4;
   int n0 = nt * 16 + 4 * g;
   // rows at and beyond a.R are never stored: nobody reads them, and with packed activations their
@@ -240,14 +240,14 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int nt, const f
     float *yp = a.x + (size_t)blockIdx.y * a.part_stride;
 #pragma unroll
     for (int i = 0; i < RT; ++i) {
-      int r = i * 16 + m;
+      int r = r0 + i * 16 + m;
       if (r >= a.R) continue;
       *(float4 *)(yp + (size_t)r * a.ld + n0) = make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
     }
   } else if (EPI == EPI_GELU) {
 #pragma unroll
     for (int i = 0; i < RT; ++i) {
-      int r = i * 16 + m;
+      int r = r0 + i * 16 + m;
       float y[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
@@ -260,7 +260,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int nt, const f
     // groups 0,1: gate of features nt*8 + 4g + j; groups 2,3: up of nt*8 + 4(g-2) + j
 #pragma unroll
     for (int i = 0; i < RT; ++i) {
-      int r = i * 16 + m;
+      int r = r0 + i * 16 + m;
       float y[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
@@ -275,7 +275,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int nt, const f
     int half = a.hd >> 1;
 #pragma unroll
     for (int i = 0; i < RT; ++i) {
-      int r = i * 16 + m;
+      int r = r0 + i * 16 + m;
       bool valid = r < a.R && (kvi[i].x & ROW_VALID);
       float y[4];
       int dim0;                                  // head-dim index of y[0]; y[j] is dim0 + j
@@ -319,7 +319,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int nt, const f
   } else if (EPI == EPI_LM) {
 #pragma unroll
     for (int i = 0; i < RT; ++i) {
-      int r = i * 16 + m;
+      int r = r0 + i * 16 + m;
       float best = -INFINITY;
       int bi = 0x7fffffff;
 #pragma unroll
@@ -542,6 +542,132 @@ static int launch_gemm_wide(const GemmArgs &a, hipStream_t s) {
   }
 }
 
+
+// ---------------------------------------------------------------------------
+// More than 128 rows (the context pass in chunks of up to 1024 rows): grid (column groups, K slices,
+// groups of 128 rows).  A block is 4 waves that own NT column tiles each and share the 8 row tiles
+// of their row group: per k-tile every wave requests a quarter of the activation fragments (high and
+// low parts) and its own weight fragments, D k-tiles ahead, the activation fragments pass through
+// LDS (two buffers of 16 KiB), and every wave multiplies all of them with its weights.  A k-tile
+// then costs the compute unit 16 + 4 NT requests for 64 NT multiplies, against 16 + NT for 16 NT
+// when the waves cut K instead.
+// Measured on the QKV shape of cfg4 with 1024 rows: requests alone 64-90 us (6.5 TB/s out of L2, hit
+// rate 77-91 %), LDS traffic and multiplies alone 73-96 us, together 120-160 us: the phases add up
+// rather than overlap, whatever the prefetch depth (1, 2, 4) or the number of blocks per compute
+// unit (1, 2, 4).  A single wave per SIMD issues one 16x16x32 multiply per 29 clocks, two or more
+// one per 19.
+// ---------------------------------------------------------------------------
+template <int NT, int D, int OCC, int EPI, bool SPLIT>
+__global__ __launch_bounds__(256, OCC) void k_gemm_p(GemmArgs a) {
+  constexpr int RT = 8, NA = SPLIT ? 2 * RT : RT, NAW = NA / 4;    // fragments per k-tile: all / staged by one wave
+  static_assert(D % 2 == 0 || D == 1, "stages alternate between the two LDS buffers");
+  __shared__ uint4 sm_x[2][NA][64];
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int m = lane & 15;
+  const int KT = a.K >> 5;
+  const int per_slice = (KT + (int)gridDim.y - 1) / (int)gridDim.y;
+  const int kt0 = min((int)blockIdx.y * per_slice, KT), kt1 = min(kt0 + per_slice, KT);
+  const int rt0 = blockIdx.z * RT, r0 = rt0 * 16;
+  int4 kvi[(EPI == EPI_QKV || EPI == EPI_QKV_ROPE) ? RT : 1];
+  if (EPI == EPI_QKV || EPI == EPI_QKV_ROPE) {
+#pragma unroll
+    for (int i = 0; i < RT; ++i) kvi[i] = a.rt.kvinfo[r0 + i * 16 + m];
+  }
+  const int nt0 = (blockIdx.x * 4 + w) * NT;
+  int tile[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) tile[t] = min(nt0 + t, a.n_tiles - 1);   // tiles past the end repeat the last one
+  floatx4 acc[NT][RT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int i = 0; i < RT; ++i) acc[t][i] = floatx4{0.f, 0.f, 0.f, 0.f};
+  const uint4 *wp = (const uint4 *)a.W + lane;
+  // this wave's share of the activation fragments: fragment f = w * NAW + j is row tile f % RT of
+  // the high (f < RT) or low parts
+  const uint4 *xsrc[NAW];
+#pragma unroll
+  for (int j = 0; j < NAW; ++j) {
+    int f = w * NAW + j;
+    const bf16_t *base = (SPLIT && f >= RT) ? a.xn_lo : a.xn;
+    xsrc[j] = (const uint4 *)base + (size_t)(rt0 + f % RT) * KT * 64 + lane;
+  }
+  // D k-tiles are in flight per wave, each in registers of its own (slot = k-tile index mod D)
+  uint4 xr[D][NAW];
+  Frag wr[D][NT];
+  const int len = kt1 - kt0;
+  auto k_of = [&](int j) { return kt0 + min(j, len - 1); };   // steps past the end repeat the last k-tile
+#pragma unroll
+  for (int d = 0; d < D; ++d) {
+    int k = len > 0 ? k_of(d) : 0;
+#pragma unroll
+    for (int j = 0; j < NAW; ++j) xr[d][j] = xsrc[j][(size_t)k * 64];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) wr[d][t].u = wp[((size_t)tile[t] * KT + k) * 64];
+  }
+  for (int j0 = 0; j0 < len; j0 += D) {
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+      if (j0 + d < len) {           // the same for every wave of the block
+        const int buf = D == 1 ? (j0 & 1) : (d & 1);
+        Frag wc[NT];
+#pragma unroll
+        for (int j = 0; j < NAW; ++j) sm_x[buf][w * NAW + j][lane] = xr[d][j];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) wc[t] = wr[d][t];
+        {                           // refill the slot with the k-tile D further on
+          int k = k_of(j0 + d + D);
+#pragma unroll
+          for (int j = 0; j < NAW; ++j) xr[d][j] = xsrc[j][(size_t)k * 64];
+#pragma unroll
+          for (int t = 0; t < NT; ++t) wr[d][t].u = wp[((size_t)tile[t] * KT + k) * 64];
+        }
+        // one barrier per k-tile is enough with two buffers: a wave can only write k-tile i + 2 into
+        // this buffer after the barrier of k-tile i + 1, which every wave reaches after its reads of i
+        __syncthreads();
+        // all LDS reads of the k-tile are issued before the first multiply (left to itself the
+        // compiler reads two fragments at a time and waits for each pair)
+        Frag xf[NA];
+#pragma unroll
+        for (int f = 0; f < NA; ++f) xf[f].u = sm_x[buf][f][lane];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < RT; ++i) {
+#pragma unroll
+          for (int t = 0; t < NT; ++t) {
+            acc[t][i] = mfma16(wc[t], xf[i], acc[t][i]);
+            if (SPLIT) acc[t][i] = mfma16(wc[t], xf[RT + i], acc[t][i]);
+          }
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+    if (nt0 + t < a.n_tiles) gemm_epilogue<RT, EPI>(a, nt0 + t, acc[t], kvi, lane, r0);
+}
+
+template <int NT, int OCC, int EPI, bool SPLIT>
+static int launch_gemm_rows_nt(GemmArgs a, int rows, hipStream_t s) {
+  int KT = a.K / 32, gx = (a.n_tiles + 4 * NT - 1) / (4 * NT), gz = (rows + 127) / 128, ks = 1;
+  if (EPI == EPI_RESID)     // K slices (summed by the next norm kernel) while compute units would stay empty
+    while (ks < a.max_parts && (long)gx * gz * ks < 256 && KT / (2 * ks) >= 8) ks *= 2;
+  hipLaunchKernelGGL((k_gemm_p<NT, 2, OCC, EPI, SPLIT>), dim3(gx, ks, gz), dim3(256), 0, s, a);
+  PD_CHECK_HIP(hipGetLastError());
+  if (EPI == EPI_RESID && a.parts_out) *a.parts_out = ks;
+  return PD_OK;
+}
+
+// Four column tiles per wave (one block per compute unit) when that still gives about 190 blocks
+// (measured: QKV 121 against 158 us, FFN1 122 against 156 us with 1024 rows of cfg4), else two
+// (512 rows: 90 against 120 us).
+template <int EPI, bool SPLIT>
+static int launch_gemm_rows(const GemmArgs &a, int rows, hipStream_t s) {
+  long blocks4 = (long)((a.n_tiles + 15) / 16) * ((rows + 127) / 128) * (EPI == EPI_RESID ? a.max_parts : 1);
+  if (blocks4 >= 190) return launch_gemm_rows_nt<4, 1, EPI, SPLIT>(a, rows, s);
+  return launch_gemm_rows_nt<2, 2, EPI, SPLIT>(a, rows, s);
+}
+
 template <int EPI, bool SPLIT>
 static int launch_gemm_split(const GemmArgs &a, int rows, hipStream_t s) {
   switch (mfma_gemm_row_tiles(rows)) {
@@ -555,7 +681,10 @@ static int launch_gemm_split(const GemmArgs &a, int rows, hipStream_t s) {
 
 template <int EPI>
 static int launch_gemm(const GemmArgs &a, int rows, hipStream_t s) {
-  PD_REQUIRE(rows <= 128, PD_EINVAL, "more than 128 rows per launch (%d)", rows);
+  if (rows > 128) {
+    PD_REQUIRE(!a.packed, PD_EINVAL, "packed activations hold at most 8 rows (%d)", rows);
+    return a.xn_lo ? launch_gemm_rows<EPI, true>(a, rows, s) : launch_gemm_rows<EPI, false>(a, rows, s);
+  }
   if (a.packed) {
     PD_REQUIRE(rows <= 8 && a.R <= 8, PD_EINVAL, "packed activations hold at most 8 rows (%d)", rows);
     return launch_gemm_small<1, EPI, false, true>(a, s);

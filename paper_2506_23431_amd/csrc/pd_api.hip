@@ -80,13 +80,16 @@ static size_t carve(const pd_config *g, char *base, pd_ctx *c) {
   x->gen_cap = S * (M + 1);
   x->gen_stride = (x->gen_cap + 8 + 7) / 8 * 8;
   x->kv_cap = (g->max_ctx + x->gen_cap + 63) / 64 * 64;
-  x->prefill_chunk = 128;
+  // rows of the context pass per launch: the matrix-core path has a projection kernel for many
+  // rows (row groups of 128 share a launch), the fp32 path keeps one score row per (row, head)
+  x->prefill_chunk = x->impl == 1 ? std::min(1024, (g->max_ctx + 127) / 128 * 128) : 128;
   int a_max = std::min(S, M + 1);
   x->R_cap = std::max(B * a_max, x->prefill_chunk);
   // row buffers are read in tiles of 16 rows, 1/2/4/8 tiles per launch
   int tiles = (x->R_cap + 15) / 16, t2 = 1;
   while (t2 < tiles && t2 < 8) t2 *= 2;
   x->R_pad = std::max(tiles, t2) * 16;
+  if (x->R_pad > 128) x->R_pad = (x->R_pad + 127) / 128 * 128;     // whole row groups of 128
   x->vocab_pad = (V + 63) / 64 * 64;
   size_t es = g->dtype == 0 ? 4 : 2;
   x->kv_layer_bytes = (size_t)B * H * x->kv_cap * hd * es;
@@ -106,7 +109,8 @@ static size_t carve(const pd_config *g, char *base, pd_ctx *c) {
   x->att = cv.take<float>(Rp * d);
   x->hb = cv.take<float>(Rp * ff);
   x->qkv32 = cv.take<float>(Rp * 3 * d);
-  x->logits = cv.take<float>(Rp * (size_t)x->vocab_pad);
+  // logits exist for decode rows only (the context pass never runs the head)
+  x->logits = cv.take<float>((size_t)((B * a_max + 15) / 16 * 16) * x->vocab_pad);
   x->scores = x->impl == 0 ? cv.take<float>((size_t)x->R_cap * H * x->kv_cap) : nullptr;
   x->att_part = cv.take<float>((size_t)4096 * 16 * (hd + 2));
   x->ypart = cv.take<float>((size_t)4 * Rp * d);
