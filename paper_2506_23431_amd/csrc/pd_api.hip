@@ -311,8 +311,6 @@ extern "C" int pd_prefill_context(pd_ctx *c, const int32_t *ctx_tokens, int B, i
   c->A = std::min(n_sub, max_sub_tokens / delta_t + 1);
   c->R = B * c->A;
   PD_REQUIRE(c->A <= 1024, PD_EINVAL, "%d rows per request exceed the 1024 one step supports", c->A);
-  PD_REQUIRE(c->impl == 0 || c->R <= 128, PD_EINVAL,
-             "B * rows-per-request = %d exceeds the 128 rows one bf16 step supports", c->R);
   PD_CHECK_HIP(hipMemcpyAsync(c->ctx_tok, ctx_tokens, sizeof(int32_t) * (size_t)B * L,
                               hipMemcpyHostToDevice, s));
   PD_CHECK_HIP(hipStreamSynchronize(s));

@@ -146,8 +146,6 @@ def main_ragged(args):
     plans = {(m, dt): [plan(m, dt, lens) for lens in targets] for m, dt in runs}
     S_cap = max(p[1] for ps in plans.values() for p in ps)
     M_cap = max(p[2] for ps in plans.values() for p in ps)
-    if base.dtype == 1 and base.batch * S_cap > 128:
-        raise SystemExit("more rows per step than the matrix-core path supports; use a smaller batch")
     mp = base.ctx_len + max((p[1] - 1) * (dt + 1) + p[2] + 1 for (m, dt), ps in plans.items() for p in ps)
     weights = pi.make_weights(base.scaled(n_sub=1, delta_t=1, sub_tokens=mp - base.ctx_len - 1))
     ctx = pi.make_context(base)
@@ -223,9 +221,6 @@ def main(argv=None):
             continue
         M = N // S
         for dt in ([1] if S == 1 else dt_list):
-            A = min(S, M // dt + 1)
-            if base.dtype == 1 and base.batch * A > 128:
-                continue                # more rows than one matrix-core step supports
             plans.append(base.scaled(n_sub=S, delta_t=dt, sub_tokens=M))
     # one set of weights whose position table covers the longest run of the sweep
     mp = max(max_positions(c) for c in plans)

@@ -202,13 +202,16 @@ def test_random_small_workloads(k):
     dec.close()
 
 
-def test_more_than_128_rows_is_an_error_on_the_matrix_core_path():
-    from paper_2506_23431_amd import PdError
+def test_more_than_128_rows_per_step():
+    """9 requests x 16 rows = 144 rows per step: beyond the 128 rows of the small projection kernels,
+    every projection (the vocabulary argmax included) runs in the many-row kernel of the context pass."""
     cfg = small("mfma-r144", seed=50, n_sub=16, delta_t=1, sub_tokens=15, batch=9, ctx_len=40, n_layer=1, **MF)
     w = pi.make_weights(cfg, threads=4)
+    ctx = pi.make_context(cfg)
+    outs = oracle_run(cfg, w, ctx, log=say)
     dec = make_decoder(cfg, w)
-    with pytest.raises(PdError, match="128 rows"):
-        dec.prefill_context(pi.make_context(cfg), cfg.n_sub, cfg.delta_t, cfg.sub_tokens, cfg.time_steps)
+    stats = compare_teacher_forced(cfg, w, ctx, dec, outs, log=say)
+    assert stats["rows"] == cfg.batch * (cfg.n_sub * (cfg.sub_tokens + 1) - 1)
     dec.close()
 
 
