@@ -123,7 +123,7 @@ struct pd_ctx {
   float *x;                 // [R_cap][d] residual stream
   void *xn, *q, *att, *hb;  // activations (type depends on impl)
   float *qkv32;             // simple path: [R_cap][3d]
-  float *logits;            // [R_cap][vocab] internal logits (simple path / parity output)
+  float *logits;            // [decode rows][vocab] internal logits (simple path / parity output)
   float *scores;            // simple path attention scratch
   float *att_part;          // split-K partials of the attention kernel
   float *ypart;             // [4][R_pad][d] split-K partial sums of the O / FFN2 projections

@@ -2,6 +2,7 @@
 Small and medium workloads that the oracle finishes in seconds: several tiles, ragged tails,
 both code paths (fp32-activation kernels and bf16 MFMA kernels), all block variants."""
 
+import os
 import sys
 
 import numpy as np
@@ -14,9 +15,21 @@ from parity_util import oracle_run, make_decoder, compare_teacher_forced
 pytestmark = pytest.mark.gpu
 
 
+_PROGRESS = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out",
+                         "gpu_parity_progress.log")
+
+
 def say(msg):
+    """Progress line: to stdout (captured by pytest unless -s is given) and appended to a log file, so
+    that a long oracle run shows signs of life to whoever watches the run from outside."""
     print(msg, flush=True)
     sys.stdout.flush()
+    try:
+        os.makedirs(os.path.dirname(_PROGRESS), exist_ok=True)
+        with open(_PROGRESS, "a") as f:
+            f.write(msg + "\n")
+    except OSError:
+        pass
 
 
 def small(name, **kw):
