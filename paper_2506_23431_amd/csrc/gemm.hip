@@ -557,7 +557,7 @@ static int launch_gemm_wide(const GemmArgs &a, hipStream_t s) {
 // unit (1, 2, 4).  A single wave per SIMD issues one 16x16x32 multiply per 29 clocks, two or more
 // one per 19.
 // ---------------------------------------------------------------------------
-template <int NT, int D, int OCC, int EPI, bool SPLIT>
+template <int NT, int D, int OCC, int EPI, bool SPLIT, int TAG = 0>
 __global__ __launch_bounds__(256, OCC) void k_gemm_p(GemmArgs a) {
   constexpr int RT = 8, NA = SPLIT ? 2 * RT : RT, NAW = NA / 4;    // fragments per k-tile: all / staged by one wave
   static_assert(D % 2 == 0 || D == 1, "stages alternate between the two LDS buffers");
@@ -631,12 +631,15 @@ __global__ __launch_bounds__(256, OCC) void k_gemm_p(GemmArgs a) {
 #pragma unroll
         for (int f = 0; f < NA; ++f) xf[f].u = sm_x[buf][f][lane];
         __builtin_amdgcn_sched_barrier(0);
+        // (two products into the same accumulator are kept NT multiplies apart: back to back the
+        // second would wait for the first to leave the pipeline)
 #pragma unroll
         for (int i = 0; i < RT; ++i) {
 #pragma unroll
-          for (int t = 0; t < NT; ++t) {
-            acc[t][i] = mfma16(wc[t], xf[i], acc[t][i]);
-            if (SPLIT) acc[t][i] = mfma16(wc[t], xf[RT + i], acc[t][i]);
+          for (int t = 0; t < NT; ++t) acc[t][i] = mfma16(wc[t], xf[i], acc[t][i]);
+          if (SPLIT) {
+#pragma unroll
+            for (int t = 0; t < NT; ++t) acc[t][i] = mfma16(wc[t], xf[RT + i], acc[t][i]);
           }
         }
       }
@@ -658,14 +661,28 @@ static int launch_gemm_rows_nt(GemmArgs a, int rows, hipStream_t s) {
   return PD_OK;
 }
 
-// Four column tiles per wave (one block per compute unit) when that still gives about 190 blocks
-// (measured: QKV 121 against 158 us, FFN1 122 against 156 us with 1024 rows of cfg4), else two
-// (512 rows: 90 against 120 us).
+// Column tiles per wave: what finishes first by the measured time of a block per k-tile (us; QKV and
+// FFN1 shapes of cfg4 and cfg5 with 512 and 1024 rows): 1.9 with four tiles and 1.7 with three, one
+// block per compute unit; with two tiles two blocks share a compute unit and take 2.45 each (1.4
+// while the launch has fewer blocks than compute units).  A launch runs ceil(blocks / resident
+// blocks) rounds of that.
 template <int EPI, bool SPLIT>
 static int launch_gemm_rows(const GemmArgs &a, int rows, hipStream_t s) {
-  long blocks4 = (long)((a.n_tiles + 15) / 16) * ((rows + 127) / 128) * (EPI == EPI_RESID ? a.max_parts : 1);
-  if (blocks4 >= 190) return launch_gemm_rows_nt<4, 1, EPI, SPLIT>(a, rows, s);
-  return launch_gemm_rows_nt<2, 2, EPI, SPLIT>(a, rows, s);
+  auto blocks = [&](int nt) {
+    long b = (long)((a.n_tiles + 4 * nt - 1) / (4 * nt)) * ((rows + 127) / 128);
+    if (EPI == EPI_RESID) {     // the K slices launch_gemm_rows_nt will choose
+      int KT = a.K / 32, ks = 1;
+      while (ks < a.max_parts && b * ks < 256 && KT / (2 * ks) >= 8) ks *= 2;
+      b *= ks;
+    }
+    return b;
+  };
+  long b4 = blocks(4), b3 = blocks(3), b2 = blocks(2);
+  double c4 = (double)((b4 + 255) / 256) * 1.9, c3 = (double)((b3 + 255) / 256) * 1.7;
+  double c2 = b2 <= 256 ? 1.4 : (double)((b2 + 511) / 512) * 2.45;
+  if (c2 < c3 && c2 < c4) return launch_gemm_rows_nt<2, 2, EPI, SPLIT>(a, rows, s);
+  if (c3 < c4) return launch_gemm_rows_nt<3, 1, EPI, SPLIT>(a, rows, s);
+  return launch_gemm_rows_nt<4, 1, EPI, SPLIT>(a, rows, s);
 }
 
 template <int EPI, bool SPLIT>

@@ -80,11 +80,19 @@ static size_t carve(const pd_config *g, char *base, pd_ctx *c) {
   x->gen_cap = S * (M + 1);
   x->gen_stride = (x->gen_cap + 8 + 7) / 8 * 8;
   x->kv_cap = (g->max_ctx + x->gen_cap + 63) / 64 * 64;
-  // rows of the context pass per launch: the matrix-core path has a projection kernel for many
-  // rows (row groups of 128 share a launch), the fp32 path keeps one score row per (row, head)
-  x->prefill_chunk = x->impl == 1 ? std::min(1024, (g->max_ctx + 127) / 128 * 128) : 128;
+  // Rows of the context pass per launch.  The matrix-core path has a projection kernel for many
+  // rows (row groups of 128 share a launch; about 0.26 PFLOP/s whatever the shape) beside the
+  // kernels for up to 128 rows, which stream a layer's weights once per 128 rows (measured: 9 us +
+  // bytes / 2.9 TB/s per projection).  With W bytes of weights per layer the many-row kernel wins
+  // while 128 W / 0.26e15 < 36e-6 + W / 2.9e12, i.e. W < 245 MB (cfg3 25 MB: 2.5 x faster, cfg4
+  // 101 MB: 1.6 x, cfg5 405 MB: 0.9 x).  The fp32 path keeps one score row per (row, head).
+  {
+    double w_layer = 2.0 * ((double)d * d * 4 + (double)d * ff * (g->ffn_kind == 1 ? 3 : 2));
+    x->prefill_chunk_cap = x->impl == 1 ? std::min(1024, (g->max_ctx + 127) / 128 * 128) : 128;
+    x->prefill_chunk = w_layer < 245e6 ? x->prefill_chunk_cap : 128;
+  }
   int a_max = std::min(S, M + 1);
-  x->R_cap = std::max(B * a_max, x->prefill_chunk);
+  x->R_cap = std::max(B * a_max, x->prefill_chunk_cap);
   // row buffers are read in tiles of 16 rows, 1/2/4/8 tiles per launch
   int tiles = (x->R_cap + 15) / 16, t2 = 1;
   while (t2 < tiles && t2 < 8) t2 *= 2;
@@ -197,7 +205,7 @@ extern "C" int pd_create(const pd_config *cfg, const pd_weights *w, void *dev_wo
     lp.n2b = cfg->norm_kind == 0 ? w->norm2_b[l] : nullptr;
   }
   c->prefilled = false; c->host_steps = 0;
-  c->embed_pending = false; c->packed = false; c->opt_splits = 0; c->opt_graph = 0; c->opt_profile = 0; c->opt_split = 1;
+  c->embed_pending = false; c->packed = false; c->opt_splits = 0; c->opt_graph = 0; c->opt_profile = 0; c->opt_split = 1; c->opt_chunk = 0;
   c->graph_exec = nullptr; c->graph_ready = false; c->ev_used = 0; c->h_pinned = nullptr;
   c->B = c->L = c->S = c->dt = c->M = c->time_max = c->A = c->R = 0;
   hipStream_t s = (hipStream_t)hip_stream;
@@ -244,6 +252,10 @@ extern "C" int pd_set_option(pd_ctx *c, int key, int value) {
       c->opt_graph = value ? 1 : 0; drop_graph(c); return PD_OK;
     case PD_OPT_SPLIT_ACT:
       c->opt_split = value ? 1 : 0; drop_graph(c); return PD_OK;
+    case PD_OPT_PREFILL_CHUNK:
+      PD_REQUIRE(value >= 0, PD_EINVAL, "prefill chunk must be >= 0");
+      c->opt_chunk = value == 0 ? 0 : std::min((value + 15) / 16 * 16, c->prefill_chunk_cap);
+      return PD_OK;
     case PD_OPT_PROFILE:
       c->opt_profile = value == 2 ? 2 : (value ? 1 : 0); drop_graph(c); c->ev_used = 0; return PD_OK;
     default:
@@ -317,8 +329,9 @@ extern "C" int pd_prefill_context(pd_ctx *c, const int32_t *ctx_tokens, int B, i
   int rc;
   if ((rc = launch_reset_state(c, s))) return rc;
   for (int b = 0; b < B; ++b) {
-    for (int p0 = 0; p0 < L; p0 += c->prefill_chunk) {
-      int n = std::min(c->prefill_chunk, L - p0);
+    const int chunk = c->opt_chunk > 0 ? c->opt_chunk : c->prefill_chunk;
+    for (int p0 = 0; p0 < L; p0 += chunk) {
+      int n = std::min(chunk, L - p0);
       if ((rc = launch_prefill_rows(c, b, p0, n, s))) return rc;
       if ((rc = run_layers(c, n, n, 1, b, p0 + n, s))) return rc;
     }

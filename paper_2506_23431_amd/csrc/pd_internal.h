@@ -116,7 +116,7 @@ struct pd_ctx {
   std::vector<LayerPtrs> layers;
   int impl;                 // 0: fp32-activation kernels; 1: bf16 MFMA kernels
   // capacities
-  int gen_cap, gen_stride, kv_cap, R_cap, R_pad, vocab_pad, prefill_chunk;
+  int gen_cap, gen_stride, kv_cap, R_cap, R_pad, vocab_pad, prefill_chunk, prefill_chunk_cap;
   size_t kv_layer_bytes;    // bytes of one K (or V) cache of one layer
   // workspace carve-up
   char *ws; size_t ws_bytes;
@@ -143,7 +143,7 @@ struct pd_ctx {
   bool prefilled;
   int host_steps;           // decode steps enqueued since prefill/reset
   // options
-  int opt_splits, opt_graph, opt_profile, opt_split;
+  int opt_splits, opt_graph, opt_profile, opt_split, opt_chunk;
   hipGraphExec_t graph_exec; bool graph_ready;
   std::vector<hipEvent_t> ev_pool; size_t ev_used;
   int32_t *h_pinned;        // small pinned host staging buffer

@@ -294,6 +294,10 @@ def test_full_width_parity(name):
     outs = oracle_run(cfg, w, ctx, steps=steps, log=say)
     say(f"[{name}] oracle done")
     dec = make_decoder(cfg, w)
+    # the context pass in 1024-row chunks whatever the default for these widths is, so that the
+    # many-row projection kernel is covered at every width
+    from paper_2506_23431_amd import binding
+    dec.set_option(binding.PD_OPT_PREFILL_CHUNK, 1024)
     stats = compare_teacher_forced(cfg, w, ctx, dec, outs, steps=steps, log=say)
     assert stats["rows"] > 0
     dec.close()
@@ -423,7 +427,8 @@ def test_whole_workload_bf16_kernels_against_fp32_kernels(name):
 
 
 def test_options_do_not_change_results():
-    """HIP-graph replay of the step, other attention split counts and
+    """HIP-graph replay of the step, other attention split counts, other chunk sizes of the context
+    pass (the default here is all 150 rows at once, in the many-row projection kernel) and
     plain-bf16 activations: same tokens as the default path on a workload whose top-2 margins are
     comfortably above the bf16 noise; the graph is replayed for every step of three runs with eager
     work and synchronisations in between, and every replayed run is compared."""
@@ -438,7 +443,9 @@ def test_options_do_not_change_results():
         args = (ctx, cfg.n_sub, cfg.delta_t, cfg.sub_tokens, cfg.time_steps)
         base = dec.generate(*args)
         for key, val in ((binding.PD_OPT_USE_GRAPH, 1), (binding.PD_OPT_ATTN_SPLITS, 3),
-                         (binding.PD_OPT_ATTN_SPLITS, 1), (binding.PD_OPT_ATTN_SPLITS, 7)):
+                         (binding.PD_OPT_ATTN_SPLITS, 1), (binding.PD_OPT_ATTN_SPLITS, 7),
+                         (binding.PD_OPT_PREFILL_CHUNK, 16), (binding.PD_OPT_PREFILL_CHUNK, 40),
+                         (binding.PD_OPT_PREFILL_CHUNK, 128), (binding.PD_OPT_PREFILL_CHUNK, 144)):
             dec.set_option(key, val)
             for rep in range(3 if key == binding.PD_OPT_USE_GRAPH else 1):
                 got = dec.generate(*args)
