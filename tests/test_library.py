@@ -5,6 +5,7 @@ import ctypes as C
 import os
 import re
 
+import numpy as np
 import pytest
 
 import pd_inputs as pi
@@ -104,3 +105,32 @@ def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "missing.so"))
     with pytest.raises(binding.PdError, match="no fallback"):
         binding.load()
+
+
+def test_option_keys_match_the_header():
+    """The binding's option constants are the header's."""
+    from paper_2506_23431_amd import binding
+    text = open(os.path.join(ROOT, "include", "pd.h")).read()
+    keys = dict(re.findall(r"#define\s+(PD_OPT_[A-Z_]+)\s+(\d+)", text))
+    assert len(keys) >= 5
+    for name, value in keys.items():
+        assert getattr(binding, name) == int(value), name
+    assert len(set(keys.values())) == len(keys), "option keys must be distinct"
+
+
+def test_ragged_targets_are_reproducible_and_hold_their_plan():
+    """Host logic of the ragged sweep: seeded draws, every length at least delta_t, and a plan
+    (S, M, T) that holds the longest target plus one exploratory subsequence."""
+    from paper_2506_23431_amd import sweep
+    for profile, (mean_n, mean_words) in sweep.RAGGED.items():
+        a = sweep.draw_ragged(profile, 64, 3, seed=11)
+        assert a == sweep.draw_ragged(profile, 64, 3, seed=11)
+        assert a != sweep.draw_ragged(profile, 64, 3, seed=12)
+        assert all(len(l) >= 1 and min(l) >= 3 for l in a)
+        n = np.mean([len(l) for l in a])
+        t = np.mean([x for l in a for x in l])
+        assert abs(n - mean_n) < 1.0 and abs(t - mean_words * sweep.TOKENS_PER_WORD) < 3.0
+        S, M, T = sweep.ragged_plan(a, 3)
+        assert S == max(len(l) for l in a) + 1 and M == max(max(l) for l in a) + 1
+        assert T == (S - 1) * 3 + M
+    assert all(len(l) <= 4 for l in sweep.draw_ragged("pubmed", 16, 2, seed=1, s_max=4))
