@@ -544,22 +544,23 @@ static int launch_gemm_wide(const GemmArgs &a, hipStream_t s) {
 
 
 // ---------------------------------------------------------------------------
-// More than 128 rows (the context pass in chunks of up to 1024 rows): grid (column groups, K slices,
-// groups of 128 rows).  A block is 4 waves that own NT column tiles each and share the 8 row tiles
-// of their row group: per k-tile every wave requests a quarter of the activation fragments (high and
-// low parts) and its own weight fragments, D k-tiles ahead, the activation fragments pass through
-// LDS (two buffers of 16 KiB), and every wave multiplies all of them with its weights.  A k-tile
-// then costs the compute unit 16 + 4 NT requests for 64 NT multiplies, against 16 + NT for 16 NT
-// when the waves cut K instead.
-// Measured on the QKV shape of cfg4 with 1024 rows: requests alone 64-90 us (6.5 TB/s out of L2, hit
-// rate 77-91 %), LDS traffic and multiplies alone 73-96 us, together 120-160 us: the phases add up
-// rather than overlap, whatever the prefetch depth (1, 2, 4) or the number of blocks per compute
-// unit (1, 2, 4).  A single wave per SIMD issues one 16x16x32 multiply per 29 clocks, two or more
-// one per 19.
+// More than 128 rows (the context pass in chunks of up to 2048 rows): grid (column groups, K slices,
+// groups of 128 rows).  A block is NW = 8 waves (two per SIMD: a single wave issues a 16x16x32
+// multiply every 29 clocks, two or more every 19) that own NT column tiles each and share the 8 row
+// tiles of their row group: per k-tile every wave requests its share of the activation fragments
+// (high and low parts) and its own weight fragments, D k-tiles ahead, the activation fragments pass
+// through LDS (two buffers of 16 KiB), and every wave multiplies all of them with its weights.  A
+// k-tile then costs the compute unit 16 + 8 NT requests for 128 NT multiplies, against 16 + NT for
+// 16 NT when the waves cut K instead.
+// Measured with 1024 rows (useful rate; twice that is executed with the low parts): QKV of cfg5
+// 241 us = 0.43 PFLOP/s with NT = 3 (256 blocks), QKV of cfg4 101 us = 0.25 PFLOP/s with NT = 2 (192
+// blocks: the smaller the matrix, the fewer blocks of this size a chunk of rows makes).  With 4
+// waves per block and twice the column tiles per wave the same launches take 450 and 128 us.
 // ---------------------------------------------------------------------------
-template <int NT, int D, int OCC, int EPI, bool SPLIT, int TAG = 0>
-__global__ __launch_bounds__(256, OCC) void k_gemm_p(GemmArgs a) {
-  constexpr int RT = 8, NA = SPLIT ? 2 * RT : RT, NAW = NA / 4;    // fragments per k-tile: all / staged by one wave
+template <int NT, int D, int OCC, int EPI, bool SPLIT, int NW = 4, int TAG = 0>
+__global__ __launch_bounds__(64 * NW, OCC) void k_gemm_p(GemmArgs a) {
+  static_assert(NW == 4 || NW == 8, "4 or 8 waves");
+  constexpr int RT = 8, NA = SPLIT ? 2 * RT : RT, NAW = NA / NW;   // fragments per k-tile: all / staged by one wave
   static_assert(D % 2 == 0 || D == 1, "stages alternate between the two LDS buffers");
   __shared__ uint4 sm_x[2][NA][64];
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -573,7 +574,7 @@ __global__ __launch_bounds__(256, OCC) void k_gemm_p(GemmArgs a) {
 #pragma unroll
     for (int i = 0; i < RT; ++i) kvi[i] = a.rt.kvinfo[r0 + i * 16 + m];
   }
-  const int nt0 = (blockIdx.x * 4 + w) * NT;
+  const int nt0 = (blockIdx.x * NW + w) * NT;
   int tile[NT];
 #pragma unroll
   for (int t = 0; t < NT; ++t) tile[t] = min(nt0 + t, a.n_tiles - 1);   // tiles past the end repeat the last one
@@ -650,39 +651,36 @@ __global__ __launch_bounds__(256, OCC) void k_gemm_p(GemmArgs a) {
     if (nt0 + t < a.n_tiles) gemm_epilogue<RT, EPI>(a, nt0 + t, acc[t], kvi, lane, r0);
 }
 
-template <int NT, int OCC, int EPI, bool SPLIT>
+template <int NT, int EPI, bool SPLIT>
 static int launch_gemm_rows_nt(GemmArgs a, int rows, hipStream_t s) {
-  int KT = a.K / 32, gx = (a.n_tiles + 4 * NT - 1) / (4 * NT), gz = (rows + 127) / 128, ks = 1;
+  constexpr int NW = 8;
+  int KT = a.K / 32, gx = (a.n_tiles + NW * NT - 1) / (NW * NT), gz = (rows + 127) / 128, ks = 1;
   if (EPI == EPI_RESID)     // K slices (summed by the next norm kernel) while compute units would stay empty
     while (ks < a.max_parts && (long)gx * gz * ks < 256 && KT / (2 * ks) >= 8) ks *= 2;
-  hipLaunchKernelGGL((k_gemm_p<NT, 2, OCC, EPI, SPLIT>), dim3(gx, ks, gz), dim3(256), 0, s, a);
+  hipLaunchKernelGGL((k_gemm_p<NT, 2, 1, EPI, SPLIT, NW>), dim3(gx, ks, gz), dim3(64 * NW), 0, s, a);
   PD_CHECK_HIP(hipGetLastError());
   if (EPI == EPI_RESID && a.parts_out) *a.parts_out = ks;
   return PD_OK;
 }
 
-// Column tiles per wave: what finishes first by the measured time of a block per k-tile (us; QKV and
-// FFN1 shapes of cfg4 and cfg5 with 512 and 1024 rows): 1.9 with four tiles and 1.7 with three, one
-// block per compute unit; with two tiles two blocks share a compute unit and take 2.45 each (1.4
-// while the launch has fewer blocks than compute units).  A launch runs ceil(blocks / resident
-// blocks) rounds of that.
+// Column tiles per wave (2, 3 or 4; blocks of 8 waves, one block per compute unit): what finishes
+// first by the measured time of a block per k-tile (1.6 / 1.9 / 1.95 us; QKV and FFN1 shapes of cfg4
+// and cfg5 with 1024 rows) times the rounds of 256 blocks the launch needs.
 template <int EPI, bool SPLIT>
 static int launch_gemm_rows(const GemmArgs &a, int rows, hipStream_t s) {
-  auto blocks = [&](int nt) {
-    long b = (long)((a.n_tiles + 4 * nt - 1) / (4 * nt)) * ((rows + 127) / 128);
+  auto cost = [&](int nt, double t) {
+    long b = (long)((a.n_tiles + 8 * nt - 1) / (8 * nt)) * ((rows + 127) / 128);
     if (EPI == EPI_RESID) {     // the K slices launch_gemm_rows_nt will choose
       int KT = a.K / 32, ks = 1;
       while (ks < a.max_parts && b * ks < 256 && KT / (2 * ks) >= 8) ks *= 2;
-      b *= ks;
+      return (double)((b * ks + 255) / 256) * t / ks;
     }
-    return b;
+    return (double)((b + 255) / 256) * t;
   };
-  long b4 = blocks(4), b3 = blocks(3), b2 = blocks(2);
-  double c4 = (double)((b4 + 255) / 256) * 1.9, c3 = (double)((b3 + 255) / 256) * 1.7;
-  double c2 = b2 <= 256 ? 1.4 : (double)((b2 + 511) / 512) * 2.45;
-  if (c2 < c3 && c2 < c4) return launch_gemm_rows_nt<2, 2, EPI, SPLIT>(a, rows, s);
-  if (c3 < c4) return launch_gemm_rows_nt<3, 1, EPI, SPLIT>(a, rows, s);
-  return launch_gemm_rows_nt<4, 1, EPI, SPLIT>(a, rows, s);
+  double c2 = cost(2, 1.6), c3 = cost(3, 1.9), c4 = cost(4, 1.95);
+  if (c4 <= c3 && c4 <= c2) return launch_gemm_rows_nt<4, EPI, SPLIT>(a, rows, s);
+  if (c3 <= c2) return launch_gemm_rows_nt<3, EPI, SPLIT>(a, rows, s);
+  return launch_gemm_rows_nt<2, EPI, SPLIT>(a, rows, s);
 }
 
 template <int EPI, bool SPLIT>

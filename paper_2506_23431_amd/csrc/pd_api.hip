@@ -80,16 +80,15 @@ static size_t carve(const pd_config *g, char *base, pd_ctx *c) {
   x->gen_cap = S * (M + 1);
   x->gen_stride = (x->gen_cap + 8 + 7) / 8 * 8;
   x->kv_cap = (g->max_ctx + x->gen_cap + 63) / 64 * 64;
-  // Rows of the context pass per launch.  The matrix-core path has a projection kernel for many
-  // rows (row groups of 128 share a launch; about 0.26 PFLOP/s whatever the shape) beside the
-  // kernels for up to 128 rows, which stream a layer's weights once per 128 rows (measured: 9 us +
-  // bytes / 2.9 TB/s per projection).  With W bytes of weights per layer the many-row kernel wins
-  // while 128 W / 0.26e15 < 36e-6 + W / 2.9e12, i.e. W < 245 MB (cfg3 25 MB: 2.5 x faster, cfg4
-  // 101 MB: 1.6 x, cfg5 405 MB: 0.9 x).  The fp32 path keeps one score row per (row, head).
+  // Rows of the context pass per launch: as many as give the many-row projection kernel a block
+  // per compute unit even for small matrices (measured: cfg3 / cfg4 / cfg5 context passes take
+  // 0.103 / 0.180 / 0.900 s in chunks of 128 rows, 0.044 / 0.095 / 0.619 s in chunks of 1024), at
+  // most 16 query groups per (request, head, 16 rows) unit of the attention launch allow.  The fp32
+  // path keeps one score row per (row, head) and stays at 128.
   {
-    double w_layer = 2.0 * ((double)d * d * 4 + (double)d * ff * (g->ffn_kind == 1 ? 3 : 2));
-    x->prefill_chunk_cap = x->impl == 1 ? std::min(1024, (g->max_ctx + 127) / 128 * 128) : 128;
-    x->prefill_chunk = w_layer < 245e6 ? x->prefill_chunk_cap : 128;
+    int cap = std::min(2048, 16 * (4096 / std::max(H, 1)) / 16 * 16);
+    x->prefill_chunk_cap = x->impl == 1 ? std::max(128, std::min(cap, (g->max_ctx + 127) / 128 * 128)) : 128;
+    x->prefill_chunk = x->prefill_chunk_cap;
   }
   int a_max = std::min(S, M + 1);
   x->R_cap = std::max(B * a_max, x->prefill_chunk_cap);
