@@ -150,10 +150,10 @@ int pd_reset_decode(pd_ctx *ctx, void *hip_stream);
  *                        multiply as a pair of bf16 values (about 16 mantissa bits) and runs two
  *                        matrix-core passes per weight / key / value fragment; 0 uses plain bf16
  *                        activations (half the matrix-core work, larger rounding error)
- *   PD_OPT_PREFILL_CHUNK rows of the context pass per launch (0 = default: 1024 on the bf16 path, 128
- *                        when a layer's weights exceed 245 MB and on the fp32 path; other
- *                        values are rounded up to a multiple of 16 and capped at 1024 / 128).
- *                        Results do not depend on it beyond rounding order.
+ *   PD_OPT_PREFILL_CHUNK rows of the context pass per launch (0 = default: up to 2048 on the bf16
+ *                        path, 128 on the fp32 path; other values are rounded up to a multiple
+ *                        of 16 and capped at that default).  Results do not depend on it beyond
+ *                        rounding order.
  * The environment variable PD_IMPL=simple makes pd_create choose the fp32-activation kernels
  * for dtype 1 too (debugging aid).                                                     */
 #define PD_OPT_ATTN_SPLITS 1
