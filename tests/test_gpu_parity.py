@@ -426,6 +426,23 @@ def test_whole_workload_bf16_kernels_against_fp32_kernels(name):
     dec.close()
 
 
+@pytest.mark.parametrize("chunk", [256, 160, 48])
+def test_context_pass_in_several_chunks(chunk):
+    """600 context tokens in chunks of 256 (two launches of the many-row kernels and a tail of 88
+    rows in the 128-row kernels), 160 (three and a tail of 120) and 48 rows: the caches the context
+    pass leaves behind must give the oracle's logits whatever the chunking."""
+    from paper_2506_23431_amd import binding
+    cfg = CASES["mfma-flat"]
+    w = pi.make_weights(cfg, threads=4)
+    ctx = pi.make_context(cfg)
+    outs = oracle_run(cfg, w, ctx)
+    dec = make_decoder(cfg, w)
+    dec.set_option(binding.PD_OPT_PREFILL_CHUNK, chunk)
+    stats = compare_teacher_forced(cfg, w, ctx, dec, outs, log=say)
+    assert stats["rows"] == cfg.batch * (cfg.n_sub * (cfg.sub_tokens + 1) - 1)
+    dec.close()
+
+
 def test_options_do_not_change_results():
     """HIP-graph replay of the step, other attention split counts, other chunk sizes of the context
     pass (the default here is all 150 rows at once, in the many-row projection kernel) and
