@@ -117,8 +117,8 @@ def main():
                          "traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print(f"bench.py: this build runs on one GPU only (got --gpus {args.gpus}); "
-              "see DESIGN.md for how the path would shard", file=sys.stderr)
+        print(f"bench.py: this build runs on one GPU only (got --gpus {args.gpus}): no collectives, no "
+              "sharding; requests, context keys and heads are the axes it would shard along", file=sys.stderr)
         sys.exit(2)
 
     import torch
