@@ -22,6 +22,9 @@ int mfma_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_overri
   a.n_tiles = 3 * d / 16; a.out_bf = (bf16_t *)c->q; a.out_lo = mfma_lo(c, c->q, d); a.kc = (f16_t *)lw.kc; a.vc = (f16_t *)lw.vc; a.rope_cs = c->rope_cs;
   a.kc_lo = (f16_t *)lw.kc_lo; a.vc_lo = (f16_t *)lw.vc_lo;
   if ((rc = mfma_gemm(g.pos_kind == 1 ? EPI_QKV_ROPE : EPI_QKV, a, R, s))) return rc;
+  // context pass, last layer: only its keys and values are ever used (nothing reads the residual
+  // stream of a context token after the last layer)
+  if (kv_override >= 0 && l == g.n_layer - 1) return PD_OK;
   if ((rc = mfma_attention(c, lw, A, nreq, req0, kv_override, s))) return rc;
   // output projection + residual
   a.W = lw.p_wo; a.xn = (const bf16_t *)c->att; a.xn_lo = mfma_lo(c, c->att, d); a.K = d; a.n_tiles = d / 16; a.x = c->ypart; a.ld = d;

@@ -259,11 +259,13 @@ int simple_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_over
   const float *cs = g.pos_kind == 1 ? c->rope_cs : nullptr;
   float scale = 1.0f / sqrtf((float)hd);
   size_t shm = (hd + 16 + 256) * sizeof(float);
+  // context pass, last layer: only its keys and values are ever used
+  const bool kv_only = kv_override >= 0 && l == g.n_layer - 1;
   if (g.dtype == 0) {
     hipLaunchKernelGGL(k_qkv_post<float>, dim3(R), dim3(256), 0, s, c->qkv32, (float *)lw.kc,
                        (float *)lw.vc, (float *)nullptr, (float *)nullptr, c->rows, cs, d, H, hd,
                        c->kv_cap);
-    hipLaunchKernelGGL(k_attn<float>, dim3(R, H), dim3(256), shm, s, att, c->qkv32,
+    if (!kv_only) hipLaunchKernelGGL(k_attn<float>, dim3(R, H), dim3(256), shm, s, att, c->qkv32,
                        (const float *)lw.kc, (const float *)lw.vc, (const float *)nullptr,
                        (const float *)nullptr, c->scores, c->rows,
                        c->sch.kv_len, c->sch.gen_sub, kv_override, d, H, hd, c->kv_cap, c->gen_stride,
@@ -272,13 +274,14 @@ int simple_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_over
     hipLaunchKernelGGL(k_qkv_post<f16_t>, dim3(R), dim3(256), 0, s, c->qkv32, (f16_t *)lw.kc,
                        (f16_t *)lw.vc, (f16_t *)lw.kc_lo, (f16_t *)lw.vc_lo, c->rows, cs, d, H, hd,
                        c->kv_cap);
-    hipLaunchKernelGGL(k_attn<f16_t>, dim3(R, H), dim3(256), shm, s, att, c->qkv32,
+    if (!kv_only) hipLaunchKernelGGL(k_attn<f16_t>, dim3(R, H), dim3(256), shm, s, att, c->qkv32,
                        (const f16_t *)lw.kc, (const f16_t *)lw.vc, (const f16_t *)lw.kc_lo,
                        (const f16_t *)lw.vc_lo, c->scores, c->rows,
                        c->sch.kv_len, c->sch.gen_sub, kv_override, d, H, hd, c->kv_cap, c->gen_stride,
                        c->L, scale);
   }
   PD_CHECK_HIP(hipGetLastError());
+  if (kv_only) return PD_OK;
   if ((rc = linear<1>(c, c->x, att, lw.wo, nullptr, c->x, R, d, d, s))) return rc;
   hipLaunchKernelGGL(k_norm_f32, dim3(R), dim3(256), 0, s, xn, c->x, lw.n2g, lw.n2b, d, g.norm_kind,
                      g.norm_eps, c->rows.flags);
