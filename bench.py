@@ -102,9 +102,9 @@ def main():
     ap.add_argument("--workload", default="cfg4")
     ap.add_argument("--graph", type=int, default=0, help="replay each step from a captured HIP graph")
     ap.add_argument("--attn-splits", type=int, default=0)
-    ap.add_argument("--kv-pair-layers", type=int, default=0,
+    ap.add_argument("--kv-pair-layers", type=int, default=None,
                     help="leading layers whose cache keeps keys and values as pairs of halves (cfg5 needs 1 "
-                         "to stay inside the logit tolerance; cfg1-cfg4 do not)")
+                         "to stay inside the logit tolerance and gets it by default; cfg1-cfg4 do not)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sync-every", type=int, default=0,
                     help="synchronise after every N iterations of the timed pass (0: never; a counter-collecting "
@@ -116,6 +116,8 @@ def main():
                     help="also run plain device-to-device copies of this many MiB (a kernel of known "
                          "traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
+    if args.kv_pair_layers is None:
+        args.kv_pair_layers = 1 if args.workload.startswith("cfg5") else 0
     if args.gpus != 1:
         print(f"bench.py: this build runs on one GPU only (got --gpus {args.gpus}): no collectives, no "
               "sharding; requests, context keys and heads are the axes it would shard along", file=sys.stderr)
