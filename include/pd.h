@@ -176,6 +176,21 @@ int pd_profile_read(pd_ctx *ctx, double *attn_avg_us, int32_t *attn_launches);
 int pd_measure_read_bandwidth(const void *dev_buf, size_t buf_bytes, size_t chunk_bytes, int iters,
                               void *hip_stream, double *gb_per_s);
 
+/* Measurement aid: bandwidth in GB/s of a kernel in which each of `blocks` work-groups reads its
+ * own slice of `slice_bytes` (multiple of 32768) `passes` times: what the caches deliver when the
+ * slices together fit them (L2: 4 MB per XCD, 32 MB in all) and what comes from behind them when
+ * they do not.  `dev_buf` DEVICE, 16-byte aligned, at least blocks * slice_bytes + 256 bytes (the
+ * last 256 may be written).  One warm-up launch, one timed launch.  Synchronises. */
+int pd_measure_cached_read_bandwidth(const void *dev_buf, size_t buf_bytes, int blocks, size_t slice_bytes,
+                                     int passes, void *hip_stream, double *gb_per_s);
+
+/* Measurement aid: nanoseconds a SIMD needs per 16x16x32 bf16 matrix-core instruction when
+ * `waves_per_simd` waves (1..8) issue independent instructions on it, over `iters` iterations of
+ * 16 instructions per wave on every compute unit.  `dev_scratch` DEVICE, written (1 KiB per
+ * work-group: 4 * waves_per_simd KiB per compute unit).  Synchronises. */
+int pd_measure_mfma_issue(void *dev_scratch, size_t scratch_bytes, int waves_per_simd, int iters,
+                          void *hip_stream, double *ns_per_instruction);
+
 /* Message for the last error on this thread (static storage, never NULL). */
 const char *pd_last_error(void);
 

@@ -16,7 +16,8 @@ PD_OPT_ATTN_SPLITS, PD_OPT_USE_GRAPH, PD_OPT_PROFILE, PD_OPT_SPLIT_ACT, PD_OPT_P
 
 EXPORTS = ["pd_workspace_bytes", "pd_create", "pd_destroy", "pd_prefill_context", "pd_decode_step",
            "pd_generate", "pd_decode_steps", "pd_reset_decode", "pd_set_option", "pd_profile_read",
-           "pd_measure_read_bandwidth", "pd_last_error"]
+           "pd_measure_read_bandwidth", "pd_measure_cached_read_bandwidth", "pd_measure_mfma_issue",
+           "pd_last_error"]
 
 
 class PdError(RuntimeError):
@@ -63,6 +64,9 @@ def load():
     lib.pd_set_option.argtypes = [vp, C.c_int, C.c_int]
     lib.pd_profile_read.argtypes = [vp, C.POINTER(C.c_double), i32p]
     lib.pd_measure_read_bandwidth.argtypes = [vp, C.c_size_t, C.c_size_t, C.c_int, vp, C.POINTER(C.c_double)]
+    lib.pd_measure_cached_read_bandwidth.argtypes = [vp, C.c_size_t, C.c_int, C.c_size_t, C.c_int, vp,
+                                                     C.POINTER(C.c_double)]
+    lib.pd_measure_mfma_issue.argtypes = [vp, C.c_size_t, C.c_int, C.c_int, vp, C.POINTER(C.c_double)]
     lib.pd_last_error.restype = C.c_char_p
     for name in EXPORTS:
         getattr(lib, name)
@@ -218,4 +222,20 @@ def measure_read_bandwidth(dev_ptr, buf_bytes, chunk_bytes, iters, stream=None):
     out = C.c_double(0)
     _check(load().pd_measure_read_bandwidth(C.c_void_p(dev_ptr), buf_bytes, chunk_bytes, iters,
                                             C.c_void_p(stream or 0), C.byref(out)))
+    return out.value
+
+
+def measure_cached_read_bandwidth(dev_ptr, buf_bytes, blocks, slice_bytes, passes, stream=None):
+    """GB/s of a kernel whose `blocks` work-groups each read their own slice `passes` times."""
+    out = C.c_double(0)
+    _check(load().pd_measure_cached_read_bandwidth(C.c_void_p(dev_ptr), buf_bytes, blocks, slice_bytes, passes,
+                                                   C.c_void_p(stream or 0), C.byref(out)))
+    return out.value
+
+
+def measure_mfma_issue(dev_ptr, scratch_bytes, waves_per_simd, iters, stream=None):
+    """Nanoseconds per 16x16x32 bf16 matrix-core instruction and SIMD with that many waves per SIMD."""
+    out = C.c_double(0)
+    _check(load().pd_measure_mfma_issue(C.c_void_p(dev_ptr), scratch_bytes, waves_per_simd, iters,
+                                        C.c_void_p(stream or 0), C.byref(out)))
     return out.value

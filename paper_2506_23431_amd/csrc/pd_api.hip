@@ -541,3 +541,101 @@ extern "C" int pd_measure_read_bandwidth(const void *dev_buf, size_t buf_bytes, 
   *gb_per_s = (double)chunk_bytes * iters / (ms * 1e-3) * 1e-9;
   return PD_OK;
 }
+
+// ---------------------------------------------------------------------------
+// repeated read of per-block slices: what the caches deliver when a kernel's working set fits them
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_slice_read(const uint4 *p, int slice_u4, int passes, unsigned *sink) {
+  const uint4 *base = p + (size_t)blockIdx.x * slice_u4;
+  unsigned acc = 0;
+  for (int r = 0; r < passes; ++r) {
+    for (int o = threadIdx.x; o + 7 * 256 < slice_u4; o += 8 * 256) {
+      uint4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = base[o + u * 256];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+  }
+  if (acc == 0x9e3779b9u) *sink = acc;       // keeps the loads alive; practically never taken
+}
+
+extern "C" int pd_measure_cached_read_bandwidth(const void *dev_buf, size_t buf_bytes, int blocks,
+                                                size_t slice_bytes, int passes, void *hip_stream,
+                                                double *gb_per_s) {
+  PD_REQUIRE(dev_buf && gb_per_s && blocks >= 1 && passes >= 1, PD_EINVAL, "NULL buffer / result, blocks or passes < 1");
+  PD_REQUIRE(slice_bytes >= 32768 && slice_bytes % 32768 == 0, PD_EINVAL, "slice_bytes must be a multiple of 32768");
+  PD_REQUIRE((size_t)blocks * slice_bytes + 256 <= buf_bytes, PD_EINVAL, "blocks * slice_bytes (+256) exceed the buffer");
+  PD_REQUIRE(((uintptr_t)dev_buf & 15) == 0, PD_EINVAL, "buffer must be 16-byte aligned");
+  hipStream_t s = (hipStream_t)hip_stream;
+  hipEvent_t e0, e1;
+  PD_CHECK_HIP(hipEventCreate(&e0));
+  PD_CHECK_HIP(hipEventCreate(&e1));
+  unsigned *sink = (unsigned *)((char *)dev_buf + (buf_bytes - 256) / 16 * 16);
+  int slice_u4 = (int)(slice_bytes / 16);
+  hipLaunchKernelGGL(k_slice_read, dim3(blocks), dim3(256), 0, s, (const uint4 *)dev_buf, slice_u4, 2, sink);
+  PD_CHECK_HIP(hipEventRecord(e0, s));
+  hipLaunchKernelGGL(k_slice_read, dim3(blocks), dim3(256), 0, s, (const uint4 *)dev_buf, slice_u4, passes, sink);
+  PD_CHECK_HIP(hipEventRecord(e1, s));
+  PD_CHECK_HIP(hipEventSynchronize(e1));
+  float ms = 0.f;
+  PD_CHECK_HIP(hipEventElapsedTime(&ms, e0, e1));
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  PD_CHECK_HIP(hipGetLastError());
+  *gb_per_s = (double)blocks * slice_bytes * passes / (ms * 1e-3) * 1e-9;
+  return PD_OK;
+}
+
+// ---------------------------------------------------------------------------
+// issue rate of the 16x16x32 bf16 matrix-core instruction with 1, 2, ... waves per SIMD
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_mfma_rate(float *out, int iters) {
+  typedef float f4 __attribute__((ext_vector_type(4)));
+  typedef __bf16 b8 __attribute__((ext_vector_type(8)));
+  f4 acc[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc[i] = f4{0.f, 0.f, 0.f, 0.f};
+  union { uint4 u; b8 v; } a, b;
+  a.u = make_uint4(threadIdx.x, 1, 2, 3);
+  b.u = make_uint4(4, 5, threadIdx.x, 7);
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, acc[i], 0, 0, 0);
+  }
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) sum += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
+  out[(size_t)blockIdx.x * 256 + threadIdx.x] = sum;
+}
+
+extern "C" int pd_measure_mfma_issue(void *dev_scratch, size_t scratch_bytes, int waves_per_simd, int iters,
+                                     void *hip_stream, double *ns_per_instruction) {
+  PD_REQUIRE(dev_scratch && ns_per_instruction && iters >= 1, PD_EINVAL, "NULL scratch / result or iters < 1");
+  PD_REQUIRE(waves_per_simd >= 1 && waves_per_simd <= 8, PD_EINVAL, "waves_per_simd must be in [1, 8]");
+  hipDeviceProp_t prop;
+  int dev = 0;
+  PD_CHECK_HIP(hipGetDevice(&dev));
+  PD_CHECK_HIP(hipGetDeviceProperties(&prop, dev));
+  int blocks = prop.multiProcessorCount * waves_per_simd;      // 4 waves per block, one per SIMD
+  PD_REQUIRE((size_t)blocks * 256 * sizeof(float) <= scratch_bytes, PD_EINVAL,
+             "scratch too small: %zu bytes needed", (size_t)blocks * 256 * sizeof(float));
+  hipStream_t s = (hipStream_t)hip_stream;
+  hipEvent_t e0, e1;
+  PD_CHECK_HIP(hipEventCreate(&e0));
+  PD_CHECK_HIP(hipEventCreate(&e1));
+  hipLaunchKernelGGL(k_mfma_rate, dim3(blocks), dim3(256), 0, s, (float *)dev_scratch, 16);
+  PD_CHECK_HIP(hipEventRecord(e0, s));
+  hipLaunchKernelGGL(k_mfma_rate, dim3(blocks), dim3(256), 0, s, (float *)dev_scratch, iters);
+  PD_CHECK_HIP(hipEventRecord(e1, s));
+  PD_CHECK_HIP(hipEventSynchronize(e1));
+  float ms = 0.f;
+  PD_CHECK_HIP(hipEventElapsedTime(&ms, e0, e1));
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  PD_CHECK_HIP(hipGetLastError());
+  // instructions one SIMD executed: 16 per iteration and wave
+  *ns_per_instruction = (double)ms * 1e6 / ((double)iters * 16 * waves_per_simd);
+  return PD_OK;
+}
+

@@ -548,3 +548,15 @@ def test_plain_read_bandwidth_measurement():
         binding.measure_read_bandwidth(buf.data_ptr(), buf.numel(), buf.numel(), 1)
     with pytest.raises(PdError, match="aligned"):
         binding.measure_read_bandwidth(buf.data_ptr() + 4, buf.numel() - 4, 1 << 20, 1)
+
+
+def test_device_probes():
+    """The probes behind the design figures run and order the way the design assumes: reads served by
+    L2 beat reads from behind it, and a SIMD issues matrix-core instructions faster with two waves."""
+    from paper_2506_23431_amd import probes
+    out = probes.main([])
+    sl = {(r["blocks"], r["slice_KiB"]): r["GB/s"] for r in out["slices"]}
+    assert sl[(256, 64)] > 1.5 * sl[(1024, 256)]
+    ns = {r["waves_per_simd"]: r["ns_per_instruction"] for r in out["mfma_issue"]}
+    assert ns[2] < 0.9 * ns[1] and ns[4] < 0.9 * ns[1]
+
