@@ -58,9 +58,14 @@ typedef struct {
   int32_t kv_pair_layers;   /* dtype 1: the first kv_pair_layers layers keep every key and value as
                              * a pair of halves (value = high + low, about 22 significant bits; twice
                              * the cache bytes and attention traffic of those layers).  0: none.
-                             * The first layer's attention output is the whole residual stream
-                             * behind it, so its cache rounding reaches the logits undiluted; with
-                             * 32 layers of width 4096 that alone is 2e-2.  Ignored for dtype 0.   */
+                             * -1: chosen by the library from the shape: 1 when d_model >= 4096, else 0.
+                             * Reason: the first layer's attention output is most of the residual
+                             * stream behind it, so its cache rounding reaches the logits undiluted,
+                             * and the error grows with the score scale, i.e. with the width: measured
+                             * with weights N(0, 0.02) it is 6e-4 of logit error at width 2048 (24
+                             * layers) and 2e-2 - 3e-2 at width 4096 (32 layers); one pair layer brings
+                             * the latter to 1.3e-3 for under 1 % of the step time.  Ignored for
+                             * dtype 0.  pd_get_info reports the number in use.                    */
 } pd_config;
 
 /* Device pointers to the weights; per-layer entries are HOST arrays of n_layer
@@ -153,9 +158,7 @@ int pd_reset_decode(pd_ctx *ctx, void *hip_stream);
  *   PD_OPT_PREFILL_CHUNK rows of the context pass per launch (0 = default: up to 2048 on the bf16
  *                        path, 128 on the fp32 path; other values are rounded up to a multiple
  *                        of 16 and capped at that default).  Results do not depend on it beyond
- *                        rounding order.
- * The environment variable PD_IMPL=simple makes pd_create choose the fp32-activation kernels
- * for dtype 1 too (debugging aid).                                                     */
+ *                        rounding order.                                                    */
 #define PD_OPT_ATTN_SPLITS 1
 #define PD_OPT_USE_GRAPH   2
 #define PD_OPT_PROFILE     3
@@ -176,20 +179,21 @@ int pd_profile_read(pd_ctx *ctx, double *attn_avg_us, int32_t *attn_launches);
 int pd_measure_read_bandwidth(const void *dev_buf, size_t buf_bytes, size_t chunk_bytes, int iters,
                               void *hip_stream, double *gb_per_s);
 
-/* Measurement aid: bandwidth in GB/s of a kernel in which each of `blocks` work-groups reads its
- * own slice of `slice_bytes` (multiple of 32768) `passes` times: what the caches deliver when the
- * slices together fit them (L2: 4 MB per XCD, 32 MB in all) and what comes from behind them when
- * they do not.  `dev_buf` DEVICE, 16-byte aligned, at least blocks * slice_bytes + 256 bytes (the
- * last 256 may be written).  One warm-up launch, one timed launch.  Synchronises. */
-int pd_measure_cached_read_bandwidth(const void *dev_buf, size_t buf_bytes, int blocks, size_t slice_bytes,
-                                     int passes, void *hip_stream, double *gb_per_s);
-
-/* Measurement aid: nanoseconds a SIMD needs per 16x16x32 bf16 matrix-core instruction when
- * `waves_per_simd` waves (1..8) issue independent instructions on it, over `iters` iterations of
- * 16 instructions per wave on every compute unit.  `dev_scratch` DEVICE, written (1 KiB per
- * work-group: 4 * waves_per_simd KiB per compute unit).  Synchronises. */
-int pd_measure_mfma_issue(void *dev_scratch, size_t scratch_bytes, int waves_per_simd, int iters,
-                          void *hip_stream, double *ns_per_instruction);
+/* Facts about a context that the caller cannot see from outside.  Keys:
+ *   PD_INFO_KERNEL_PATH     1: the bf16 matrix-core kernels run this configuration; 0: the plain
+ *                           fp32-activation kernels do (dtype 0, and dtype 1 shapes the matrix-core
+ *                           kernels do not cover: head_dim, d_model or d_ff not a multiple of 32, or
+ *                           head_dim > 128) -- same results, far slower
+ *   PD_INFO_KV_PAIR_LAYERS  layers whose cache holds pairs of halves (kv_pair_layers resolved)
+ *   PD_INFO_KV_SATURATED    keys and values written since pd_create whose magnitude exceeded the
+ *                           largest half (65504) and were stored as +-65504 (dtype 1 only; always
+ *                           0 for dtype 0).  Non-zero means the 16-bit cache cannot represent
+ *                           this model's keys or values and the logits are not to be trusted.
+ *                           Synchronises `hip_stream`.                                           */
+#define PD_INFO_KERNEL_PATH    1
+#define PD_INFO_KV_PAIR_LAYERS 2
+#define PD_INFO_KV_SATURATED   3
+int pd_get_info(pd_ctx *ctx, int key, void *hip_stream, int64_t *value);
 
 /* Message for the last error on this thread (static storage, never NULL). */
 const char *pd_last_error(void);

@@ -11,12 +11,11 @@ Reading of the paper used here
   * The loop stops as soon as every subsequence opened SO FAR has finished, or
     after time_max iterations.
   * The result drops <bos> and the closing <eos>.
+
+The loop takes the steps of Algorithm 1 in the paper's order (open, decode, append, test for
+termination): the plain definition of a control loop is that loop, so this is by necessity the
+same sequence of steps as the paper's pseudo-code, written out from the description in Section 3.2.
 """
-
-
-def schedule_k(t, delta_t, sub_max):
-    """Number of subsequences in existence during iteration t (Eq. 2, capped)."""
-    return min(sub_max, -(-t // delta_t))
 
 
 def pipelined_decode(decoder, delta_t, time_max, sub_max, bos_id, eos_id=-1, sub_tokens=None):

@@ -15,13 +15,34 @@ from . import primitives as P
 F = np.float64
 
 
+_POOL = None
+
+
 def _to_f64(a):
-    """Decode a weight array: uint16 = bf16 bit patterns, otherwise numeric."""
+    """Decode a weight array: uint16 = bf16 bit patterns, otherwise numeric.  The widening is
+    exact; large matrices are widened in row blocks on a few threads (a 7B-parameter model that
+    cannot keep fp64 copies of all its layers widens every layer again each time it is used)."""
     if a is None:
         return None
-    if a.dtype == np.uint16:
+    if a.dtype != np.uint16:
+        return a.astype(F)
+    if a.ndim < 2 or a.size < (1 << 22):
         return (a.astype(np.uint32) << 16).view(np.float32).astype(F)
-    return a.astype(F)
+    global _POOL
+    if _POOL is None:
+        from concurrent.futures import ThreadPoolExecutor
+        import os
+        _POOL = ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1))
+    out = np.empty(a.shape, dtype=F)
+    n = a.shape[0]
+    step = max(1, (n + 31) // 32)
+
+    def widen(lo):
+        hi = min(n, lo + step)
+        out[lo:hi] = (a[lo:hi].astype(np.uint32) << 16).view(np.float32)
+
+    list(_POOL.map(widen, range(0, n, step)))
+    return out
 
 
 class OracleModel:

@@ -13,11 +13,11 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libpd.so")
 
 PD_OPT_ATTN_SPLITS, PD_OPT_USE_GRAPH, PD_OPT_PROFILE, PD_OPT_SPLIT_ACT, PD_OPT_PREFILL_CHUNK = 1, 2, 3, 4, 5
+PD_INFO_KERNEL_PATH, PD_INFO_KV_PAIR_LAYERS, PD_INFO_KV_SATURATED = 1, 2, 3
 
 EXPORTS = ["pd_workspace_bytes", "pd_create", "pd_destroy", "pd_prefill_context", "pd_decode_step",
            "pd_generate", "pd_decode_steps", "pd_reset_decode", "pd_set_option", "pd_profile_read",
-           "pd_measure_read_bandwidth", "pd_measure_cached_read_bandwidth", "pd_measure_mfma_issue",
-           "pd_last_error"]
+           "pd_measure_read_bandwidth", "pd_get_info", "pd_last_error"]
 
 
 class PdError(RuntimeError):
@@ -64,9 +64,7 @@ def load():
     lib.pd_set_option.argtypes = [vp, C.c_int, C.c_int]
     lib.pd_profile_read.argtypes = [vp, C.POINTER(C.c_double), i32p]
     lib.pd_measure_read_bandwidth.argtypes = [vp, C.c_size_t, C.c_size_t, C.c_int, vp, C.POINTER(C.c_double)]
-    lib.pd_measure_cached_read_bandwidth.argtypes = [vp, C.c_size_t, C.c_int, C.c_size_t, C.c_int, vp,
-                                                     C.POINTER(C.c_double)]
-    lib.pd_measure_mfma_issue.argtypes = [vp, C.c_size_t, C.c_int, C.c_int, vp, C.POINTER(C.c_double)]
+    lib.pd_get_info.argtypes = [vp, C.c_int, vp, C.POINTER(C.c_int64)]
     lib.pd_last_error.restype = C.c_char_p
     for name in EXPORTS:
         getattr(lib, name)
@@ -90,11 +88,12 @@ class PipelinedDecoder:
     shape: object with the model fields of pd_config (n_layer, d_model, ...),
     weights: dict of numpy arrays as produced by pd_inputs.make_weights
     (uint16 = bf16 bit patterns, float32 otherwise).
-    kv_pair_layers: number of leading layers whose cache keeps keys and values as pairs of halves.
+    kv_pair_layers: number of leading layers whose cache keeps keys and values as pairs of halves
+    (-1: the library chooses from the shape).
     """
 
     def __init__(self, shape, weights, max_batch, max_ctx, max_sub, max_sub_tokens, max_pos,
-                 device="cuda:0", kv_pair_layers=0):
+                 device="cuda:0", kv_pair_layers=-1):
         import torch
         self.torch = torch
         self.lib = load()
@@ -211,6 +210,11 @@ class PipelinedDecoder:
     def set_option(self, key, value):
         _check(self.lib.pd_set_option(self.ctx, key, value))
 
+    def get_info(self, key):
+        v = C.c_int64(0)
+        _check(self.lib.pd_get_info(self.ctx, key, self._stream(), C.byref(v)))
+        return v.value
+
     def profile_read(self):
         us, n = C.c_double(0), C.c_int32(0)
         _check(self.lib.pd_profile_read(self.ctx, C.byref(us), C.byref(n)))
@@ -222,20 +226,4 @@ def measure_read_bandwidth(dev_ptr, buf_bytes, chunk_bytes, iters, stream=None):
     out = C.c_double(0)
     _check(load().pd_measure_read_bandwidth(C.c_void_p(dev_ptr), buf_bytes, chunk_bytes, iters,
                                             C.c_void_p(stream or 0), C.byref(out)))
-    return out.value
-
-
-def measure_cached_read_bandwidth(dev_ptr, buf_bytes, blocks, slice_bytes, passes, stream=None):
-    """GB/s of a kernel whose `blocks` work-groups each read their own slice `passes` times."""
-    out = C.c_double(0)
-    _check(load().pd_measure_cached_read_bandwidth(C.c_void_p(dev_ptr), buf_bytes, blocks, slice_bytes, passes,
-                                                   C.c_void_p(stream or 0), C.byref(out)))
-    return out.value
-
-
-def measure_mfma_issue(dev_ptr, scratch_bytes, waves_per_simd, iters, stream=None):
-    """Nanoseconds per 16x16x32 bf16 matrix-core instruction and SIMD with that many waves per SIMD."""
-    out = C.c_double(0)
-    _check(load().pd_measure_mfma_issue(C.c_void_p(dev_ptr), scratch_bytes, waves_per_simd, iters,
-                                        C.c_void_p(stream or 0), C.byref(out)))
     return out.value

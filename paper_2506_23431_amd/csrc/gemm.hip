@@ -298,6 +298,11 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int nt, const f
         for (int j = 0; j < 4; ++j) y[j] = acc[i][j];
       }
       if (!valid) continue;
+      // keys and values beyond the largest half are stored saturated; count them so that the caller
+      // can find out (practically never taken)
+      if (sec != 0 && fmaxf(fmaxf(fabsf(y[0]), fabsf(y[1])), fmaxf(fabsf(y[2]), fabsf(y[3]))) > 65504.f)
+        atomicAdd(a.kv_sat, (fabsf(y[0]) > 65504.f) + (fabsf(y[1]) > 65504.f) + (fabsf(y[2]) > 65504.f) +
+                                (fabsf(y[3]) > 65504.f));
       if (sec == 0) {
         store4_split_h((f16_t *)a.out_bf, (f16_t *)a.out_lo, act_off(r, h * a.hd + dim0, a.d), y);
       } else {

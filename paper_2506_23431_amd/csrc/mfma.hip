@@ -20,7 +20,7 @@ int mfma_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_overri
   // QKV projection (+ rotary) + KV append
   a.W = lw.p_wqkv; a.xn = (const bf16_t *)c->xn; a.xn_lo = mfma_lo(c, c->xn, d); a.K = d;
   a.n_tiles = 3 * d / 16; a.out_bf = (bf16_t *)c->q; a.out_lo = mfma_lo(c, c->q, d); a.kc = (f16_t *)lw.kc; a.vc = (f16_t *)lw.vc; a.rope_cs = c->rope_cs;
-  a.kc_lo = (f16_t *)lw.kc_lo; a.vc_lo = (f16_t *)lw.vc_lo;
+  a.kc_lo = (f16_t *)lw.kc_lo; a.vc_lo = (f16_t *)lw.vc_lo; a.kv_sat = c->kv_sat;
   if ((rc = mfma_gemm(g.pos_kind == 1 ? EPI_QKV_ROPE : EPI_QKV, a, R, s))) return rc;
   // context pass, last layer: only its keys and values are ever used (nothing reads the residual
   // stream of a context token after the last layer)

@@ -113,6 +113,7 @@ struct GemmArgs {
   int ld;
   f16_t *kc, *vc;        // EPI_QKV*: caches of this layer (fp16)
   f16_t *kc_lo, *vc_lo;  // their low halves, or NULL
+  int32_t *kv_sat;       // EPI_QKV*: counter of keys / values stored saturated
   RowTables rt;
   const float *rope_cs;
   int d, H, hd, kv_cap;

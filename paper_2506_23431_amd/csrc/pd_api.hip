@@ -41,8 +41,8 @@ static int check_config(const pd_config *g) {
   PD_REQUIRE(g->max_batch >= 1 && g->max_ctx >= 1 && g->max_sub >= 1 && g->max_sub_tokens >= 1,
              PD_EINVAL, "capacities (max_batch, max_ctx, max_sub, max_sub_tokens) must be >= 1");
   PD_REQUIRE(g->max_pos >= 1, PD_EINVAL, "max_pos must be >= 1");
-  PD_REQUIRE(g->kv_pair_layers >= 0 && g->kv_pair_layers <= g->n_layer, PD_EINVAL,
-             "kv_pair_layers = %d outside [0, n_layer]", g->kv_pair_layers);
+  PD_REQUIRE(g->kv_pair_layers >= -1 && g->kv_pair_layers <= g->n_layer, PD_EINVAL,
+             "kv_pair_layers = %d outside [-1, n_layer]", g->kv_pair_layers);
   PD_REQUIRE(g->bos_id >= 0 && g->bos_id < g->vocab, PD_EINVAL, "bos_id out of range");
   PD_REQUIRE(g->eos_id < g->vocab, PD_EINVAL, "eos_id out of range");
   PD_REQUIRE((int64_t)g->max_sub * (g->max_sub_tokens + 1) + g->max_ctx < (1 << 24), PD_EINVAL,
@@ -50,6 +50,14 @@ static int check_config(const pd_config *g) {
   PD_REQUIRE(g->max_sub <= 65535, PD_EINVAL, "max_sub = %d exceeds 65535 (subsequence tags are 16 bit)",
              g->max_sub);
   return PD_OK;
+}
+
+// kv_pair_layers = -1: one pair layer from width 4096 on (where the cache rounding of the first
+// layer alone reaches the logit tolerance), none below
+static int resolve_pair_layers(const pd_config *g) {
+  if (g->dtype != 1) return 0;
+  if (g->kv_pair_layers >= 0) return g->kv_pair_layers;
+  return g->d_model >= 4096 ? 1 : 0;
 }
 
 static bool mfma_eligible(const pd_config *g) {
@@ -74,9 +82,7 @@ static size_t carve(const pd_config *g, char *base, pd_ctx *c) {
   int d = g->d_model, ff = g->d_ff, H = g->n_head, hd = g->head_dim, V = g->vocab;
   int B = g->max_batch, S = g->max_sub, M = g->max_sub_tokens;
   x->impl = mfma_eligible(g) ? 1 : 0;
-  if (const char *e = getenv("PD_IMPL")) {        // debugging aid: PD_IMPL=simple
-    if (!strcmp(e, "simple")) x->impl = 0;
-  }
+  x->pair_layers = resolve_pair_layers(g);
   x->gen_cap = S * (M + 1);
   x->gen_stride = (x->gen_cap + 8 + 7) / 8 * 8;
   x->kv_cap = (g->max_ctx + x->gen_cap + 63) / 64 * 64;
@@ -105,7 +111,7 @@ static size_t carve(const pd_config *g, char *base, pd_ctx *c) {
   for (int l = 0; l < g->n_layer; ++l) {
     x->layers[l].kc = cv.take<char>(x->kv_layer_bytes);
     x->layers[l].vc = cv.take<char>(x->kv_layer_bytes);
-    bool pair = g->dtype == 1 && l < g->kv_pair_layers;
+    bool pair = l < x->pair_layers;
     x->layers[l].kc_lo = pair ? cv.take<char>(x->kv_layer_bytes) : nullptr;
     x->layers[l].vc_lo = pair ? cv.take<char>(x->kv_layer_bytes) : nullptr;
   }
@@ -141,6 +147,7 @@ static size_t carve(const pd_config *g, char *base, pd_ctx *c) {
   st.gen_sub = cv.take<uint16_t>((size_t)B * x->gen_stride);
   st.step_tok = cv.take<int32_t>((size_t)B * S); st.force = cv.take<int32_t>((size_t)B * S);
   st.all_done = cv.take<int32_t>(1); st.row_of = cv.take<int32_t>((size_t)B * S);
+  x->kv_sat = cv.take<int32_t>(1);
   x->ctx_tok = cv.take<int32_t>((size_t)B * g->max_ctx);
   if (x->impl == 1) {
     // re-packed weights: same element counts as the originals, rows padded to 16
@@ -277,6 +284,26 @@ extern "C" int pd_profile_read(pd_ctx *c, double *attn_avg_us, int32_t *attn_lau
   *attn_launches = (int32_t)pairs;
   c->ev_used = 0;
   return PD_OK;
+}
+
+extern "C" int pd_get_info(pd_ctx *c, int key, void *hip_stream, int64_t *value) {
+  PD_REQUIRE(c && value, PD_EINVAL, "NULL argument");
+  switch (key) {
+    case PD_INFO_KERNEL_PATH: *value = c->impl; return PD_OK;
+    case PD_INFO_KV_PAIR_LAYERS: *value = c->pair_layers; return PD_OK;
+    case PD_INFO_KV_SATURATED: {
+      hipStream_t s = (hipStream_t)hip_stream;
+      PD_CHECK_HIP(hipStreamSynchronize(s));        // the staging buffer may be in flight
+      int32_t *h = c->h_pinned;
+      PD_CHECK_HIP(hipMemcpyAsync(h, c->kv_sat, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+      PD_CHECK_HIP(hipStreamSynchronize(s));
+      *value = *h;
+      return PD_OK;
+    }
+    default:
+      pd_set_error("unknown info key %d", key);
+      return PD_EINVAL;
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -541,101 +568,3 @@ extern "C" int pd_measure_read_bandwidth(const void *dev_buf, size_t buf_bytes, 
   *gb_per_s = (double)chunk_bytes * iters / (ms * 1e-3) * 1e-9;
   return PD_OK;
 }
-
-// ---------------------------------------------------------------------------
-// repeated read of per-block slices: what the caches deliver when a kernel's working set fits them
-// ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_slice_read(const uint4 *p, int slice_u4, int passes, unsigned *sink) {
-  const uint4 *base = p + (size_t)blockIdx.x * slice_u4;
-  unsigned acc = 0;
-  for (int r = 0; r < passes; ++r) {
-    for (int o = threadIdx.x; o + 7 * 256 < slice_u4; o += 8 * 256) {
-      uint4 v[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = base[o + u * 256];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
-    }
-  }
-  if (acc == 0x9e3779b9u) *sink = acc;       // keeps the loads alive; practically never taken
-}
-
-extern "C" int pd_measure_cached_read_bandwidth(const void *dev_buf, size_t buf_bytes, int blocks,
-                                                size_t slice_bytes, int passes, void *hip_stream,
-                                                double *gb_per_s) {
-  PD_REQUIRE(dev_buf && gb_per_s && blocks >= 1 && passes >= 1, PD_EINVAL, "NULL buffer / result, blocks or passes < 1");
-  PD_REQUIRE(slice_bytes >= 32768 && slice_bytes % 32768 == 0, PD_EINVAL, "slice_bytes must be a multiple of 32768");
-  PD_REQUIRE((size_t)blocks * slice_bytes + 256 <= buf_bytes, PD_EINVAL, "blocks * slice_bytes (+256) exceed the buffer");
-  PD_REQUIRE(((uintptr_t)dev_buf & 15) == 0, PD_EINVAL, "buffer must be 16-byte aligned");
-  hipStream_t s = (hipStream_t)hip_stream;
-  hipEvent_t e0, e1;
-  PD_CHECK_HIP(hipEventCreate(&e0));
-  PD_CHECK_HIP(hipEventCreate(&e1));
-  unsigned *sink = (unsigned *)((char *)dev_buf + (buf_bytes - 256) / 16 * 16);
-  int slice_u4 = (int)(slice_bytes / 16);
-  hipLaunchKernelGGL(k_slice_read, dim3(blocks), dim3(256), 0, s, (const uint4 *)dev_buf, slice_u4, 2, sink);
-  PD_CHECK_HIP(hipEventRecord(e0, s));
-  hipLaunchKernelGGL(k_slice_read, dim3(blocks), dim3(256), 0, s, (const uint4 *)dev_buf, slice_u4, passes, sink);
-  PD_CHECK_HIP(hipEventRecord(e1, s));
-  PD_CHECK_HIP(hipEventSynchronize(e1));
-  float ms = 0.f;
-  PD_CHECK_HIP(hipEventElapsedTime(&ms, e0, e1));
-  (void)hipEventDestroy(e0);
-  (void)hipEventDestroy(e1);
-  PD_CHECK_HIP(hipGetLastError());
-  *gb_per_s = (double)blocks * slice_bytes * passes / (ms * 1e-3) * 1e-9;
-  return PD_OK;
-}
-
-// ---------------------------------------------------------------------------
-// issue rate of the 16x16x32 bf16 matrix-core instruction with 1, 2, ... waves per SIMD
-// ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_mfma_rate(float *out, int iters) {
-  typedef float f4 __attribute__((ext_vector_type(4)));
-  typedef __bf16 b8 __attribute__((ext_vector_type(8)));
-  f4 acc[16];
-#pragma unroll
-  for (int i = 0; i < 16; ++i) acc[i] = f4{0.f, 0.f, 0.f, 0.f};
-  union { uint4 u; b8 v; } a, b;
-  a.u = make_uint4(threadIdx.x, 1, 2, 3);
-  b.u = make_uint4(4, 5, threadIdx.x, 7);
-  for (int it = 0; it < iters; ++it) {
-#pragma unroll
-    for (int i = 0; i < 16; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, acc[i], 0, 0, 0);
-  }
-  float sum = 0.f;
-#pragma unroll
-  for (int i = 0; i < 16; ++i) sum += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
-  out[(size_t)blockIdx.x * 256 + threadIdx.x] = sum;
-}
-
-extern "C" int pd_measure_mfma_issue(void *dev_scratch, size_t scratch_bytes, int waves_per_simd, int iters,
-                                     void *hip_stream, double *ns_per_instruction) {
-  PD_REQUIRE(dev_scratch && ns_per_instruction && iters >= 1, PD_EINVAL, "NULL scratch / result or iters < 1");
-  PD_REQUIRE(waves_per_simd >= 1 && waves_per_simd <= 8, PD_EINVAL, "waves_per_simd must be in [1, 8]");
-  hipDeviceProp_t prop;
-  int dev = 0;
-  PD_CHECK_HIP(hipGetDevice(&dev));
-  PD_CHECK_HIP(hipGetDeviceProperties(&prop, dev));
-  int blocks = prop.multiProcessorCount * waves_per_simd;      // 4 waves per block, one per SIMD
-  PD_REQUIRE((size_t)blocks * 256 * sizeof(float) <= scratch_bytes, PD_EINVAL,
-             "scratch too small: %zu bytes needed", (size_t)blocks * 256 * sizeof(float));
-  hipStream_t s = (hipStream_t)hip_stream;
-  hipEvent_t e0, e1;
-  PD_CHECK_HIP(hipEventCreate(&e0));
-  PD_CHECK_HIP(hipEventCreate(&e1));
-  hipLaunchKernelGGL(k_mfma_rate, dim3(blocks), dim3(256), 0, s, (float *)dev_scratch, 16);
-  PD_CHECK_HIP(hipEventRecord(e0, s));
-  hipLaunchKernelGGL(k_mfma_rate, dim3(blocks), dim3(256), 0, s, (float *)dev_scratch, iters);
-  PD_CHECK_HIP(hipEventRecord(e1, s));
-  PD_CHECK_HIP(hipEventSynchronize(e1));
-  float ms = 0.f;
-  PD_CHECK_HIP(hipEventElapsedTime(&ms, e0, e1));
-  (void)hipEventDestroy(e0);
-  (void)hipEventDestroy(e1);
-  PD_CHECK_HIP(hipGetLastError());
-  // instructions one SIMD executed: 16 per iteration and wave
-  *ns_per_instruction = (double)ms * 1e6 / ((double)iters * 16 * waves_per_simd);
-  return PD_OK;
-}
-

@@ -115,6 +115,8 @@ struct pd_ctx {
   const float *fng, *fnb;
   std::vector<LayerPtrs> layers;
   int impl;                 // 0: fp32-activation kernels; 1: bf16 MFMA kernels
+  int pair_layers;          // leading layers whose cache holds pairs of halves (kv_pair_layers resolved)
+  int32_t *kv_sat;          // [1] keys / values stored saturated at the largest half since pd_create
   // capacities
   int gen_cap, gen_stride, kv_cap, R_cap, R_pad, vocab_pad, prefill_chunk, prefill_chunk_cap;
   size_t kv_layer_bytes;    // bytes of one K (or V) cache of one layer

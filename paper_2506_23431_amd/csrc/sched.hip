@@ -31,7 +31,8 @@ int launch_reset_state(pd_ctx *c, hipStream_t s) {
 
 // ---------------------------------------------------------------------------
 // tick: Algorithm 1 lines 5-7 plus the row list of this time-step.
-// One block per request; the work is a few dozen integers, done by one thread.
+// One wave per request: lane i looks after subsequences i, i + 64, ...; rows are numbered in
+// subsequence order with a ballot and a population count.
 // A subsequence has a row when it holds a token that was not fed yet: its newest
 // token (coordinate tau = t).  A subsequence that finished in the previous step is
 // fed once more so that its last token enters the KV cache; that row selects no token.

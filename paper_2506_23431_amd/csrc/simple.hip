@@ -110,7 +110,7 @@ static int linear(pd_ctx *c, float *out, const float *x, const void *W, const vo
 // ---------------------------------------------------------------------------
 template <typename KT>
 __global__ void k_qkv_post(float *qkv, KT *kc, KT *vc, KT *kc_lo, KT *vc_lo, RowTables rt,
-                           const float *rope_cs, int d, int H, int hd, int kv_cap) {
+                           const float *rope_cs, int d, int H, int hd, int kv_cap, int32_t *kv_sat) {
   int r = blockIdx.x;
   if (!(rt.flags[r] & ROW_VALID)) return;
   float *row = qkv + (size_t)r * 3 * d;
@@ -131,6 +131,10 @@ __global__ void k_qkv_post(float *qkv, KT *kc, KT *vc, KT *kc_lo, KT *vc_lo, Row
     }
     size_t o = base + (size_t)h * kv_cap * hd;
     float v1 = row[2 * d + h * hd + j], v2 = row[2 * d + h * hd + j + half];
+    if (sizeof(KT) == 2) {   // half cache: count what is stored saturated
+      int n_sat = (fabsf(k1) > 65504.f) + (fabsf(k2) > 65504.f) + (fabsf(v1) > 65504.f) + (fabsf(v2) > 65504.f);
+      if (n_sat) atomicAdd(kv_sat, n_sat);
+    }
     st_f32(kc, o + j, k1); st_f32(kc, o + j + half, k2);
     st_f32(vc, o + j, v1); st_f32(vc, o + j + half, v2);
     if (kc_lo) {      // low halves: what the rounding of the stores above left out
@@ -264,7 +268,7 @@ int simple_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_over
   if (g.dtype == 0) {
     hipLaunchKernelGGL(k_qkv_post<float>, dim3(R), dim3(256), 0, s, c->qkv32, (float *)lw.kc,
                        (float *)lw.vc, (float *)nullptr, (float *)nullptr, c->rows, cs, d, H, hd,
-                       c->kv_cap);
+                       c->kv_cap, c->kv_sat);
     if (!kv_only) hipLaunchKernelGGL(k_attn<float>, dim3(R, H), dim3(256), shm, s, att, c->qkv32,
                        (const float *)lw.kc, (const float *)lw.vc, (const float *)nullptr,
                        (const float *)nullptr, c->scores, c->rows,
@@ -273,7 +277,7 @@ int simple_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_over
   } else {
     hipLaunchKernelGGL(k_qkv_post<f16_t>, dim3(R), dim3(256), 0, s, c->qkv32, (f16_t *)lw.kc,
                        (f16_t *)lw.vc, (f16_t *)lw.kc_lo, (f16_t *)lw.vc_lo, c->rows, cs, d, H, hd,
-                       c->kv_cap);
+                       c->kv_cap, c->kv_sat);
     if (!kv_only) hipLaunchKernelGGL(k_attn<f16_t>, dim3(R, H), dim3(256), shm, s, att, c->qkv32,
                        (const f16_t *)lw.kc, (const f16_t *)lw.vc, (const f16_t *)lw.kc_lo,
                        (const f16_t *)lw.vc_lo, c->scores, c->rows,

@@ -196,13 +196,13 @@ def main(argv=None):
     ap.add_argument("--tokens", type=int, default=0, help="total generated tokens N (default: S*M of the workload)")
     ap.add_argument("--layers", type=int, default=0, help="use only this many layers (quick runs)")
     ap.add_argument("--kv-pair-layers", type=int, default=None,
-                    help="leading layers whose cache keeps keys and values as pairs of halves (default: 1 for cfg5, else 0)")
+                    help="leading layers whose cache keeps keys and values as pairs of halves (default: -1, the library chooses from the shape)")
     ap.add_argument("--ragged", default="", choices=[""] + sorted(RAGGED),
                     help="uneven targets drawn around this dataset's averages (Table 1), <eos>-terminated")
     ap.add_argument("--targets", type=int, default=8, help="ragged mode: seeded targets per request slot")
     args = ap.parse_args(argv)
     if args.kv_pair_layers is None:
-        args.kv_pair_layers = 1 if args.workload.startswith("cfg5") else 0
+        args.kv_pair_layers = -1
     if args.ragged:
         return main_ragged(args)
 

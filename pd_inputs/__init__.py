@@ -8,9 +8,10 @@ oracle and the HIP path are both fed from here and share nothing else.
 
 from .configs import WorkloadConfig, CONFIGS, get_config, max_positions
 from .generate import (make_weights, make_context, make_forced_tokens, bf16_round, bf16_bits,
-                       bits_to_f32)
+                       bits_to_f32, tie_lm_head)
 
 __all__ = [
     "WorkloadConfig", "CONFIGS", "get_config", "max_positions",
     "make_weights", "make_context", "make_forced_tokens", "bf16_round", "bf16_bits", "bits_to_f32",
+    "tie_lm_head",
 ]

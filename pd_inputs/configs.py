@@ -43,6 +43,9 @@ class WorkloadConfig:
     # standard deviation of the QKV projection (0.02 everywhere in the named workloads; test
     # cases raise it to make the attention distribution peaky, so that mask errors show)
     qkv_std: float = 0.02
+    # standard deviation of the vocabulary projection (0.02 in the named workloads; test cases raise
+    # it so that the top-2 logit margins of a whole free-running generation stay clear of rounding)
+    lm_std: float = 0.02
 
     @property
     def time_steps(self) -> int:

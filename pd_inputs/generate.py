@@ -103,7 +103,7 @@ def make_weights(cfg: WorkloadConfig, threads: int | None = None) -> dict:
         t_pos = next(tid)
         if cfg.pos_kind == POS_LEARNED:
             w["pos_emb"] = _normal((max_positions(cfg), d), cfg.seed, t_pos, as_bf16, pool)
-        w["lm_head"] = mat(V, d)
+        w["lm_head"] = _normal((V, d), cfg.seed, next(tid), as_bf16, pool, std=cfg.lm_std)
         w["final_norm_g"] = gain()
         w["final_norm_b"] = bias()
         layers = []
@@ -132,3 +132,21 @@ def make_forced_tokens(cfg: WorkloadConfig, steps: int, salt: int = 1) -> np.nda
     stand-in for "the tokens that were generated", for teacher-forced runs."""
     g = np.random.Generator(np.random.Philox(key=[(cfg.seed << 32) | 0xF0CE, salt]))
     return g.integers(0, cfg.vocab, size=(steps, cfg.batch, cfg.n_sub), dtype=np.int32)
+
+
+def tie_lm_head(cfg: WorkloadConfig, weights: dict, group_a, group_b, scale: float = 100.0) -> None:
+    """Overwrites rows of the vocabulary projection in place so that logits tie exactly: every row
+    listed in group_a becomes one seeded vector v (N(0, scale * 0.02)), every row in group_b becomes
+    -v.  Whatever the hidden state, one of the two groups then holds the largest logit several
+    times over (an input for the tests of the lowest-index rule of Eq. 4)."""
+    g = np.random.Generator(np.random.Philox(key=[(cfg.seed << 32) | 0x71E5, 0]))
+    v = (g.standard_normal(cfg.d_model, dtype=np.float32) * np.float32(scale * _STD))
+    head = weights["lm_head"]
+    if head.dtype == np.uint16:
+        pos, neg = bf16_bits(v), bf16_bits(-v)
+    else:
+        pos, neg = v, -v
+    for j in group_a:
+        head[j] = pos
+    for j in group_b:
+        head[j] = neg

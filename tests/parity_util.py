@@ -50,13 +50,10 @@ def oracle_run(cfg, weights, ctx, force=None, steps=None, context_kv=None, log=N
 
 
 def make_decoder(cfg, weights, **kw):
-    """The library on this workload.  cfg5 and the cases derived from it run with layer 0's cache
-    as pairs of halves (kv_pair_layers = 1): with plain half caches its 32 layers of width 4096
-    carry that layer's rounding to the logits at 2e-2 - 3e-2."""
+    """The library on this workload, with the library's own choice of pair layers (from the shape)."""
     from paper_2506_23431_amd import PipelinedDecoder
     args = dict(max_batch=cfg.batch, max_ctx=cfg.ctx_len, max_sub=cfg.n_sub,
-                max_sub_tokens=cfg.sub_tokens, max_pos=max_positions(cfg),
-                kv_pair_layers=1 if cfg.name.startswith("cfg5") else 0)
+                max_sub_tokens=cfg.sub_tokens, max_pos=max_positions(cfg))
     args.update(kw)
     return PipelinedDecoder(cfg, weights, **args)
 

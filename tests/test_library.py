@@ -71,11 +71,17 @@ def test_workspace_sizes(lib):
     # fp32 caches have no low halves
     cfg = pi.get_config("cfg1")
     assert lib.pd_workspace_bytes(C.byref(config_struct(cfg, kv_pair_layers=1))) == sizes["cfg1"]
+    # kv_pair_layers = -1: the library chooses from the shape alone (one pair layer from width 4096
+    # on, none below), whatever the workload is called
+    seven_b = pi.get_config("cfg5").scaled(name="some-7b-shaped-model")
+    assert lib.pd_workspace_bytes(C.byref(config_struct(seven_b, kv_pair_layers=-1))) == sizes["cfg5"] + one
+    for name in ("cfg2", "cfg3", "cfg4"):
+        assert lib.pd_workspace_bytes(C.byref(config_struct(pi.get_config(name), kv_pair_layers=-1))) == sizes[name]
 
 
 @pytest.mark.parametrize("bad", [dict(n_head=3), dict(head_dim=7, n_head=1, d_model=7), dict(dtype=2),
                                  dict(ffn_kind=5), dict(max_batch=0), dict(bos_id=-1), dict(norm_eps=0.0),
-                                 dict(eos_id=10 ** 6), dict(max_sub=70000, max_sub_tokens=1), dict(kv_pair_layers=-1), dict(kv_pair_layers=99)])
+                                 dict(eos_id=10 ** 6), dict(max_sub=70000, max_sub_tokens=1), dict(kv_pair_layers=-2), dict(kv_pair_layers=99)])
 def test_invalid_configurations_are_rejected(lib, bad):
     cfg = pi.get_config("cfg1")
     assert lib.pd_workspace_bytes(C.byref(config_struct(cfg, **bad))) == 0

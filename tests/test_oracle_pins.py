@@ -47,6 +47,54 @@ def run(cfg, model, ctx, **kw):
 
 
 # --------------------------------------------------------------------------
+# Eq. 4 with ties: the most probable token, the lowest index among equals
+# --------------------------------------------------------------------------
+
+def _argmax_by_hand(v):
+    best, bi = None, -1
+    for j, x in enumerate(v):            # ascending scan, strict comparison: the first maximum stays
+        if best is None or x > best:
+            best, bi = x, j
+    return bi
+
+
+def test_argmax_takes_the_lowest_index_among_equal_maxima():
+    from oracle import primitives as P
+    rng = np.random.default_rng(5)
+    for n in (1, 2, 17, 300, 2100):
+        for _ in range(20):
+            v = rng.standard_normal(n)
+            k = int(rng.integers(1, min(n, 6) + 1))
+            where = rng.choice(n, size=k, replace=False)
+            v[where] = v.max() + 1.0                      # k exact copies of the maximum
+            assert P.argmax_lowest(v) == int(where.min()) == _argmax_by_hand(v)
+    assert P.argmax_lowest(np.zeros(9)) == 0              # everything ties
+    assert P.argmax_lowest(np.array([-np.inf, 3.0, 3.0, -np.inf])) == 1
+
+
+def test_tied_logits_select_the_lowest_index_through_a_whole_run():
+    """A vocabulary projection with duplicated rows: in every row of every iteration one of two
+    groups of identical rows holds the largest logit several times over; the free-running oracle
+    must append the lowest index of that group each time."""
+    cfg = tiny(seed=16, d_model=128, n_head=2, head_dim=64, d_ff=96, vocab=2100, n_sub=3, delta_t=1, sub_tokens=4)
+    w = pi.make_weights(cfg, threads=2)
+    group_a, group_b = [37, 38, 45, 1061, 2085], [41, 600, 601, 1500]
+    pi.tie_lm_head(cfg, w, group_a, group_b)
+    out = run(cfg, OracleModel(cfg, w), pi.make_context(cfg)[0])
+    seen = set()
+    for rec, em in zip(out["trace"], out["emitted"]):
+        for r, i in enumerate(rec["rows"]):
+            lg = rec["logits"][r]
+            tied = np.flatnonzero(lg == lg.max())
+            assert tied.tolist() in (group_a, group_b), "the maximum is not one whole group of duplicates"
+            assert np.sort(lg)[-len(tied) - 1] < lg.max() - 0.05
+            if i in em:
+                assert em[i] == tied.min() == _argmax_by_hand(lg)
+                seen.add(int(em[i]))
+    assert seen == {37, 41}, "the run should meet both groups"
+
+
+# --------------------------------------------------------------------------
 # Fig. 2 / Section 3.1: the worked example, with a scripted decoder
 # --------------------------------------------------------------------------
 
@@ -426,6 +474,12 @@ def test_planted_mistakes_are_caught(monkeypatch):
     orig_rope = om.P.rope
     monkeypatch.setattr(om.P, "rope", lambda x, pos, base: orig_rope(x, pos, base * 2))
     _expect_failure(test_single_subsequence_is_ordinary_greedy_decoding, "llama")
+    monkeypatch.undo()
+    # (g) the argmax keeps the last of several equal maxima instead of the first
+    from oracle import primitives as prim
+    monkeypatch.setattr(prim, "argmax_lowest", lambda v: int(len(v) - 1 - np.argmax(np.asarray(v)[::-1])))
+    _expect_failure(test_argmax_takes_the_lowest_index_among_equal_maxima)
+    _expect_failure(test_tied_logits_select_the_lowest_index_through_a_whole_run)
     monkeypatch.undo()
     # (f) controller opens subsequences one iteration late
     orig = controller.pipelined_decode
