@@ -10,10 +10,14 @@ and the schedule advances.  The workload is synthetic (seeded weights N(0, 0.02)
 uniform context ids), already resident in HBM when the timed region starts; the
 context pass (prefill) is outside the metric and reported separately.
 
-Prints ONE JSON line: generated tokens/s over exactly K steps, plus
-  roofline      achieved HBM GB/s of the attention kernel (algorithmic bytes per launch /
-                average launch duration from HIP events attached to its dispatches) vs 8 TB/s,
-                beside what a kernel that only reads the same bytes reaches
+Prints ONE JSON line: generated tokens/s over exactly K steps (median of several repeats).  With
+K below the length of the run, the K steps are a window centred in the run, reached by an untimed
+fast-forward from t = 1; the line then also carries `full_run`, the whole run from t = 1 (B*S*M
+tokens over its T steps).  Further objects:
+  roofline      achieved HBM GB/s of the attention kernel (algorithmic bytes per launch over the
+                window / average launch duration from HIP events attached to its dispatches) vs
+                8 TB/s, the same with the kernel that merges its partials, the whole step against
+                its algorithmic bytes, and what a kernel that only reads the same bytes reaches
   cpu_baseline  the CPU oracle timed on the host cores on a bounded sample
 """
 
@@ -41,18 +45,42 @@ def fed(cfg, t):
     return sum(1 for i in range(cfg.n_sub) if i * cfg.delta_t < t <= i * cfg.delta_t + cfg.sub_tokens + 1)
 
 
-def attention_bytes(cfg, steps):
-    """Algorithmic HBM bytes of one attention launch, averaged over iterations 1..steps:
-    every visible key and value once (bf16), shared by the rows of a request, plus Q in and O out."""
+def attention_bytes(cfg, t0, t1):
+    """Algorithmic HBM bytes of one attention launch, averaged over iterations t0..t1 (1-based,
+    inclusive): every visible key and value once (16 bit), shared by the rows of a request, plus Q in
+    and O out."""
     H, hd, B = cfg.n_head, cfg.head_dim, cfg.batch
     total, n_gen = 0.0, 0
-    for t in range(1, steps + 1):
+    for t in range(1, t1 + 1):
         rows = fed(cfg, t)
         n_gen += rows
+        if t < t0:
+            continue
         kv = B * H * (cfg.ctx_len + n_gen) * hd * 2 * 2
-        qo = B * rows * cfg.d_model * 2 * 2 * 2      # q and o, each as a bf16 pair
+        qo = B * rows * cfg.d_model * 2 * 2 * 2      # q and o, each as a 16-bit pair
         total += kv + qo
-    return total / steps
+    return total / (t1 - t0 + 1)
+
+
+def step_bytes(cfg, t0, t1, pair_layers):
+    """Algorithmic HBM bytes of one whole time-step, averaged over iterations t0..t1: every weight
+    once (shared by all rows and requests), every request's visible keys and values once per layer."""
+    d, ff, V, nl = cfg.d_model, cfg.d_ff, cfg.vocab, cfg.n_layer
+    c = 3 if cfg.ffn_kind == 1 else 2
+    weights = 2.0 * (nl * (4 * d * d + c * d * ff) + V * d)
+    attn = attention_bytes(cfg, t0, t1) * (nl + pair_layers)
+    return weights + attn
+
+
+def window(cfg, K):
+    """Iterations t0..t1 that a run of K < T steps times: K consecutive iterations centred in the run,
+    where the schedule is in its steady state (every slot of the pipeline holds a subsequence) and the
+    generated-side cache is about as long as on average over the run."""
+    T = cfg.time_steps
+    if K >= T:
+        return 1, T
+    t0 = (T - K) // 2 + 1
+    return t0, t0 + K - 1
 
 
 def cpu_baseline(cfg, weights, ctx, budget_s=20.0):
@@ -97,41 +125,46 @@ def cpu_baseline(cfg, weights, ctx, budget_s=20.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=None, help="decode iterations to time (default: the full run)")
+    ap.add_argument("--steps", type=int, default=None,
+                    help="decode iterations to time (default: the full run; fewer: a window centred in the run, "
+                         "reached by an untimed fast-forward)")
     ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--repeats", type=int, default=5, help="timed repeats of the window (the median is reported)")
     ap.add_argument("--workload", default="cfg4")
     ap.add_argument("--graph", type=int, default=0, help="replay each step from a captured HIP graph")
     ap.add_argument("--attn-splits", type=int, default=0)
-    ap.add_argument("--kv-pair-layers", type=int, default=None,
-                    help="leading layers whose cache keeps keys and values as pairs of halves (cfg5 needs 1 "
-                         "to stay inside the logit tolerance and gets it by default; cfg1-cfg4 do not)")
+    ap.add_argument("--kv-pair-layers", type=int, default=-1,
+                    help="leading layers whose cache keeps keys and values as pairs of halves (-1: the library "
+                         "chooses from the shape)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sync-every", type=int, default=0,
-                    help="synchronise after every N iterations of the timed pass (0: never; a counter-collecting "
-                         "profiler cannot queue tens of thousands of launches)")
+                    help="synchronise after every N iterations of the timed pass (0: never; for runs under a "
+                         "counter-collecting profiler)")
     ap.add_argument("--no-event-passes", action="store_true",
-                    help="skip the passes that time the attention kernel with HIP events and the plain-read "
-                         "measurement (for runs under a counter-collecting profiler)")
+                    help="skip the passes that time the attention kernel with HIP events, the full-run pass and the "
+                         "plain-read measurement (for runs under a profiler)")
     ap.add_argument("--calibrate-copy-mb", type=int, default=0,
                     help="also run plain device-to-device copies of this many MiB (a kernel of known "
                          "traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
-    if args.kv_pair_layers is None:
-        args.kv_pair_layers = 1 if args.workload.startswith("cfg5") else 0
     if args.gpus != 1:
         print(f"bench.py: this build runs on one GPU only (got --gpus {args.gpus}): no collectives, no "
               "sharding; requests, context keys and heads are the axes it would shard along", file=sys.stderr)
         sys.exit(2)
 
+    import statistics
     import torch
     import pd_inputs as pi
     from pd_inputs import max_positions
     from paper_2506_23431_amd import PipelinedDecoder, binding
 
     cfg = pi.get_config(args.workload)
-    K = args.steps if args.steps is not None else cfg.time_steps
-    K = max(1, min(K, cfg.time_steps))
-    W = max(0, min(args.warmup, cfg.time_steps))
+    T = cfg.time_steps
+    K = args.steps if args.steps is not None else T
+    K = max(1, min(K, T))
+    W = max(0, min(args.warmup, T))
+    reps = max(1, args.repeats)
+    t0w, t1w = window(cfg, K)
     weights = pi.make_weights(cfg)
     ctx = pi.make_context(cfg)
     stream = torch.cuda.Stream()
@@ -139,6 +172,7 @@ def main():
         dec = PipelinedDecoder(cfg, weights, max_batch=cfg.batch, max_ctx=cfg.ctx_len, max_sub=cfg.n_sub,
                                max_sub_tokens=cfg.sub_tokens, max_pos=max_positions(cfg),
                                kv_pair_layers=args.kv_pair_layers)
+        pair_layers = dec.get_info(binding.PD_INFO_KV_PAIR_LAYERS)
         dec.set_option(binding.PD_OPT_USE_GRAPH, args.graph)
         dec.set_option(binding.PD_OPT_ATTN_SPLITS, args.attn_splits)
         if args.calibrate_copy_mb > 0:
@@ -149,82 +183,128 @@ def main():
             del src, dst
         torch.cuda.synchronize()
         t0 = time.time()
-        dec.prefill_context(ctx, cfg.n_sub, cfg.delta_t, cfg.sub_tokens, cfg.time_steps)
+        dec.prefill_context(ctx, cfg.n_sub, cfg.delta_t, cfg.sub_tokens, T)
         torch.cuda.synchronize()
         prefill_s = time.time() - t0
-        # warm-up: W untimed iterations, then back to t = 0
+        # warm-up: W untimed iterations
         dec.decode_steps(W)
-        dec.reset_decode()
         torch.cuda.synchronize()
-        # timed region: exactly K iterations
-        t0 = time.perf_counter()
-        if args.sync_every > 0:
-            for k0 in range(0, K, args.sync_every):
-                dec.decode_steps(min(args.sync_every, K - k0))
-                torch.cuda.synchronize()
-        else:
-            dec.decode_steps(K)
-        torch.cuda.synchronize()
-        elapsed = time.perf_counter() - t0
-        attn_us, attn_launches, pair_us, read_gbs = 0.0, 0, 0.0, 0.0
+
+        def timed_window():
+            """Back to t = 0, untimed fast-forward to the window, then exactly K timed iterations."""
+            dec.reset_decode()
+            dec.decode_steps(t0w - 1)
+            torch.cuda.synchronize()
+            t_start = time.perf_counter()
+            if args.sync_every > 0:
+                for k0 in range(0, K, args.sync_every):
+                    dec.decode_steps(min(args.sync_every, K - k0))
+                    torch.cuda.synchronize()
+            else:
+                dec.decode_steps(K)
+            torch.cuda.synchronize()
+            return time.perf_counter() - t_start
+
+        times = [timed_window() for _ in range(reps)]
+        elapsed = statistics.median(times)
+        attn_us, attn_launches, pair_us, read_gbs, full = 0.0, 0, 0.0, 0.0, None
         if not args.no_event_passes:
-            # second pass over the same K iterations with HIP events around every launch of the attention
-            # kernel (the one that streams the keys and values); third pass: around the kernel and the
-            # small kernel that merges its partial results
+            # the whole run, all T iterations from t = 1 (the metric as defined: B*S*M tokens over the T steps)
+            full_times = []
+            for _ in range(3 if K < T else 0):
+                dec.reset_decode()
+                torch.cuda.synchronize()
+                t_start = time.perf_counter()
+                dec.decode_steps(T)
+                torch.cuda.synchronize()
+                full_times.append(time.perf_counter() - t_start)
+            if K >= T:
+                full_times = times
+            ft = statistics.median(full_times)
+            full_tokens = cfg.batch * cfg.n_sub * cfg.sub_tokens
+            full = {"steps": T, "tokens": full_tokens, "ms_per_step": ft / T * 1e3,
+                    "tokens_per_s": full_tokens / ft, "repeats": len(full_times),
+                    "hbm_frac_step": step_bytes(cfg, 1, T, pair_layers) / (ft / T) / 1e9 / HBM_PEAK_GBS}
+            # the same window again with HIP events attached to every launch of the attention kernel (the
+            # one that streams the keys and values); then with events around that kernel and the small
+            # kernel that merges its partial results
             dec.set_option(binding.PD_OPT_USE_GRAPH, 0)
-            dec.set_option(binding.PD_OPT_PROFILE, 1)
-            dec.reset_decode()
-            dec.decode_steps(K)
-            torch.cuda.synchronize()
-            attn_us, attn_launches = dec.profile_read()
-            dec.set_option(binding.PD_OPT_PROFILE, 2)
-            dec.reset_decode()
-            dec.decode_steps(K)
-            torch.cuda.synchronize()
-            pair_us, _ = dec.profile_read()
-            dec.set_option(binding.PD_OPT_PROFILE, 0)
+            for mode in (1, 2):
+                dec.reset_decode()
+                dec.decode_steps(t0w - 1)
+                torch.cuda.synchronize()
+                dec.set_option(binding.PD_OPT_PROFILE, mode)
+                dec.decode_steps(K)
+                torch.cuda.synchronize()
+                us, n = dec.profile_read()
+                dec.set_option(binding.PD_OPT_PROFILE, 0)
+                if mode == 1:
+                    attn_us, attn_launches = us, n
+                else:
+                    pair_us = us
             # what a kernel that only reads reaches on this device, at the size of one attention launch
             buf = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
             buf.fill_(1)
             torch.cuda.synchronize()
-            chunk = int(attention_bytes(cfg, K)) // 4096 * 4096
+            chunk = int(attention_bytes(cfg, t0w, t1w)) // 4096 * 4096
             read_gbs = binding.measure_read_bandwidth(buf.data_ptr(), buf.numel(), chunk, 200,
                                                       torch.cuda.current_stream().cuda_stream)
             del buf
-
         dec.close()
 
-    tokens = cfg.batch * sum(producing(cfg, t) for t in range(1, K + 1))
+    tokens = cfg.batch * sum(producing(cfg, t) for t in range(t0w, t1w + 1))
     # a pair layer reads every key and value twice (high and low halves)
-    abytes = attention_bytes(cfg, K) * (1.0 + args.kv_pair_layers / cfg.n_layer)
+    abytes = attention_bytes(cfg, t0w, t1w) * (1.0 + pair_layers / cfg.n_layer)
     achieved = abytes / (attn_us * 1e-6) / 1e9 if attn_us > 0 else 0.0
-    # HBM bytes per launch from the rocprofv3 counter runs summarised under profiles/ (null if none)
-    traffic = None
+    # HBM bytes per launch from the rocprofv3 counter runs summarised under profiles/: the figure
+    # measured for exactly this window when there is one, else the measured ratio of counter bytes to
+    # algorithmic bytes (over the full run) times this window's algorithmic bytes; null if neither
+    traffic, traffic_src = None, None
     pmc = os.path.join(ROOT, "profiles", f"attention_{cfg.name}_hbm_traffic.md")
     if os.path.exists(pmc):
-        m = re.search(r"bytes_per_launch\s*=\s*(\d+)", open(pmc).read())
-        traffic = float(m.group(1)) if m else None
+        text = open(pmc).read()
+        m = re.search(rf"bytes_per_launch\[t{t0w}-{t1w}\]\s*=\s*(\d+)", text)
+        r = re.search(r"traffic_over_algorithmic\s*=\s*([0-9.]+)", text)
+        if m:
+            traffic, traffic_src = float(m.group(1)), "rocprofv3 FETCH_SIZE + WRITE_SIZE over this window"
+        elif r:
+            traffic = float(r.group(1)) * abytes
+            traffic_src = "rocprofv3 FETCH_SIZE + WRITE_SIZE ratio to algorithmic bytes over the full run, scaled to this window"
+    sbytes = step_bytes(cfg, t0w, t1w, pair_layers)
     out = {
         "metric": "pipelined_decode_generated_tokens_per_s", "value": tokens / elapsed, "unit": "tokens/s",
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": elapsed / K * 1e3,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
-        "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == 1 else "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {cfg.n_layer} layers, d_model {cfg.d_model}, "
                                f"{cfg.n_head}x{cfg.head_dim} heads, FFN {cfg.d_ff}, vocab {cfg.vocab}, "
                                f"batch {cfg.batch}, context {cfg.ctx_len}, S={cfg.n_sub}, dt={cfg.delta_t}, "
                                f"M={cfg.sub_tokens}",
-                   "tokens_generated": tokens, "time_steps_full_run": cfg.time_steps,
+                   "window": {"first_iteration": t0w, "last_iteration": t1w,
+                              "rows_per_request": [fed(cfg, t0w), fed(cfg, t1w)],
+                              "reached_by": "untimed decode iterations from t = 1" if t0w > 1 else "start of the run"},
+                   "repeats": reps, "repeat_ms_per_step": [x / K * 1e3 for x in times], "statistic": "median",
+                   "tokens_generated": tokens, "time_steps_full_run": T,
                    "prefill_s": prefill_s, "hip_graph": bool(args.graph),
-                   "kv_pair_layers": args.kv_pair_layers},
+                   "kv_pair_layers": pair_layers},
+        "full_run": full,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_src,
                      "kernel": "k_attn_mfma (masked multi-query attention over the KV cache, one launch "
                                "per layer per step)",
                      "algorithmic_bytes_per_launch": abytes, "avg_launch_us": attn_us,
                      "launches": attn_launches,
                      "timing": "HIP start and stop events attached to every dispatch of the kernel on the "
-                               "launch stream, in a second pass over the same K iterations",
-                     "with_merge_kernel_us": pair_us,
+                               "launch stream, in a further pass over the same window",
+                     "with_merge_kernel": {"avg_us": pair_us,
+                                           "frac": abytes / (pair_us * 1e-6) / 1e9 / HBM_PEAK_GBS if pair_us > 0 else 0.0,
+                                           "note": "attention kernel plus the kernel that merges its split "
+                                                   "partials, events around the pair; same algorithmic bytes"},
+                     "step": {"algorithmic_bytes": sbytes, "ms": elapsed / K * 1e3,
+                              "achieved": sbytes / (elapsed / K) / 1e9,
+                              "frac": sbytes / (elapsed / K) / 1e9 / HBM_PEAK_GBS,
+                              "note": "all kernels of one time-step: every weight once, every request's keys "
+                                      "and values once per layer"},
                      "plain_read_same_bytes": {"GB/s": read_gbs, "frac_of_peak": read_gbs / HBM_PEAK_GBS,
                                                "note": "a kernel that only reads this many bytes, launched "
                                                        "back to back on the same device"}},
