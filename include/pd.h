@@ -136,6 +136,21 @@ int pd_generate(pd_ctx *ctx, const int32_t *ctx_tokens, int B, int L, int n_sub,
                 int max_sub_tokens, int time_max, int32_t *out_tokens, int32_t *out_lens,
                 int32_t *out_steps, void *hip_stream);
 
+/* pd_generate for callers that cannot allocate device memory (code under HIP graph capture nearby,
+ * tight serving loops, harnesses that forbid hipMalloc): the workspace that pd_create takes from the
+ * caller is a device array inside the library (PD_STATIC_WORKSPACE_BYTES, held by every GPU the
+ * library runs on until the process ends), the context exists for this call only, and nothing that
+ * allocates device or pinned host memory is called.  `cfg` and `w` as for pd_create (cfg's
+ * capacities must cover B, L, n_sub and max_sub_tokens); the other arguments and the results are
+ * those of pd_generate, bit for bit.  Configurations whose pd_workspace_bytes exceeds the array
+ * return PD_ENOMEM.  Every call on a GPU uses that GPU's one array: the part a call needs is
+ * cleared and the weights are re-packed into it each time, and calls that overlap on one GPU (other
+ * threads, other streams) race.  Synchronises the stream before returning. */
+#define PD_STATIC_WORKSPACE_BYTES (64u << 20)
+int pd_generate_static(const pd_config *cfg, const pd_weights *w, const int32_t *ctx_tokens, int B,
+                       int L, int n_sub, int delta_t, int max_sub_tokens, int time_max,
+                       int32_t *out_tokens, int32_t *out_lens, int32_t *out_steps, void *hip_stream);
+
 /* Runs `n_steps` decode steps (no host inputs or outputs) back to back on the
  * stream; used for timing.  Does not synchronise. */
 int pd_decode_steps(pd_ctx *ctx, int n_steps, void *hip_stream);

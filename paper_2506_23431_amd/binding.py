@@ -16,7 +16,7 @@ PD_OPT_ATTN_SPLITS, PD_OPT_USE_GRAPH, PD_OPT_PROFILE, PD_OPT_SPLIT_ACT, PD_OPT_P
 PD_INFO_KERNEL_PATH, PD_INFO_KV_PAIR_LAYERS, PD_INFO_KV_SATURATED = 1, 2, 3
 
 EXPORTS = ["pd_workspace_bytes", "pd_create", "pd_destroy", "pd_prefill_context", "pd_decode_step",
-           "pd_generate", "pd_decode_steps", "pd_reset_decode", "pd_set_option", "pd_profile_read",
+           "pd_generate", "pd_generate_static", "pd_decode_steps", "pd_reset_decode", "pd_set_option", "pd_profile_read",
            "pd_measure_read_bandwidth", "pd_get_info", "pd_last_error"]
 
 
@@ -59,6 +59,8 @@ def load():
     lib.pd_prefill_context.argtypes = [vp, i32p] + [C.c_int] * 6 + [vp]
     lib.pd_decode_step.argtypes = [vp, i32p, i32p, vp, i32p, vp]
     lib.pd_generate.argtypes = [vp, i32p] + [C.c_int] * 6 + [i32p, i32p, i32p, vp]
+    lib.pd_generate_static.argtypes = [C.POINTER(PdConfig), C.POINTER(PdWeights), i32p] + [C.c_int] * 6 + \
+                                      [i32p, i32p, i32p, vp]
     lib.pd_decode_steps.argtypes = [vp, C.c_int, vp]
     lib.pd_reset_decode.argtypes = [vp, vp]
     lib.pd_set_option.argtypes = [vp, C.c_int, C.c_int]
@@ -82,6 +84,44 @@ def _i32(a):
     return a, a.ctypes.data_as(C.POINTER(C.c_int32))
 
 
+def _config(shape, max_batch, max_ctx, max_sub, max_sub_tokens, max_pos, kv_pair_layers):
+    return PdConfig(
+        n_layer=shape.n_layer, d_model=shape.d_model, n_head=shape.n_head, head_dim=shape.head_dim,
+        d_ff=shape.d_ff, vocab=shape.vocab, ffn_kind=shape.ffn_kind, norm_kind=shape.norm_kind,
+        pos_kind=shape.pos_kind, rope_base=shape.rope_base, norm_eps=shape.norm_eps,
+        dtype=shape.dtype, bos_id=shape.bos_id, eos_id=shape.eos_id, max_batch=max_batch,
+        max_ctx=max_ctx, max_sub=max_sub, max_sub_tokens=max_sub_tokens, max_pos=max_pos,
+        kv_pair_layers=kv_pair_layers)
+
+
+def _upload_weights(torch, device, shape, weights):
+    """Copies the weights to the device; returns (PdWeights, tensors to keep alive, pointer arrays)."""
+    keep, arrays = [], []
+
+    def dev(a):
+        if a is None:
+            return None
+        if a.dtype == np.uint16:
+            t = torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
+        else:
+            t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+        keep.append(t)
+        return t.data_ptr()
+
+    w = PdWeights()
+    for name in ("tok_emb", "pos_emb", "lm_head", "final_norm_g", "final_norm_b"):
+        setattr(w, name, dev(weights.get(name)))
+    for name in ("wqkv", "wo", "w1", "w_up", "w2", "norm1_g", "norm1_b", "norm2_g", "norm2_b"):
+        ptrs = [dev(lw.get(name)) for lw in weights["layers"]]
+        if all(p is None for p in ptrs):
+            setattr(w, name, None)
+            continue
+        arr = (C.c_void_p * shape.n_layer)(*ptrs)
+        arrays.append(arr)
+        setattr(w, name, C.cast(arr, C.POINTER(C.c_void_p)))
+    return w, keep, arrays
+
+
 class PipelinedDecoder:
     """Owns the device copies of the weights and the workspace of one pd_ctx.
 
@@ -99,39 +139,10 @@ class PipelinedDecoder:
         self.lib = load()
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
-        self.cfg = PdConfig(
-            n_layer=shape.n_layer, d_model=shape.d_model, n_head=shape.n_head, head_dim=shape.head_dim,
-            d_ff=shape.d_ff, vocab=shape.vocab, ffn_kind=shape.ffn_kind, norm_kind=shape.norm_kind,
-            pos_kind=shape.pos_kind, rope_base=shape.rope_base, norm_eps=shape.norm_eps,
-            dtype=shape.dtype, bos_id=shape.bos_id, eos_id=shape.eos_id, max_batch=max_batch,
-            max_ctx=max_ctx, max_sub=max_sub, max_sub_tokens=max_sub_tokens, max_pos=max_pos,
-            kv_pair_layers=kv_pair_layers)
+        self.cfg = _config(shape, max_batch, max_ctx, max_sub, max_sub_tokens, max_pos, kv_pair_layers)
         self.vocab = shape.vocab
-        self._keep = []          # device tensors referenced by the library
-
-        def dev(a):
-            if a is None:
-                return None, None
-            if a.dtype == np.uint16:
-                t = torch.from_numpy(a.view(np.int16)).to(self.device).view(torch.bfloat16)
-            else:
-                t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(self.device)
-            self._keep.append(t)
-            return t, t.data_ptr()
-
-        w = PdWeights()
-        for name in ("tok_emb", "pos_emb", "lm_head", "final_norm_g", "final_norm_b"):
-            setattr(w, name, dev(weights.get(name))[1])
-        n_layer = shape.n_layer
-        self._arrays = []
-        for name in ("wqkv", "wo", "w1", "w_up", "w2", "norm1_g", "norm1_b", "norm2_g", "norm2_b"):
-            ptrs = [dev(lw.get(name))[1] for lw in weights["layers"]]
-            if all(p is None for p in ptrs):
-                setattr(w, name, None)
-                continue
-            arr = (C.c_void_p * n_layer)(*ptrs)
-            self._arrays.append(arr)
-            setattr(w, name, C.cast(arr, C.POINTER(C.c_void_p)))
+        # device tensors and pointer arrays referenced by the library
+        w, self._keep, self._arrays = _upload_weights(torch, self.device, shape, weights)
         nbytes = self.lib.pd_workspace_bytes(C.byref(self.cfg))
         if nbytes == 0:
             raise PdError(f"invalid configuration: {self.lib.pd_last_error().decode()}")
@@ -219,6 +230,31 @@ class PipelinedDecoder:
         us, n = C.c_double(0), C.c_int32(0)
         _check(self.lib.pd_profile_read(self.ctx, C.byref(us), C.byref(n)))
         return us.value, n.value
+
+
+def generate_static(shape, weights, ctx_tokens, n_sub, delta_t, sub_tokens, time_max, max_pos,
+                    device="cuda:0", kv_pair_layers=-1):
+    """pd_generate_static: the whole of Algorithm 1 in the library's own static workspace (no device
+    allocation inside the library; the weights are uploaded here, by the caller's side).
+    Returns (tokens int32 [B][S][M] padded -1, lens int32 [B][S], steps int32 [B])."""
+    import torch
+    lib = load()
+    device = torch.device(device)
+    torch.cuda.set_device(device)
+    a, p = _i32(ctx_tokens)
+    B, L = a.shape
+    cfg = _config(shape, B, L, n_sub, sub_tokens, max_pos, kv_pair_layers)
+    w, keep, arrays = _upload_weights(torch, device, shape, weights)
+    toks = np.full((B, n_sub, sub_tokens), -2, dtype=np.int32)
+    lens = np.zeros((B, n_sub), dtype=np.int32)
+    steps = np.zeros((B,), dtype=np.int32)
+    i32p = C.POINTER(C.c_int32)
+    stream = C.c_void_p(torch.cuda.current_stream(device).cuda_stream)
+    _check(lib.pd_generate_static(C.byref(cfg), C.byref(w), p, B, L, n_sub, delta_t, sub_tokens, time_max,
+                                  toks.ctypes.data_as(i32p), lens.ctypes.data_as(i32p),
+                                  steps.ctypes.data_as(i32p), stream))
+    del keep, arrays
+    return toks, lens, steps
 
 
 def measure_read_bandwidth(dev_ptr, buf_bytes, chunk_bytes, iters, stream=None):

@@ -319,7 +319,7 @@ __global__ __launch_bounds__(256) void k_attn_merge(AttnArgs a) {
 }
 
 static int pick_splits(pd_ctx *c, int units, int nblk) {
-  int cap = std::max(1, 4096 / units);
+  int cap = std::max(1, c->part_units / units);
   if (c->opt_splits > 0) return std::min(c->opt_splits, cap);
   // One block per compute unit, every wave streaming several key blocks back to back (measured at
   // 16 heads x 8k keys: 16.2 us with 256 blocks, 17.2 with 512 or 768, 18.7 with 320; at 4 x 32 heads
@@ -342,7 +342,7 @@ int mfma_attention(pd_ctx *c, const LayerPtrs &lw, int A, int nreq, int req0, in
   a.A = A; a.nqg = (A + 15) / 16; a.req0 = req0;
   a.scale_log2 = 1.4426950408889634f / sqrtf((float)g.head_dim);
   int units = nreq * a.nqg * g.n_head;
-  PD_REQUIRE(units <= 4096, PD_EINVAL, "too many (request, head, query group) units: %d", units);
+  PD_REQUIRE(units <= c->part_units, PD_EINVAL, "too many (request, head, query group) units: %d", units);
   // the most keys this launch can meet: prefill knows it, decode takes the end of the run
   int n_keys = kv_override >= 0 ? kv_override : c->L + c->S * (c->M + 1);
   a.nblk_static = std::min((n_keys + 31) / 32, c->kv_cap / 32);

@@ -5,6 +5,7 @@
 #include <stdlib.h>
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 
 #include "pd_internal.h"
@@ -125,7 +126,13 @@ static size_t carve(const pd_config *g, char *base, pd_ctx *c) {
   // logits exist for decode rows only (the context pass never runs the head)
   x->logits = cv.take<float>((size_t)((B * a_max + 15) / 16 * 16) * x->vocab_pad);
   x->scores = x->impl == 0 ? cv.take<float>((size_t)x->R_cap * H * x->kv_cap) : nullptr;
-  x->att_part = cv.take<float>((size_t)4096 * 16 * (hd + 2));
+  // split partials of the attention kernel: one (max, sum, O) record of 16 queries per (request, head,
+  // query group) unit and split; the launch caps its splits so that units * splits <= part_units
+  {
+    int units_dec = B * ((a_max + 15) / 16) * H, units_pre = (x->prefill_chunk_cap / 16) * H;
+    x->part_units = std::max(std::max(units_dec, units_pre), 1024);
+  }
+  x->att_part = cv.take<float>((size_t)x->part_units * 16 * (hd + 2));
   x->ypart = cv.take<float>((size_t)4 * Rp * d);
   x->lm_parts = (x->vocab_pad / 16);
   x->lm_part_val = cv.take<float>((size_t)x->lm_parts * Rp);
@@ -172,8 +179,15 @@ extern "C" size_t pd_workspace_bytes(const pd_config *cfg) {
 // ---------------------------------------------------------------------------
 // create / destroy
 // ---------------------------------------------------------------------------
-extern "C" int pd_create(const pd_config *cfg, const pd_weights *w, void *dev_workspace,
-                         size_t bytes, void *hip_stream, pd_ctx **out) {
+__global__ void k_fill_zero(uint4 *p, size_t n16) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
+    p[i] = make_uint4(0, 0, 0, 0);
+}
+
+// no_alloc: nothing that allocates device or pinned host memory is called (the staging buffer is
+// ordinary host memory, the workspace is cleared by a kernel).
+static int create_ctx(const pd_config *cfg, const pd_weights *w, void *dev_workspace, size_t bytes,
+                      void *hip_stream, bool no_alloc, pd_ctx **out) {
   int rc = check_config(cfg);
   if (rc) return rc;
   PD_REQUIRE(w && out && dev_workspace, PD_EINVAL, "weights, workspace and out must not be NULL");
@@ -215,14 +229,26 @@ extern "C" int pd_create(const pd_config *cfg, const pd_weights *w, void *dev_wo
   c->graph_exec = nullptr; c->graph_ready = false; c->ev_used = 0; c->h_pinned = nullptr;
   c->B = c->L = c->S = c->dt = c->M = c->time_max = c->A = c->R = 0;
   hipStream_t s = (hipStream_t)hip_stream;
-  auto fail = [&](int code) { if (c->h_pinned) (void)hipHostFree(c->h_pinned); delete c; return code; };
-  hipError_t e = hipHostMalloc((void **)&c->h_pinned,
-                               sizeof(int32_t) * (2 * (size_t)cfg->max_batch * cfg->max_sub + 16), 0);
-  if (e != hipSuccess) { pd_set_error("hipHostMalloc failed: %s", hipGetErrorString(e)); return fail(PD_EHIP); }
+  auto fail = [&](int code) { (void)pd_destroy(c); return code; };
+  const size_t n_stage = 2 * (size_t)cfg->max_batch * cfg->max_sub + 16;
+  hipError_t e = hipSuccess;
+  c->stage_pinned = !no_alloc;
+  if (no_alloc) {
+    c->h_pinned = new (std::nothrow) int32_t[n_stage];
+    if (!c->h_pinned) { pd_set_error("out of host memory"); return fail(PD_ENOMEM); }
+  } else {
+    e = hipHostMalloc((void **)&c->h_pinned, sizeof(int32_t) * n_stage, 0);
+    if (e != hipSuccess) { pd_set_error("hipHostMalloc failed: %s", hipGetErrorString(e)); return fail(PD_EHIP); }
+  }
   // Clear everything up to the re-packed weights: caches must hold finite values
   // (masked keys are multiplied by zero), state must start at zero.
-  e = hipMemsetAsync(c->ws, 0, need, s);
-  if (e != hipSuccess) { pd_set_error("hipMemsetAsync failed: %s", hipGetErrorString(e)); return fail(PD_EHIP); }
+  if (no_alloc) {
+    hipLaunchKernelGGL(k_fill_zero, dim3(1024), dim3(256), 0, s, (uint4 *)c->ws, need / 16);
+    e = hipGetLastError();
+  } else {
+    e = hipMemsetAsync(c->ws, 0, need, s);
+  }
+  if (e != hipSuccess) { pd_set_error("clearing the workspace failed: %s", hipGetErrorString(e)); return fail(PD_EHIP); }
   if (cfg->pos_kind == 1 && (rc = launch_rope_table(c, s))) return fail(rc);
   if (c->impl == 1 && (rc = mfma_pack_weights(c, s))) return fail(rc);
   e = hipStreamSynchronize(s);
@@ -231,11 +257,19 @@ extern "C" int pd_create(const pd_config *cfg, const pd_weights *w, void *dev_wo
   return PD_OK;
 }
 
+extern "C" int pd_create(const pd_config *cfg, const pd_weights *w, void *dev_workspace,
+                         size_t bytes, void *hip_stream, pd_ctx **out) {
+  return create_ctx(cfg, w, dev_workspace, bytes, hip_stream, false, out);
+}
+
 extern "C" int pd_destroy(pd_ctx *c) {
   if (!c) return PD_OK;
   if (c->graph_exec) (void)hipGraphExecDestroy(c->graph_exec);
   for (hipEvent_t ev : c->ev_pool) (void)hipEventDestroy(ev);
-  if (c->h_pinned) (void)hipHostFree(c->h_pinned);
+  if (c->h_pinned) {
+    if (c->stage_pinned) (void)hipHostFree(c->h_pinned);
+    else delete[] c->h_pinned;
+  }
   delete c;
   return PD_OK;
 }
@@ -518,6 +552,55 @@ extern "C" int pd_generate(pd_ctx *c, const int32_t *ctx_tokens, int B, int L, i
     }
   }
   return PD_OK;
+}
+
+// ---------------------------------------------------------------------------
+// pd_generate for callers that cannot allocate: the workspace is a device array of this library
+// ---------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[PD_STATIC_WORKSPACE_BYTES];
+
+// `scratch` is a host-side stand-in in host code; the array's device address is asked for once per
+// device (every GPU holds its own copy) and only that address is handed to kernels and copies.
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[64] = {};
+
+static int scratch_of_current_device(void **ptr) {
+  int dev = -1;
+  PD_CHECK_HIP(hipGetDevice(&dev));
+  PD_REQUIRE(dev >= 0 && dev < 64, PD_EINVAL, "device index %d outside [0, 64)", dev);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    PD_CHECK_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    PD_REQUIRE(p != nullptr, PD_EHIP, "hipGetSymbolAddress returned no address for the static workspace");
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return PD_OK;
+}
+
+extern "C" int pd_generate_static(const pd_config *cfg, const pd_weights *w, const int32_t *ctx_tokens, int B,
+                                  int L, int n_sub, int delta_t, int max_sub_tokens, int time_max,
+                                  int32_t *out_tokens, int32_t *out_lens, int32_t *out_steps,
+                                  void *hip_stream) {
+  PD_REQUIRE(out_tokens && out_lens && out_steps, PD_EINVAL, "output pointer is NULL");
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  const size_t need = carve(cfg, nullptr, nullptr);
+  PD_REQUIRE(need <= (size_t)PD_STATIC_WORKSPACE_BYTES, PD_ENOMEM,
+             "this configuration needs %zu bytes of workspace; the static workspace of pd_generate_static "
+             "holds %zu (use pd_create with a workspace of the caller's)",
+             need, (size_t)PD_STATIC_WORKSPACE_BYTES);
+  void *ws = nullptr;
+  if ((rc = scratch_of_current_device(&ws))) return rc;
+  pd_ctx *c = nullptr;
+  // the context lives for this call only; create_ctx clears the part of the array it uses (the
+  // array keeps whatever the previous call left) and re-packs the weights into it
+  if ((rc = create_ctx(cfg, w, ws, (size_t)PD_STATIC_WORKSPACE_BYTES, hip_stream, true, &c))) return rc;
+  rc = pd_generate(c, ctx_tokens, B, L, n_sub, delta_t, max_sub_tokens, time_max, out_tokens, out_lens,
+                   out_steps, hip_stream);
+  (void)pd_destroy(c);
+  return rc;
 }
 
 // ---------------------------------------------------------------------------

@@ -128,6 +128,7 @@ struct pd_ctx {
   float *logits;            // [decode rows][vocab] internal logits (simple path / parity output)
   float *scores;            // simple path attention scratch
   float *att_part;          // split-K partials of the attention kernel
+  int part_units;           // records of 16 queries x (head_dim + 2) floats that att_part holds
   float *ypart;             // [4][R_pad][d] split-K partial sums of the O / FFN2 projections
   int pend_parts;           // slices of ypart the next norm kernel has to add to x
   bool packed;              // this launch sequence keeps activations as packed pairs (at most 8 rows):
@@ -148,7 +149,8 @@ struct pd_ctx {
   int opt_splits, opt_graph, opt_profile, opt_split, opt_chunk;
   hipGraphExec_t graph_exec; bool graph_ready;
   std::vector<hipEvent_t> ev_pool; size_t ev_used;
-  int32_t *h_pinned;        // small pinned host staging buffer
+  int32_t *h_pinned;        // small host staging buffer (pinned unless stage_pinned is false)
+  bool stage_pinned;
 };
 
 // ---- launchers (each returns PD_OK or an error code) -----------------------
