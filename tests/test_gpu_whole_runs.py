@@ -1,0 +1,172 @@
+"""The named workloads cfg3, cfg4 and cfg5 at full size (every layer, the whole context, the whole
+batch, every iteration of the run), in the launch configuration the benchmark times.
+
+(1) Against stored full-run results of the CPU oracle.  tests/golden/make_full_run.py (CPU only; it
+    calls oracle/ and the seeded input generators, nothing else) ran the oracle free-running over the
+    whole workload and kept, per logit row, the appended token, its top-2 margin, the 8 largest
+    logits with their indices and the logits at 256 fixed columns.  Here the library is stepped over
+    the same run: rows whose stored margin exceeds 0.05 are left to the library's own argmax, which
+    must equal the stored token; the others are forced to the stored token so that both sides keep the
+    same history.  Every fed row's logits are compared at the stored columns and at the stored top-8
+    indices, and the row's largest logit anywhere may not exceed the stored maximum by more than the
+    tolerance.  Requests without a stored file (the oracle needs hours per request of the 7B-shaped
+    workload) run free beside the checked ones and are not compared.
+(2) The bf16 matrix-core kernels against the library's own fp32 kernels in lock-step: a consistency
+    check over every request and row, not a parity claim (both sides share the schedule kernels).
+"""
+
+import glob
+import os
+
+import numpy as np
+import pytest
+
+import pd_inputs as pi
+from pd_inputs.configs import DTYPE_F32
+from parity_util import make_decoder, TOL, MARGIN
+
+pytestmark = pytest.mark.gpu
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+@pytest.fixture(scope="module", params=["cfg3", "cfg4", "cfg5"])
+def workload(request):
+    """Weights and context of one named workload, drawn once for the tests that use it."""
+    cfg = pi.get_config(request.param)
+    w = pi.make_weights(cfg)
+    say(f"[{cfg.name}] weights drawn")
+    yield cfg, w, pi.make_context(cfg)
+
+
+def stored_runs(name):
+    out = {}
+    for path in sorted(glob.glob(os.path.join(GOLDEN, f"full_run_{name}_req*.npz"))):
+        z = np.load(path)
+        out[int(z["request"])] = {k: z[k] for k in z.files}
+    return out
+
+
+def test_whole_run_against_stored_oracle_results(workload):
+    import torch
+    cfg, w, ctx = workload
+    gold = stored_runs(cfg.name)
+    if not gold:
+        pytest.skip(f"no stored oracle results for {cfg.name} (tests/golden/make_full_run.py writes them)")
+    B, S, T, tol = cfg.batch, cfg.n_sub, cfg.time_steps, TOL[cfg.dtype]
+    rows_at = {}
+    for b, g in gold.items():
+        assert int(g["steps"]) == T and str(g["workload"]) == cfg.name
+        assert len(g["token"]) == S * (cfg.sub_tokens + 1) - 1, "one row per fed token"
+        by_step = [[] for _ in range(T + 1)]
+        for r, t in enumerate(g["step"]):
+            by_step[t].append(r)
+        rows_at[b] = by_step
+    cols = torch.from_numpy(next(iter(gold.values()))["cols"].astype(np.int64)).cuda()
+    dec = make_decoder(cfg, w)
+    dec.prefill_context(ctx, S, cfg.delta_t, cfg.sub_tokens, T)
+    say(f"[{cfg.name}] contexts encoded; requests with stored oracle results: {sorted(gold)} of {B}")
+    worst, n_rows, n_free, n_forced = 0.0, 0, 0, 0
+    for t in range(1, T + 1):
+        force = np.full((B, S), -1, dtype=np.int32)
+        want = {}
+        for b, g in gold.items():
+            for r in rows_at[b][t]:
+                i, tok = int(g["sub"][r]), int(g["token"][r])
+                want[(b, i)] = (r, tok)
+                if tok >= 0 and g["margin"][r] <= MARGIN:
+                    force[b, i - 1] = tok
+        toks, logits, done = dec.decode_step(force=force, want_logits=True)
+        fed = (~torch.isnan(logits[:, :, 0])).cpu().numpy()
+        for b in gold:
+            assert sorted(i for (bb, i) in want if bb == b) == (np.flatnonzero(fed[b]) + 1).tolist(), \
+                f"step {t} request {b}: rows fed {np.flatnonzero(fed[b]) + 1} differ from the oracle's"
+        if want:
+            keys = sorted(want)
+            bi = torch.tensor([k[0] for k in keys]).cuda()
+            si = torch.tensor([k[1] - 1 for k in keys]).cuda()
+            rows = logits[bi, si]                                           # [n, V]
+            top_idx = np.stack([gold[k[0]]["top_idx"][want[k][0]] for k in keys]).astype(np.int64)
+            got_cols = rows[:, cols].cpu().numpy().astype(np.float64)
+            got_top = rows.gather(1, torch.from_numpy(top_idx).cuda()).cpu().numpy().astype(np.float64)
+            got_max = rows.max(dim=1).values.cpu().numpy().astype(np.float64)
+            for n, k in enumerate(keys):
+                g = gold[k[0]]
+                r, tok = want[k]
+                e = max(np.abs(got_cols[n] - g["sample"][r]).max(), np.abs(got_top[n] - g["top_val"][r]).max())
+                assert np.isfinite(e) and e <= tol, \
+                    f"step {t} request {k[0]} subsequence {k[1]}: max|logit diff| = {e:.3e} > {tol}"
+                assert got_max[n] <= g["top_val"][r][0] + tol, \
+                    f"step {t} request {k[0]} subsequence {k[1]}: a logit above the oracle's maximum"
+                worst = max(worst, e)
+                n_rows += 1
+                if tok >= 0:
+                    assert toks[k[0], k[1] - 1] == tok, \
+                        (f"step {t} request {k[0]} subsequence {k[1]}: token {toks[k[0], k[1] - 1]}, oracle {tok} "
+                         f"(margin {g['margin'][r]:.3f}, forced {force[k[0], k[1] - 1] >= 0})")
+                    n_free += int(force[k[0], k[1] - 1] < 0)
+                    n_forced += int(force[k[0], k[1] - 1] >= 0)
+                else:
+                    assert toks[k[0], k[1] - 1] == -1, "a row that only feeds a finished subsequence selects nothing"
+        assert done == (t == T), f"step {t}: all_done = {done}"
+        if t % 64 == 0:
+            say(f"[{cfg.name}] step {t}/{T}: max|diff| so far {worst:.3e}")
+    assert n_rows == len(gold) * (S * (cfg.sub_tokens + 1) - 1)
+    say(f"[full run] {cfg.name}: {T} steps, requests {sorted(gold)}, {n_rows} logit rows against the stored oracle "
+        f"results, max|diff| = {worst:.3e} (tol {tol}); {n_free} greedy tokens chosen by the library and equal to "
+        f"the oracle's (margin > {MARGIN}), {n_forced} forced (margin <= {MARGIN})")
+    dec.close()
+
+
+def _as_f32_weights(v):
+    if isinstance(v, np.ndarray) and v.dtype == np.uint16:
+        return (v.astype(np.uint32) << 16).view(np.float32)
+    if isinstance(v, list):
+        return [_as_f32_weights(x) for x in v]
+    if isinstance(v, dict):
+        return {k: _as_f32_weights(x) for k, x in v.items()}
+    return v
+
+
+def test_whole_workload_bf16_kernels_against_fp32_kernels(workload):
+    """Every request, every iteration: the bf16 matrix-core kernels and the library's fp32 kernels
+    (separate kernels: no matrix cores, fp32 caches, one block per row and head) on the same
+    bf16-rounded weights, in lock-step.  Rows whose fp32 top-2 margin exceeds MARGIN are left to the
+    bf16 path's own argmax and must agree; the others are forced so that both keep the same history."""
+    import torch
+    cfg, w, ctx = workload
+    ref = make_decoder(cfg.scaled(dtype=DTYPE_F32), _as_f32_weights(w), kv_pair_layers=0)
+    dec = make_decoder(cfg, w)
+    B, S, T = cfg.batch, cfg.n_sub, cfg.time_steps
+    ref.prefill_context(ctx, S, cfg.delta_t, cfg.sub_tokens, T)
+    dec.prefill_context(ctx, S, cfg.delta_t, cfg.sub_tokens, T)
+    say(f"[{cfg.name}] contexts encoded")
+    worst, rows, free_rows = 0.0, 0, 0
+    for t in range(1, T + 1):
+        rt, rl, rdone = ref.decode_step(want_logits=True)
+        fed = ~torch.isnan(rl[:, :, 0])
+        top2 = torch.topk(rl, 2, dim=-1).values
+        clear = (fed & ((top2[:, :, 0] - top2[:, :, 1]) > MARGIN)).cpu().numpy()
+        force = np.where(clear, -1, rt).astype(np.int32)      # -1: the bf16 path decides
+        dt_, dl, ddone = dec.decode_step(force=force, want_logits=True)
+        assert np.array_equal(dt_, rt), f"step {t}: tokens differ\n{dt_}\n{rt}"
+        assert ddone == rdone
+        assert torch.equal(~torch.isnan(dl[:, :, 0]), fed), f"step {t}: different rows were fed"
+        if bool(fed.any()):
+            err = float((dl[fed] - rl[fed]).abs().max())
+            assert np.isfinite(err) and err <= TOL[1], f"step {t}: max|logit diff| = {err:.3e}"
+            worst = max(worst, err)
+        rows += int(fed.sum())
+        free_rows += int((clear & (rt >= 0)).sum())
+        if t % 64 == 0:
+            say(f"[{cfg.name}] step {t}/{T}: max|diff| so far {worst:.3e}")
+    assert rdone
+    assert rows == B * (S * (cfg.sub_tokens + 1) - 1)
+    say(f"[whole] {cfg.name}: {T} steps, {rows} logit rows, max|diff| = {worst:.3e} (tol {TOL[1]}), "
+        f"{free_rows} greedy tokens chosen by the bf16 path and equal")
+    ref.close()
+    dec.close()
