@@ -133,6 +133,7 @@ def main():
     ap.add_argument("--workload", default="cfg4")
     ap.add_argument("--graph", type=int, default=0, help="replay each step from a captured HIP graph")
     ap.add_argument("--attn-splits", type=int, default=0)
+    ap.add_argument("--prefill-chunk", type=int, default=0, help="rows of the context pass per launch (0: the library's default)")
     ap.add_argument("--kv-pair-layers", type=int, default=-1,
                     help="leading layers whose cache keeps keys and values as pairs of halves (-1: the library "
                          "chooses from the shape)")
@@ -175,6 +176,7 @@ def main():
         pair_layers = dec.get_info(binding.PD_INFO_KV_PAIR_LAYERS)
         dec.set_option(binding.PD_OPT_USE_GRAPH, args.graph)
         dec.set_option(binding.PD_OPT_ATTN_SPLITS, args.attn_splits)
+        dec.set_option(binding.PD_OPT_PREFILL_CHUNK, args.prefill_chunk)
         if args.calibrate_copy_mb > 0:
             src = torch.ones(args.calibrate_copy_mb << 20, dtype=torch.uint8, device="cuda")
             dst = torch.empty_like(src)

@@ -170,7 +170,7 @@ int pd_reset_decode(pd_ctx *ctx, void *hip_stream);
  *                        multiply as a pair of bf16 values (about 16 mantissa bits) and runs two
  *                        matrix-core passes per weight / key / value fragment; 0 uses plain bf16
  *                        activations (half the matrix-core work, larger rounding error)
- *   PD_OPT_PREFILL_CHUNK rows of the context pass per launch (0 = default: up to 2048 on the bf16
+ *   PD_OPT_PREFILL_CHUNK rows of the context pass per launch (0 = default: up to 4096 on the bf16
  *                        path, 128 on the fp32 path; other values are rounded up to a multiple
  *                        of 16 and capped at that default).  Results do not depend on it beyond
  *                        rounding order.                                                    */

@@ -16,6 +16,8 @@ Modules
   matrix_form.py  formulation F2: full recompute of the flattened sequence under the
                   boolean attention matrix of Fig. 3b
   splitk.py       log-sum-exp merge of softmax partials (exact identity used by the GPU)
+  encdec.py       the encoder-decoder form the paper itself runs (Eq. 1 encoder states, cross-attention,
+                  bucketed relative-position bias on the Manhattan distance of Section 4.3); oracle only
 
 Parity status: the logit VALUES on random weights are printed nowhere in the
 paper; they are pinned by (a) an independent dense transformer written with

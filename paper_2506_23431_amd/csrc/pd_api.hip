@@ -88,12 +88,12 @@ static size_t carve(const pd_config *g, char *base, pd_ctx *c) {
   x->gen_stride = (x->gen_cap + 8 + 7) / 8 * 8;
   x->kv_cap = (g->max_ctx + x->gen_cap + 63) / 64 * 64;
   // Rows of the context pass per launch: as many as give the many-row projection kernel a block
-  // per compute unit even for small matrices (measured: cfg3 / cfg4 / cfg5 context passes take
-  // 0.103 / 0.180 / 0.900 s in chunks of 128 rows, 0.044 / 0.095 / 0.619 s in chunks of 1024), at
-  // most 16 query groups per (request, head, 16 rows) unit of the attention launch allow.  The fp32
-  // path keeps one score row per (row, head) and stays at 128.
+  // per compute unit even for small matrices (measured: the cfg4 context pass takes 0.180 s in chunks
+  // of 128 rows, 0.095 s in chunks of 1024, 0.075 s in chunks of 2048 and 0.070 s in chunks of 4096),
+  // at most the 4096 (request, head, 16 rows) units of one attention launch allow.  The fp32 path
+  // keeps one score row per (row, head) and stays at 128.
   {
-    int cap = std::min(2048, 16 * (4096 / std::max(H, 1)) / 16 * 16);
+    int cap = std::min(4096, 16 * (4096 / std::max(H, 1)) / 16 * 16);
     x->prefill_chunk_cap = x->impl == 1 ? std::max(128, std::min(cap, (g->max_ctx + 127) / 128 * 128)) : 128;
     x->prefill_chunk = x->prefill_chunk_cap;
   }

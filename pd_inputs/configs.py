@@ -88,3 +88,35 @@ CONFIGS = {
 
 def get_config(name: str) -> WorkloadConfig:
     return CONFIGS[name]
+
+
+@dataclass(frozen=True)
+class EncDecConfig:
+    """Encoder-decoder workload (the kind of backbone the paper itself runs, Section 4.3): a stacked
+    encoder over the input, a decoder with self-attention over the generated side, cross-attention
+    over the encoder states and bucketed relative-position biases.  Oracle-side only for now."""
+    name: str
+    seed: int
+    n_enc_layer: int
+    n_dec_layer: int
+    d_model: int
+    n_head: int
+    head_dim: int       # n_head * head_dim need not equal d_model in this family
+    d_ff: int
+    vocab: int
+    rel_buckets: int = 32
+    rel_max_distance: int = 128
+    norm_eps: float = 1e-6
+    bos_id: int = 0
+    eos_id: int = -1
+    ctx_len: int = 16
+    n_sub: int = 3
+    delta_t: int = 1
+    sub_tokens: int = 4
+
+    @property
+    def time_steps(self) -> int:
+        return (self.n_sub - 1) * self.delta_t + self.sub_tokens
+
+    def scaled(self, **kw) -> "EncDecConfig":
+        return replace(self, **kw)

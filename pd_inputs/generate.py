@@ -150,3 +150,37 @@ def tie_lm_head(cfg: WorkloadConfig, weights: dict, group_a, group_b, scale: flo
         head[j] = pos
     for j in group_b:
         head[j] = neg
+
+
+def make_encdec_weights(cfg, threads: int = 2) -> dict:
+    """Weights of an encoder-decoder workload (float32, row-major [out][in]):
+    "tok_emb" [V,d] shared by both stacks, "lm_head" [V,d], "enc_rel_bias"/"dec_rel_bias"
+    [buckets, H] (one table per stack, used by all its layers), "enc_final_g"/"dec_final_g" [d],
+    "enc_layers": dicts with "wq","wk","wv" [H*hd,d], "wo" [d,H*hd], "w1" [ff,d], "w2" [d,ff],
+    "norm1_g","norm2_g" [d]; "dec_layers": the same plus "cq","ck","cv","co" (cross-attention) and
+    "norm3_g".  Matrices N(0, 0.05), biases N(0, 0.5), gains 1 + N(0, 0.1)."""
+    d, ff, V, inner = cfg.d_model, cfg.d_ff, cfg.vocab, cfg.n_head * cfg.head_dim
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        tid = iter(range(1, 1 << 20))
+
+        def mat(*shape, std=0.05):
+            return _normal(shape, cfg.seed, next(tid), False, pool, std=std)
+
+        def gain():
+            return _normal((d,), cfg.seed, next(tid), False, pool, std=0.1, mean=1.0)
+
+        def layer(cross):
+            lw = {"wq": mat(inner, d), "wk": mat(inner, d), "wv": mat(inner, d), "wo": mat(d, inner),
+                  "w1": mat(ff, d), "w2": mat(d, ff), "norm1_g": gain(), "norm2_g": gain()}
+            if cross:
+                lw.update({"cq": mat(inner, d), "ck": mat(inner, d), "cv": mat(inner, d),
+                           "co": mat(d, inner), "norm3_g": gain()})
+            return lw
+
+        w = {"tok_emb": mat(V, d, std=1.0), "lm_head": mat(V, d),
+             "enc_rel_bias": mat(cfg.rel_buckets, cfg.n_head, std=0.5),
+             "dec_rel_bias": mat(cfg.rel_buckets, cfg.n_head, std=0.5),
+             "enc_final_g": gain(), "dec_final_g": gain()}
+        w["enc_layers"] = [layer(False) for _ in range(cfg.n_enc_layer)]
+        w["dec_layers"] = [layer(True) for _ in range(cfg.n_dec_layer)]
+    return w
