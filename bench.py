@@ -188,22 +188,26 @@ def main():
         dec.prefill_context(ctx, cfg.n_sub, cfg.delta_t, cfg.sub_tokens, T)
         torch.cuda.synchronize()
         prefill_s = time.time() - t0
+        def advance(n):
+            """n decode iterations; under --sync-every in groups with a synchronisation after each."""
+            if args.sync_every > 0:
+                for k0 in range(0, n, args.sync_every):
+                    dec.decode_steps(min(args.sync_every, n - k0))
+                    torch.cuda.synchronize()
+            else:
+                dec.decode_steps(n)
+
         # warm-up: W untimed iterations
-        dec.decode_steps(W)
+        advance(W)
         torch.cuda.synchronize()
 
         def timed_window():
             """Back to t = 0, untimed fast-forward to the window, then exactly K timed iterations."""
             dec.reset_decode()
-            dec.decode_steps(t0w - 1)
+            advance(t0w - 1)
             torch.cuda.synchronize()
             t_start = time.perf_counter()
-            if args.sync_every > 0:
-                for k0 in range(0, K, args.sync_every):
-                    dec.decode_steps(min(args.sync_every, K - k0))
-                    torch.cuda.synchronize()
-            else:
-                dec.decode_steps(K)
+            advance(K)
             torch.cuda.synchronize()
             return time.perf_counter() - t_start
 
