@@ -173,12 +173,18 @@ int pd_reset_decode(pd_ctx *ctx, void *hip_stream);
  *   PD_OPT_PREFILL_CHUNK rows of the context pass per launch (0 = default: up to 4096 on the bf16
  *                        path, 128 on the fp32 path; other values are rounded up to a multiple
  *                        of 16 and capped at that default).  Results do not depend on it beyond
- *                        rounding order.                                                    */
+ *                        rounding order.
+ *   PD_OPT_FUSE_NORM     1 (default): in steps of at most 16 rows the output projection adds its result
+ *                        to the residual stream itself, hands gain * x and per-tile row sums to the
+ *                        first FFN projection, and that projection finishes the second norm of the
+ *                        layer in its epilogue (one kernel less per layer); 0: a separate norm kernel,
+ *                        as in steps with more rows.  Same results up to rounding order.          */
 #define PD_OPT_ATTN_SPLITS 1
 #define PD_OPT_USE_GRAPH   2
 #define PD_OPT_PROFILE     3
 #define PD_OPT_SPLIT_ACT   4
 #define PD_OPT_PREFILL_CHUNK 5
+#define PD_OPT_FUSE_NORM 6
 int pd_set_option(pd_ctx *ctx, int key, int value);
 
 /* Average time in microseconds between the two events of the brackets recorded since the

@@ -13,6 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libpd.so")
 
 PD_OPT_ATTN_SPLITS, PD_OPT_USE_GRAPH, PD_OPT_PROFILE, PD_OPT_SPLIT_ACT, PD_OPT_PREFILL_CHUNK = 1, 2, 3, 4, 5
+PD_OPT_FUSE_NORM = 6
 PD_INFO_KERNEL_PATH, PD_INFO_KV_PAIR_LAYERS, PD_INFO_KV_SATURATED = 1, 2, 3
 
 EXPORTS = ["pd_workspace_bytes", "pd_create", "pd_destroy", "pd_prefill_context", "pd_decode_step",

@@ -71,6 +71,47 @@ int mfma_pack_weights(pd_ctx *c, hipStream_t s) {
 }
 
 // ---------------------------------------------------------------------------
+// c1[n] = sum_k W[n][k] gain[k], c2[n] = sum_k W[n][k] bias[k] over a packed weight matrix (columns n
+// in packed order): what a projection needs to finish a norm in its epilogue when it is fed
+// gain * x instead of the normalised row.  One wave per 16-column tile; runs once, in pd_create.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void k_norm_fold(float *c1, float *c2, const bf16_t *Wp, const float *gain,
+                                                  const float *bias, int KT) {
+  const int nt = blockIdx.x, lane = threadIdx.x, m = lane & 15, g = lane >> 4;
+  const uint4 *wp = (const uint4 *)Wp + (size_t)nt * KT * 64 + lane;
+  float s1 = 0.f, s2 = 0.f;
+  for (int kt = 0; kt < KT; ++kt) {
+    Frag w;
+    w.u = wp[(size_t)kt * 64];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int k = kt * 32 + g * 8 + e;
+      const float wv = bf16_to_f32(w.h[e]);
+      s1 = fmaf(wv, gain[k], s1);
+      if (bias) s2 = fmaf(wv, bias[k], s2);
+    }
+  }
+  s1 += __shfl_xor(s1, 16); s1 += __shfl_xor(s1, 32);
+  s2 += __shfl_xor(s2, 16); s2 += __shfl_xor(s2, 32);
+  if (g == 0) {
+    c1[nt * 16 + m] = s1;
+    if (c2) c2[nt * 16 + m] = s2;
+  }
+}
+
+int mfma_fold_norms(pd_ctx *c, hipStream_t s) {
+  const pd_config &g = c->cfg;
+  const int n_out = (g.ffn_kind == 1 ? 2 : 1) * g.d_ff;
+  for (int l = 0; l < g.n_layer; ++l) {
+    LayerPtrs &lp = c->layers[l];
+    hipLaunchKernelGGL(k_norm_fold, dim3(n_out / 16), dim3(64), 0, s, lp.c1, g.norm_kind == 0 ? lp.c2 : nullptr,
+                       lp.p_w1, lp.n2g, g.norm_kind == 0 ? lp.n2b : nullptr, g.d_model / 32);
+    PD_CHECK_HIP(hipGetLastError());
+  }
+  return PD_OK;
+}
+
+// ---------------------------------------------------------------------------
 // norm -> bf16 activations.  One block per row; rows without a token become zero.
 // The row is read once into registers (gain and bias are requested at the same
 // time), so the kernel costs one memory round trip plus two block reductions.
@@ -224,15 +265,72 @@ int mfma_norm(pd_ctx *c, const float *gain, const float *bias, int R, hipStream_
 // fragments of the row tiles, then the weight fragments of its tiles) into registers of their own;
 // only then the multiplies run.  A share that is not a multiple of U ends with chunks of 4, 2 and
 // 1 k-tiles, so that no load is ever conditional.
-// This file is compiled once per epilogue (PD_GEMM_EPI = 0..5: kernels and launch code of that
+// This file is compiled once per epilogue (PD_GEMM_EPI = 0..6: kernels and launch code of that
 // epilogue) and once without (weight packing, norm kernel, dispatcher).
 // ---------------------------------------------------------------------------
 // epilogue of one 16-column tile: lane holds y[r][n0 + j], r = i*16 + m, n0 = nt*16 + 4g, j = 0..3
+// Mean and reciprocal standard deviation of a row from the per-tile sums the producing projection
+// left (EPI_RESID_NORM), stats[row][tile] = (sum, sum of squares).  The NW waves of a block share the
+// work: wave w, lane (m, g) takes the tile pairs g + 4 (w + NW u) of row m, u = 0 .. PS-1, requested at
+// kernel start so that they arrive with the first weights; what lies beyond (very wide models) is
+// read when the sums are taken.  Fixed order, no atomics: deterministic.
+constexpr int PS = 4;
+__device__ __forceinline__ void stats_request(const GemmArgs &a, int lane, int w, int nw, float4 (&pre)[PS]) {
+  const int m = lane & 15, g = lane >> 4, npair = a.stats_tiles >> 1;
+  const float4 *sp = (const float4 *)(a.stats_in + (size_t)m * a.stats_tiles);
+#pragma unroll
+  for (int u = 0; u < PS; ++u) pre[u] = sp[min(g + 4 * (w + nw * u), npair - 1)];
+}
+__device__ __forceinline__ float2 stats_partial(const GemmArgs &a, int lane, int w, int nw, const float4 (&pre)[PS]) {
+  const int m = lane & 15, g = lane >> 4, npair = a.stats_tiles >> 1;
+  const float4 *sp = (const float4 *)(a.stats_in + (size_t)m * a.stats_tiles);
+  float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+  for (int u = 0; u < PS; ++u)
+    if (g + 4 * (w + nw * u) < npair) { s1 += pre[u].x + pre[u].z; s2 += pre[u].y + pre[u].w; }
+  for (int p = g + 4 * (w + nw * PS); p < npair; p += 4 * nw) {
+    float4 v = sp[p];
+    s1 += v.x + v.z; s2 += v.y + v.w;
+  }
+  s1 += __shfl_xor(s1, 16); s1 += __shfl_xor(s1, 32);
+  s2 += __shfl_xor(s2, 16); s2 += __shfl_xor(s2, 32);
+  return make_float2(s1, s2);
+}
+__device__ __forceinline__ float2 stats_finish(const GemmArgs &a, float2 s) {
+  const float inv_d = 1.f / (float)a.norm_d;
+  const float mean = a.norm_kind == 0 ? s.x * inv_d : 0.f;
+  const float var = fmaxf(s.y * inv_d - mean * mean, 0.f);
+  return make_float2(mean, rsqrtf(var + a.norm_eps));
+}
+
+// what the finishing wave of a tile asked for at kernel start (EPI_RESID_NORM): the residual rows
+// and the next norm's gain at its columns
+struct ResidPre { float4 x, g; };
+// ... and for a projection that finishes a norm: c1 and c2 at the tile's columns
+struct NormPre { float4 c1, c2; };
+
 template <int RT, int EPI>
-__device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int nt, const floatx4 (&acc)[RT],
-                                              const int4 *kvi, int lane, int r0 = 0) {
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int nt, const floatx4 (&acc_in)[RT],
+                                              const int4 *kvi, int lane, int r0 = 0,
+                                              const float2 *nrm = nullptr, const ResidPre *pre = nullptr,
+                                              const NormPre *npre = nullptr) {
   int m = lane & 15, g = lane >> 4;
   int n0 = nt * 16 + 4 * g;
+  floatx4 acc[RT];
+#pragma unroll
+  for (int i = 0; i < RT; ++i) acc[i] = acc_in[i];
+  if ((EPI == EPI_GELU || EPI == EPI_SWIGLU) && nrm) {
+    // the activations were gain * x: finish the norm here (columns in the packed order of the weights)
+    const float4 c1 = npre ? npre->c1 : *(const float4 *)(a.c1 + n0);
+    const float4 c2 = npre ? npre->c2 : (a.c2 ? *(const float4 *)(a.c2 + n0) : make_float4(0.f, 0.f, 0.f, 0.f));
+#pragma unroll
+    for (int i = 0; i < RT; ++i) {
+      acc[i][0] = nrm[i].y * (acc[i][0] - nrm[i].x * c1.x) + c2.x;
+      acc[i][1] = nrm[i].y * (acc[i][1] - nrm[i].x * c1.y) + c2.y;
+      acc[i][2] = nrm[i].y * (acc[i][2] - nrm[i].x * c1.z) + c2.z;
+      acc[i][3] = nrm[i].y * (acc[i][3] - nrm[i].x * c1.w) + c2.w;
+    }
+  }
   // rows at and beyond a.R are never stored: nobody reads them, and with packed activations their
   // slots hold the low parts of rows 0-7
   if (EPI == EPI_RESID) {
@@ -243,6 +341,27 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int nt, const f
       int r = r0 + i * 16 + m;
       if (r >= a.R) continue;
       *(float4 *)(yp + (size_t)r * a.ld + n0) = make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
+    }
+  } else if (EPI == EPI_RESID_NORM) {
+    const float4 gn = pre ? pre->g : *(const float4 *)(a.gain + n0);
+#pragma unroll
+    for (int i = 0; i < RT; ++i) {
+      int r = r0 + i * 16 + m;
+      const bool in = r < a.R;
+      float4 xo = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (in) xo = (pre && RT == 1) ? pre->x : *(const float4 *)(a.x_res + (size_t)r * a.ld + n0);
+      float xn[4] = {xo.x + acc[i][0], xo.y + acc[i][1], xo.z + acc[i][2], xo.w + acc[i][3]};
+      float s1 = 0.f, s2 = 0.f;
+      if (in) {
+        *(float4 *)(a.x_res + (size_t)r * a.ld + n0) = make_float4(xn[0], xn[1], xn[2], xn[3]);
+        float z[4] = {gn.x * xn[0], gn.y * xn[1], gn.z * xn[2], gn.w * xn[3]};
+        store4_split(a.out_bf, a.out_lo, act_off(r, n0, a.ld), z);
+        s1 = (xn[0] + xn[1]) + (xn[2] + xn[3]);
+        s2 = (xn[0] * xn[0] + xn[1] * xn[1]) + (xn[2] * xn[2] + xn[3] * xn[3]);
+      }
+      s1 += __shfl_xor(s1, 16); s1 += __shfl_xor(s1, 32);
+      s2 += __shfl_xor(s2, 16); s2 += __shfl_xor(s2, 32);
+      if (g == 0) a.stats_out[(size_t)r * a.n_tiles + nt] = make_float2(s1, s2);
     }
   } else if (EPI == EPI_GELU) {
 #pragma unroll
@@ -403,6 +522,27 @@ __global__ __launch_bounds__(64 * NW_K) void k_gemm_s(GemmArgs a) {
   int tile[NT];
 #pragma unroll
   for (int t = 0; t < NT; ++t) tile[t] = min(nt0 + t, a.n_tiles - 1);   // tiles past the end repeat the last one
+  // one row tile: what the epilogue needs from memory is asked for now, so that it arrives with the weights
+  constexpr bool FUSED_IN = RT == 1 && (EPI == EPI_GELU || EPI == EPI_SWIGLU);
+  constexpr bool FUSED_OUT = RT == 1 && EPI == EPI_RESID_NORM;
+  __shared__ float2 sm_stat[FUSED_IN ? NW_K : 1][16];
+  float4 pre_s[PS];
+  const bool fused_norm = FUSED_IN && a.stats_in != nullptr;          // the same for the whole launch
+  NormPre pre_n;
+  if (fused_norm) {
+    stats_request(a, lane, wk, NW_K, pre_s);
+    const int n0 = min(nt0 + (wk < NT ? wk : 0), a.n_tiles - 1) * 16 + 4 * (lane >> 4);
+    pre_n.c1 = *(const float4 *)(a.c1 + n0);
+    pre_n.c2 = a.c2 ? *(const float4 *)(a.c2 + n0) : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  ResidPre pre_r;
+  if (FUSED_OUT) {       // wave w < NT finishes tile nt0 + w (the other waves ask for a tile they will not use)
+    const int n0 = min(nt0 + (wk < NT ? wk : 0), a.n_tiles - 1) * 16 + 4 * (lane >> 4);
+    pre_r.g = *(const float4 *)(a.gain + n0);
+    // (rows beyond R read row R - 1 and are masked where the value is used, not here: touching the
+    // value now would make the wave wait for it before it has asked for its weights)
+    pre_r.x = *(const float4 *)(a.x_res + (size_t)min(m, max(a.R - 1, 0)) * a.ld + n0);
+  }
   constexpr int NA = (SPLIT && NT * RT <= 2) ? 2 : 1;
   floatx4 acc2[NT][RT][NA];
 #pragma unroll
@@ -435,7 +575,18 @@ __global__ __launch_bounds__(64 * NW_K) void k_gemm_s(GemmArgs a) {
     for (int t = 0; t < NT; ++t)
 #pragma unroll
       for (int i = 0; i < RT; ++i) red[((wk * NT + t) * RT + i) * 64 + lane] = acc[t][i];
+    if (fused_norm) {
+      float2 sp = stats_partial(a, lane, wk, NW_K, pre_s);
+      if (lane < 16) sm_stat[wk][lane] = sp;
+    }
     __syncthreads();
+    float2 nrm[RT];
+    if (fused_norm && wk < NT) {            // finishing waves: add the waves' shares in wave order
+      float2 tot = sm_stat[0][m];
+#pragma unroll
+      for (int w = 1; w < NW_K; ++w) { tot.x += sm_stat[w][m].x; tot.y += sm_stat[w][m].y; }
+      nrm[0] = stats_finish(a, tot);
+    }
     for (int t = wk; t < NT && nt0 + t < a.n_tiles; t += NW_K) {
       floatx4 sum[RT];
 #pragma unroll
@@ -444,12 +595,17 @@ __global__ __launch_bounds__(64 * NW_K) void k_gemm_s(GemmArgs a) {
       for (int w = 1; w < NW_K; ++w)
 #pragma unroll
         for (int i = 0; i < RT; ++i) sum[i] += red[((w * NT + t) * RT + i) * 64 + lane];
-      gemm_epilogue<RT, EPI>(a, nt0 + t, sum, kvi, lane);
+      gemm_epilogue<RT, EPI>(a, nt0 + t, sum, kvi, lane, 0, fused_norm ? nrm : nullptr,
+                             (FUSED_OUT && t == wk) ? &pre_r : nullptr, (fused_norm && t == wk) ? &pre_n : nullptr);
     }
   } else {
+    float2 nrm[RT];
+    if (fused_norm) nrm[0] = stats_finish(a, stats_partial(a, lane, 0, 1, pre_s));
 #pragma unroll
     for (int t = 0; t < NT; ++t)
-      if (nt0 + t < a.n_tiles) gemm_epilogue<RT, EPI>(a, nt0 + t, acc[t], kvi, lane);
+      if (nt0 + t < a.n_tiles)
+        gemm_epilogue<RT, EPI>(a, nt0 + t, acc[t], kvi, lane, 0, fused_norm ? nrm : nullptr,
+                               (FUSED_OUT && t == 0) ? &pre_r : nullptr, (fused_norm && t == 0) ? &pre_n : nullptr);
   }
 }
 
@@ -701,6 +857,8 @@ static int launch_gemm_split(const GemmArgs &a, int rows, hipStream_t s) {
 
 template <int EPI>
 static int launch_gemm(const GemmArgs &a, int rows, hipStream_t s) {
+  if (EPI == EPI_RESID_NORM)
+    PD_REQUIRE(rows <= 16 && a.R <= 16, PD_EINVAL, "the residual projection that also prepares the next norm takes at most 16 rows (%d)", rows);
   if (rows > 128) {
     PD_REQUIRE(!a.packed, PD_EINVAL, "packed activations hold at most 8 rows (%d)", rows);
     return a.xn_lo ? launch_gemm_rows<EPI, true>(a, rows, s) : launch_gemm_rows<EPI, false>(a, rows, s);
@@ -728,6 +886,7 @@ int mfma_gemm_epi2(const GemmArgs &a, int rows, hipStream_t s);
 int mfma_gemm_epi3(const GemmArgs &a, int rows, hipStream_t s);
 int mfma_gemm_epi4(const GemmArgs &a, int rows, hipStream_t s);
 int mfma_gemm_epi5(const GemmArgs &a, int rows, hipStream_t s);
+int mfma_gemm_epi6(const GemmArgs &a, int rows, hipStream_t s);
 
 int mfma_gemm(int epi, const GemmArgs &a, int rows, hipStream_t s) {
   switch (epi) {
@@ -737,6 +896,7 @@ int mfma_gemm(int epi, const GemmArgs &a, int rows, hipStream_t s) {
     case EPI_GELU: return mfma_gemm_epi3(a, rows, s);
     case EPI_SWIGLU: return mfma_gemm_epi4(a, rows, s);
     case EPI_LM: return mfma_gemm_epi5(a, rows, s);
+    case EPI_RESID_NORM: return mfma_gemm_epi6(a, rows, s);
   }
   pd_set_error("unknown epilogue %d", epi);
   return PD_EINVAL;

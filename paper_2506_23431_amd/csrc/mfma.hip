@@ -29,8 +29,20 @@ int mfma_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_overri
   // output projection + residual
   a.W = lw.p_wo; a.xn = (const bf16_t *)c->att; a.xn_lo = mfma_lo(c, c->att, d); a.K = d; a.n_tiles = d / 16; a.x = c->ypart; a.ld = d;
   a.part_stride = (size_t)c->R_pad * d; a.max_parts = 4; a.parts_out = &c->pend_parts;
-  if ((rc = mfma_gemm(EPI_RESID, a, R, s))) return rc;
-  if ((rc = mfma_norm(c, lw.n2g, lw.n2b, R, s))) return rc;
+  // At most 16 rows: the projection is not cut along K over blocks, so its epilogue holds the final
+  // x + y.  It writes x, gain * x as the activation fragments of the FFN, and per-tile row sums; the
+  // first FFN projection finishes the norm in its epilogue and the norm kernel in between is gone.
+  const bool fuse = c->opt_fuse_norm && R <= 16 && mfma_gemm_row_tiles(R) == 16;
+  if (fuse) {
+    a.x_res = c->x; a.gain = lw.n2g; a.stats_out = c->nstats;
+    a.out_bf = (bf16_t *)c->xn; a.out_lo = mfma_lo(c, c->xn, d);
+    if ((rc = mfma_gemm(EPI_RESID_NORM, a, R, s))) return rc;
+    a.stats_in = c->nstats; a.stats_tiles = d / 16; a.c1 = lw.c1; a.c2 = g.norm_kind == 0 ? lw.c2 : nullptr;
+    a.norm_kind = g.norm_kind; a.norm_d = d; a.norm_eps = g.norm_eps;
+  } else {
+    if ((rc = mfma_gemm(EPI_RESID, a, R, s))) return rc;
+    if ((rc = mfma_norm(c, lw.n2g, lw.n2b, R, s))) return rc;
+  }
   // FFN
   a.xn = (const bf16_t *)c->xn; a.xn_lo = mfma_lo(c, c->xn, d); a.K = d;
   a.out_bf = (bf16_t *)c->hb; a.out_lo = mfma_lo(c, c->hb, ff); a.ld = ff; a.W = lw.p_w1;
@@ -42,6 +54,7 @@ int mfma_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_overri
     rc = mfma_gemm(EPI_GELU, a, R, s);
   }
   if (rc) return rc;
+  a.stats_in = nullptr;
   a.W = lw.p_w2; a.xn = (const bf16_t *)c->hb; a.xn_lo = mfma_lo(c, c->hb, ff); a.K = ff; a.n_tiles = d / 16; a.x = c->ypart; a.ld = d;
   return mfma_gemm(EPI_RESID, a, R, s);
 }

@@ -96,7 +96,7 @@ __device__ __forceinline__ size_t v_cache_off(int key, int dim, int hd) {
 
 
 // ---- entry points between the sources of the bf16 path -------------------------------------
-enum { EPI_QKV = 0, EPI_QKV_ROPE = 1, EPI_RESID = 2, EPI_GELU = 3, EPI_SWIGLU = 4, EPI_LM = 5 };
+enum { EPI_QKV = 0, EPI_QKV_ROPE = 1, EPI_RESID = 2, EPI_GELU = 3, EPI_SWIGLU = 4, EPI_LM = 5, EPI_RESID_NORM = 6 };
 
 struct GemmArgs {
   const bf16_t *W;       // packed
@@ -119,6 +119,14 @@ struct GemmArgs {
   int d, H, hd, kv_cap;
   float *logits; int V, ld_logits;     // EPI_LM: optional logits [rows][ld_logits]
   float *part_val; int32_t *part_idx;  // EPI_LM: [16*RT][n_tiles] best value / index per tile
+  // EPI_RESID_NORM (at most 16 rows, K not cut over blocks): x_res += y in place, out_bf / out_lo receive
+  // gain * x_res as activation fragments, stats_out[row][tile] the sum and the sum of squares of x_res
+  // over the tile's 16 columns
+  float *x_res; const float *gain; float2 *stats_out;
+  // EPI_GELU / EPI_SWIGLU with stats_in != NULL: the activations are gain * x (not normalised); the
+  // epilogue applies the norm, y = rstd * (acc - mean * c1[n]) + c2[n], with mean and rstd of every row
+  // from stats_in[row][stats_tiles] and c1 = W gain, c2 = W bias (c2 NULL: no bias)
+  const float2 *stats_in; int stats_tiles; const float *c1, *c2; int norm_kind, norm_d; float norm_eps;
 };
 
 int mfma_gemm(int epi, const GemmArgs &a, int rows, hipStream_t s);

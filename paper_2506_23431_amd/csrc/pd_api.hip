@@ -165,7 +165,10 @@ static size_t carve(const pd_config *g, char *base, pd_ctx *c) {
       lp.p_wo = cv.take<bf16_t>(dd * d);
       lp.p_w1 = cv.take<bf16_t>((g->ffn_kind == 1 ? 2 : 1) * (size_t)ff * d);
       lp.p_w2 = cv.take<bf16_t>(dd * ff);
+      lp.c1 = cv.take<float>((g->ffn_kind == 1 ? 2 : 1) * (size_t)ff);
+      lp.c2 = cv.take<float>((g->ffn_kind == 1 ? 2 : 1) * (size_t)ff);
     }
+    x->nstats = cv.take<float2>((size_t)16 * (d / 16));
     x->p_lm_head = cv.take<bf16_t>((size_t)x->vocab_pad * d);
   }
   return (cv.off + 255) & ~(size_t)255;
@@ -225,7 +228,7 @@ static int create_ctx(const pd_config *cfg, const pd_weights *w, void *dev_works
     lp.n2b = cfg->norm_kind == 0 ? w->norm2_b[l] : nullptr;
   }
   c->prefilled = false; c->host_steps = 0;
-  c->embed_pending = false; c->packed = false; c->opt_splits = 0; c->opt_graph = 0; c->opt_profile = 0; c->opt_split = 1; c->opt_chunk = 0;
+  c->embed_pending = false; c->packed = false; c->opt_splits = 0; c->opt_graph = 0; c->opt_profile = 0; c->opt_split = 1; c->opt_chunk = 0; c->opt_fuse_norm = 1;
   c->graph_exec = nullptr; c->graph_ready = false; c->ev_used = 0; c->h_pinned = nullptr;
   c->B = c->L = c->S = c->dt = c->M = c->time_max = c->A = c->R = 0;
   hipStream_t s = (hipStream_t)hip_stream;
@@ -251,6 +254,7 @@ static int create_ctx(const pd_config *cfg, const pd_weights *w, void *dev_works
   if (e != hipSuccess) { pd_set_error("clearing the workspace failed: %s", hipGetErrorString(e)); return fail(PD_EHIP); }
   if (cfg->pos_kind == 1 && (rc = launch_rope_table(c, s))) return fail(rc);
   if (c->impl == 1 && (rc = mfma_pack_weights(c, s))) return fail(rc);
+  if (c->impl == 1 && (rc = mfma_fold_norms(c, s))) return fail(rc);
   e = hipStreamSynchronize(s);
   if (e != hipSuccess) { pd_set_error("pd_create: %s", hipGetErrorString(e)); return fail(PD_EHIP); }
   *out = c;
@@ -296,6 +300,8 @@ extern "C" int pd_set_option(pd_ctx *c, int key, int value) {
       PD_REQUIRE(value >= 0, PD_EINVAL, "prefill chunk must be >= 0");
       c->opt_chunk = value == 0 ? 0 : std::min((value + 15) / 16 * 16, c->prefill_chunk_cap);
       return PD_OK;
+    case PD_OPT_FUSE_NORM:
+      c->opt_fuse_norm = value ? 1 : 0; drop_graph(c); return PD_OK;
     case PD_OPT_PROFILE:
       c->opt_profile = value == 2 ? 2 : (value ? 1 : 0); drop_graph(c); c->ev_used = 0; return PD_OK;
     default:

@@ -104,6 +104,7 @@ struct LayerPtrs {
   const float *n1g, *n1b, *n2g, *n2b;
   // MFMA path: re-packed copies inside the workspace
   bf16_t *p_wqkv, *p_wo, *p_w1, *p_w2;
+  float *c1, *c2;                                  // p_w1 times the second norm's gain / bias, per packed column
   void *kc, *vc;                                   // KV caches of this layer
   void *kc_lo, *vc_lo;                             // low halves (layers below kv_pair_layers), else NULL
 };
@@ -131,6 +132,7 @@ struct pd_ctx {
   int part_units;           // records of 16 queries x (head_dim + 2) floats that att_part holds
   float *ypart;             // [4][R_pad][d] split-K partial sums of the O / FFN2 projections
   int pend_parts;           // slices of ypart the next norm kernel has to add to x
+  float2 *nstats;           // [16][d/16] per-tile row sums left by the output projection for the next norm
   bool packed;              // this launch sequence keeps activations as packed pairs (at most 8 rows):
                             // high parts in rows 0-7 of a 16-row fragment, low parts in rows 8-15
   bool embed_pending;       // matrix-core path: the next norm kernel gathers x from the embedding tables
@@ -146,7 +148,7 @@ struct pd_ctx {
   bool prefilled;
   int host_steps;           // decode steps enqueued since prefill/reset
   // options
-  int opt_splits, opt_graph, opt_profile, opt_split, opt_chunk;
+  int opt_splits, opt_graph, opt_profile, opt_split, opt_chunk, opt_fuse_norm;
   hipGraphExec_t graph_exec; bool graph_ready;
   std::vector<hipEvent_t> ev_pool; size_t ev_used;
   int32_t *h_pinned;        // small host staging buffer (pinned unless stage_pinned is false)
@@ -166,6 +168,7 @@ int simple_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_over
 int simple_head(pd_ctx *c, int R, hipStream_t s);
 // MFMA path (mfma.hip)
 int mfma_pack_weights(pd_ctx *c, hipStream_t s);
+int mfma_fold_norms(pd_ctx *c, hipStream_t s);
 int mfma_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_override, hipStream_t s);
 int mfma_head(pd_ctx *c, int R, bool want_logits, hipStream_t s);
 size_t mfma_packed_weight_bytes(const pd_config *cfg);

@@ -515,6 +515,22 @@ def test_options_do_not_change_results():
         dec.close()
 
 
+@pytest.mark.parametrize("name", ["mfma-hd64", "mfma-llama-packed", "mfma-hd128-llama", "mfma-hd32"])
+def test_separate_second_norm_kernel(name):
+    """Steps of at most 16 rows normally finish the layer's second norm inside the first FFN projection
+    (PD_OPT_FUSE_NORM); with the option off they take the separate norm kernel that larger steps use."""
+    from paper_2506_23431_amd import binding
+    cfg = CASES[name]
+    w = pi.make_weights(cfg, threads=4)
+    ctx = pi.make_context(cfg)
+    outs = oracle_run(cfg, w, ctx)
+    dec = make_decoder(cfg, w)
+    dec.set_option(binding.PD_OPT_FUSE_NORM, 0)
+    stats = compare_teacher_forced(cfg, w, ctx, dec, outs, log=say)
+    assert stats["rows"] == cfg.batch * (cfg.n_sub * (cfg.sub_tokens + 1) - 1)
+    dec.close()
+
+
 def test_sweep_runs_sequential_and_pipelined():
     """The sweep tool (sequential S = 1 against pipelined schedules with the same token count) runs on
     a two-layer variant of cfg2 and reports the step counts of the schedule's closed form."""
