@@ -279,7 +279,10 @@ __device__ __forceinline__ void stats_request(const GemmArgs &a, int lane, int w
   const int m = lane & 15, g = lane >> 4, npair = a.stats_tiles >> 1;
   const float4 *sp = (const float4 *)(a.stats_in + (size_t)m * a.stats_tiles);
 #pragma unroll
-  for (int u = 0; u < PS; ++u) pre[u] = sp[min(g + 4 * (w + nw * u), npair - 1)];
+  for (int u = 0; u < PS; ++u) {
+    pre[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (4 * (w + nw * u) < npair) pre[u] = sp[min(g + 4 * (w + nw * u), npair - 1)];   // the same for the whole wave
+  }
 }
 __device__ __forceinline__ float2 stats_partial(const GemmArgs &a, int lane, int w, int nw, const float4 (&pre)[PS]) {
   const int m = lane & 15, g = lane >> 4, npair = a.stats_tiles >> 1;
@@ -529,15 +532,15 @@ __global__ __launch_bounds__(64 * NW_K) void k_gemm_s(GemmArgs a) {
   float4 pre_s[PS];
   const bool fused_norm = FUSED_IN && a.stats_in != nullptr;          // the same for the whole launch
   NormPre pre_n;
-  if (fused_norm) {
-    stats_request(a, lane, wk, NW_K, pre_s);
-    const int n0 = min(nt0 + (wk < NT ? wk : 0), a.n_tiles - 1) * 16 + 4 * (lane >> 4);
+  if (fused_norm) stats_request(a, lane, wk, NW_K, pre_s);
+  if (fused_norm && wk < NT) {      // wave w < NT finishes tile nt0 + w
+    const int n0 = min(nt0 + wk, a.n_tiles - 1) * 16 + 4 * (lane >> 4);
     pre_n.c1 = *(const float4 *)(a.c1 + n0);
     pre_n.c2 = a.c2 ? *(const float4 *)(a.c2 + n0) : make_float4(0.f, 0.f, 0.f, 0.f);
   }
   ResidPre pre_r;
-  if (FUSED_OUT) {       // wave w < NT finishes tile nt0 + w (the other waves ask for a tile they will not use)
-    const int n0 = min(nt0 + (wk < NT ? wk : 0), a.n_tiles - 1) * 16 + 4 * (lane >> 4);
+  if (FUSED_OUT && wk < NT) {       // wave w < NT finishes tile nt0 + w
+    const int n0 = min(nt0 + wk, a.n_tiles - 1) * 16 + 4 * (lane >> 4);
     pre_r.g = *(const float4 *)(a.gain + n0);
     // (rows beyond R read row R - 1 and are masked where the value is used, not here: touching the
     // value now would make the wave wait for it before it has asked for its weights)
