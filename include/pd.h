@@ -151,6 +151,56 @@ int pd_generate_static(const pd_config *cfg, const pd_weights *w, const int32_t 
                        int L, int n_sub, int delta_t, int max_sub_tokens, int time_max,
                        int32_t *out_tokens, int32_t *out_lens, int32_t *out_steps, void *hip_stream);
 
+/* Encoder-decoder form, the form the paper itself runs (Eq. 1: H^E = Encoder(X), computed once per
+ * request by a stacked bidirectional encoder; Eq. 3: every decoder layer attends to the generated
+ * side under the dependency rule of Section 3.2, then to H^E; Section 4.3: the relative position of
+ * two generated-side tokens is the Manhattan distance |t1 - t2| + |i1 - i2| of their grid
+ * coordinates).  The backbone is the text-to-text transformer family that Section 4.3 names:
+ * pre-norm blocks, RMS norm (gain only), W2 relu(W1 u), no biases in linear layers, scores q.k +
+ * bias[head][bucket(relative position)] without a 1/sqrt(head_dim) factor, one bias table per stack
+ * shared by its layers, no bias in the attention over H^E, no absolute positions.  bucket(n) for a
+ * key n >= 0 positions behind the query: n below buckets/2, then logarithmic up to
+ * rel_max_distance, the last bucket beyond; the encoder uses half of the buckets for keys behind or
+ * at the query and half for keys ahead.  Readings: the decoder's distance is (t_q - t_k) + (i_q - i_k)
+ * (both terms are non-negative on visible pairs); the vocabulary projection is a separate matrix.
+ * bf16 weights only (the matrix-core kernels); n_head * head_dim == d_model; head_dim, d_model and
+ * d_ff multiples of 32, head_dim <= 128; rel_buckets even; rel_max_distance <= 128;
+ * max_ctx at most min(4096, 65536 / n_head) (the encoder runs a request's input as one launch
+ * sequence).  Weight pointers as in pd_weights: per-layer entries are HOST arrays of device pointers. */
+typedef struct {
+  int32_t n_enc_layer, n_dec_layer, d_model, n_head, head_dim, d_ff, vocab;
+  int32_t rel_buckets, rel_max_distance;
+  float   norm_eps;
+  int32_t bos_id, eos_id;
+  int32_t max_batch, max_ctx, max_sub, max_sub_tokens;
+} pd_encdec_config;
+
+typedef struct {
+  const void *tok_emb;            /* [vocab][d], shared by both stacks           */
+  const void *lm_head;            /* [vocab][d]                                  */
+  const float *enc_rel_bias, *dec_rel_bias;           /* [rel_buckets][n_head]   */
+  const float *enc_final_norm_g, *dec_final_norm_g;   /* [d]                     */
+  /* encoder layers (n_enc_layer entries each) */
+  const void *const *enc_wqkv, *const *enc_wo, *const *enc_w1, *const *enc_w2;   /* as in pd_weights */
+  const float *const *enc_norm1_g, *const *enc_norm2_g;
+  /* decoder layers (n_dec_layer entries each): self-attention, attention over H^E, feed-forward */
+  const void *const *dec_wqkv, *const *dec_wo, *const *dec_w1, *const *dec_w2;
+  const void *const *cross_wq;    /* [d][d]                                      */
+  const void *const *cross_wkv;   /* [2d][d]: rows 0..d-1 = K, d..2d-1 = V       */
+  const void *const *cross_wo;    /* [d][d]                                      */
+  const float *const *dec_norm1_g, *const *dec_norm3_g, *const *dec_norm2_g;     /* before self-attention,
+                                                                   before the attention over H^E, before the FFN */
+} pd_encdec_weights;
+
+/* Workspace size and creation, as pd_workspace_bytes / pd_create.  The context is used through the
+ * same calls as a decoder-only one: pd_prefill_context encodes the B inputs (Eq. 1) and fills every
+ * decoder layer's keys and values of H^E; pd_decode_step, pd_generate, pd_decode_steps,
+ * pd_reset_decode, pd_set_option and pd_get_info behave as described there (a row's position index is
+ * its grid coordinate (t-1) + (i-1); there is no context part in the decoder's own cache). */
+size_t pd_encdec_workspace_bytes(const pd_encdec_config *cfg);
+int pd_encdec_create(const pd_encdec_config *cfg, const pd_encdec_weights *w, void *dev_workspace,
+                     size_t bytes, void *hip_stream, pd_ctx **out);
+
 /* Runs `n_steps` decode steps (no host inputs or outputs) back to back on the
  * stream; used for timing.  Does not synchronise. */
 int pd_decode_steps(pd_ctx *ctx, int n_steps, void *hip_stream);

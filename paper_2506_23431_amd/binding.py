@@ -18,7 +18,7 @@ PD_INFO_KERNEL_PATH, PD_INFO_KV_PAIR_LAYERS, PD_INFO_KV_SATURATED = 1, 2, 3
 
 EXPORTS = ["pd_workspace_bytes", "pd_create", "pd_destroy", "pd_prefill_context", "pd_decode_step",
            "pd_generate", "pd_generate_static", "pd_decode_steps", "pd_reset_decode", "pd_set_option", "pd_profile_read",
-           "pd_measure_read_bandwidth", "pd_get_info", "pd_last_error"]
+           "pd_measure_read_bandwidth", "pd_get_info", "pd_last_error", "pd_encdec_workspace_bytes", "pd_encdec_create"]
 
 
 class PdError(RuntimeError):
@@ -38,6 +38,24 @@ class PdWeights(C.Structure):
                 ("final_norm_g", C.c_void_p), ("final_norm_b", C.c_void_p)] + \
                [(n, C.POINTER(C.c_void_p)) for n in ("wqkv", "wo", "w1", "w_up", "w2", "norm1_g",
                                                       "norm1_b", "norm2_g", "norm2_b")]
+
+
+class PdEncDecConfig(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_enc_layer", "n_dec_layer", "d_model", "n_head", "head_dim", "d_ff",
+                                         "vocab", "rel_buckets", "rel_max_distance")] + \
+               [("norm_eps", C.c_float)] + \
+               [(n, C.c_int32) for n in ("bos_id", "eos_id", "max_batch", "max_ctx", "max_sub", "max_sub_tokens")]
+
+
+_ENCDEC_GLOBAL = ("tok_emb", "lm_head", "enc_rel_bias", "dec_rel_bias", "enc_final_norm_g", "dec_final_norm_g")
+_ENCDEC_ENC = ("enc_wqkv", "enc_wo", "enc_w1", "enc_w2", "enc_norm1_g", "enc_norm2_g")
+_ENCDEC_DEC = ("dec_wqkv", "dec_wo", "dec_w1", "dec_w2", "cross_wq", "cross_wkv", "cross_wo",
+               "dec_norm1_g", "dec_norm3_g", "dec_norm2_g")
+
+
+class PdEncDecWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _ENCDEC_GLOBAL] + \
+               [(n, C.POINTER(C.c_void_p)) for n in _ENCDEC_ENC + _ENCDEC_DEC]
 
 
 _lib = None
@@ -69,6 +87,10 @@ def load():
     lib.pd_measure_read_bandwidth.argtypes = [vp, C.c_size_t, C.c_size_t, C.c_int, vp, C.POINTER(C.c_double)]
     lib.pd_get_info.argtypes = [vp, C.c_int, vp, C.POINTER(C.c_int64)]
     lib.pd_last_error.restype = C.c_char_p
+    lib.pd_encdec_workspace_bytes.restype = C.c_size_t
+    lib.pd_encdec_workspace_bytes.argtypes = [C.POINTER(PdEncDecConfig)]
+    lib.pd_encdec_create.argtypes = [C.POINTER(PdEncDecConfig), C.POINTER(PdEncDecWeights), vp, C.c_size_t, vp,
+                                     C.POINTER(vp)]
     for name in EXPORTS:
         getattr(lib, name)
     _lib = lib
@@ -231,6 +253,62 @@ class PipelinedDecoder:
         us, n = C.c_double(0), C.c_int32(0)
         _check(self.lib.pd_profile_read(self.ctx, C.byref(us), C.byref(n)))
         return us.value, n.value
+
+
+class EncDecPipelinedDecoder(PipelinedDecoder):
+    """The encoder-decoder form behind the same calls: prefill_context encodes the inputs (Eq. 1),
+    decode_step / generate run Algorithm 1 over the decoder.
+
+    shape: object with the fields of pd_encdec_config's model part (pd_inputs.EncDecConfig);
+    weights: the `device` dict of pd_inputs.encdec_to_bf16 (uint16 = bf16 bit patterns)."""
+
+    def __init__(self, shape, weights, max_batch, max_ctx, max_sub, max_sub_tokens, device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.lib = load()
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        self.cfg = PdEncDecConfig(
+            n_enc_layer=shape.n_enc_layer, n_dec_layer=shape.n_dec_layer, d_model=shape.d_model,
+            n_head=shape.n_head, head_dim=shape.head_dim, d_ff=shape.d_ff, vocab=shape.vocab,
+            rel_buckets=shape.rel_buckets, rel_max_distance=shape.rel_max_distance, norm_eps=shape.norm_eps,
+            bos_id=shape.bos_id, eos_id=shape.eos_id, max_batch=max_batch, max_ctx=max_ctx, max_sub=max_sub,
+            max_sub_tokens=max_sub_tokens)
+        self.vocab = shape.vocab
+        self._keep, self._arrays = [], []
+
+        def dev(a):
+            if a.dtype == np.uint16:
+                t = torch.from_numpy(a.view(np.int16)).to(self.device).view(torch.bfloat16)
+            else:
+                t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(self.device)
+            self._keep.append(t)
+            return t.data_ptr()
+
+        def per_layer(layers, key):
+            arr = (C.c_void_p * len(layers))(*[dev(lw[key]) for lw in layers])
+            self._arrays.append(arr)
+            return C.cast(arr, C.POINTER(C.c_void_p))
+
+        w = PdEncDecWeights()
+        for name, key in zip(_ENCDEC_GLOBAL, ("tok_emb", "lm_head", "enc_rel_bias", "dec_rel_bias", "enc_final_g",
+                                              "dec_final_g")):
+            setattr(w, name, dev(weights[key]))
+        for name, key in zip(_ENCDEC_ENC, ("wqkv", "wo", "w1", "w2", "norm1_g", "norm2_g")):
+            setattr(w, name, per_layer(weights["enc_layers"], key))
+        for name, key in zip(_ENCDEC_DEC, ("wqkv", "wo", "w1", "w2", "cq", "ckv", "co", "norm1_g", "norm3_g",
+                                           "norm2_g")):
+            setattr(w, name, per_layer(weights["dec_layers"], key))
+        nbytes = self.lib.pd_encdec_workspace_bytes(C.byref(self.cfg))
+        if nbytes == 0:
+            raise PdError(f"invalid configuration: {self.lib.pd_last_error().decode()}")
+        self.workspace_bytes = nbytes
+        self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+        base = (self.workspace.data_ptr() + 255) // 256 * 256
+        self.ctx = C.c_void_p()
+        _check(self.lib.pd_encdec_create(C.byref(self.cfg), C.byref(w), base, nbytes, self._stream(),
+                                         C.byref(self.ctx)))
+        self.B = self.S = self.M = 0
 
 
 def generate_static(shape, weights, ctx_tokens, n_sub, delta_t, sub_tokens, time_max, max_pos,

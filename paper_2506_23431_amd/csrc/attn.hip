@@ -32,15 +32,22 @@ struct AttnArgs {
   float *part;
   int d, H, kv_cap, gen_stride, L, A, nqg, req0, nsplit, nblk_static;
   float scale_log2;         // log2(e) / sqrt(hd)
+  // BIAS kernels (relative-position bias of the encoder-decoder form, Section 4.3): the score of query
+  // r and key j gets bias[h][clamp(pos[r] - coord[j] + bias_off, 0, bias_len - 1)] (already times
+  // log2(e)); coord[j] of key slot j is read at coord[req * coord_req_stride + j]
+  const float *bias; const uint16_t *coord;
+  int bias_len, bias_off, coord_stride, coord_req_stride;
 };
+constexpr int BIAS_MAX = 264;   // entries of one head's bias table that the kernel keeps in LDS
 
 // PAIR: the layer keeps keys and values as high + low halves.  Scores add q_hi K_lo (q_lo K_lo is
 // below the rounding of everything else), outputs add P V_lo; the kernel holds twice the fragments
 // and is built for one block per compute unit.
-template <int HD, bool SPLIT, bool PAIR>
+template <int HD, bool SPLIT, bool PAIR, bool BIAS = false>
 __global__ __launch_bounds__(256, PAIR ? 1 : 3) void k_attn_mfma(AttnArgs a) {
   constexpr int NC = HD / 32, NHB = HD / 16, PSTR = HD + 2;   // partial: m, l, O[HD] per query
   __shared__ float sm_m[4][16], sm_l[4][16];
+  __shared__ float sm_bias[BIAS ? BIAS_MAX : 1];
   __shared__ floatx4 sm_o[4][HD / 16][64];
   __shared__ uint4 sm_q[(SPLIT ? 2 : 1) * NC][64];
   int split = blockIdx.x, h = blockIdx.y, z = blockIdx.z;
@@ -56,6 +63,13 @@ __global__ __launch_bounds__(256, PAIR ? 1 : 3) void k_attn_mfma(AttnArgs a) {
   int r = reqi * a.A + (in_req ? qa : 0);     // row (clamped: loads stay in bounds)
   int4 qi = a.rt.qinfo[r];                    // {flags, sub, lim, req}
   int n_keys = a.kv_override >= 0 ? a.kv_override : a.kv_len[req];
+  int q_pos = 0;
+  float bias_pre[2] = {0.f, 0.f};
+  if (BIAS) {
+    q_pos = a.rt.pos[r];
+    bias_pre[0] = a.bias[(size_t)h * a.bias_len + min((int)threadIdx.x, a.bias_len - 1)];
+    bias_pre[1] = a.bias[(size_t)h * a.bias_len + min((int)threadIdx.x + 256, a.bias_len - 1)];
+  }
   // Query fragments (high and low parts) go to LDS, in operand order: the four waves share them,
   // and keeping them out of the registers leaves room for three waves per SIMD.  Rows without a
   // token keep whatever finite numbers their q slots hold: all their keys are masked below, and
@@ -84,7 +98,8 @@ __global__ __launch_bounds__(256, PAIR ? 1 : 3) void k_attn_mfma(AttnArgs a) {
   int kb = split * 4 + wave;
   Frag kf[2][NC], vf[NHB];
   Frag kl[PAIR ? 2 : 1][PAIR ? NC : 1], vl[PAIR ? NHB : 1];
-  union { uint4 u; uint16_t s[8]; } tg;
+  union { uint4 u; uint16_t s[8]; } tg, kco;
+  const uint16_t *kcp = BIAS ? a.coord + (size_t)req * a.coord_req_stride : nullptr;
   auto load_k = [&](int kbx) {
 #pragma unroll
     for (int t = 0; t < 2; ++t)
@@ -97,6 +112,7 @@ __global__ __launch_bounds__(256, PAIR ? 1 : 3) void k_attn_mfma(AttnArgs a) {
   auto load_v = [&](int kbx) {
     // tags of the lane's 8 keys (clamped: context blocks read entry 0 and never use it)
     tg.u = *(const uint4 *)(gs + min(max(kbx * 32 + 8 * g - L8, 0), a.gen_stride - 8));
+    if (BIAS) kco.u = *(const uint4 *)(kcp + min(kbx * 32 + 8 * g, a.coord_stride - 8));
 #pragma unroll
     for (int i = 0; i < NHB; ++i) {
       vf[i].u = Vp[((size_t)kbx * NHB + i) * 64];
@@ -113,6 +129,10 @@ __global__ __launch_bounds__(256, PAIR ? 1 : 3) void k_attn_mfma(AttnArgs a) {
     int c = min(wave + 4 * i, NC - 1);
     sm_q[c][lane] = qh[i];
     if (SPLIT) sm_q[NC + c][lane] = qlo[i];
+  }
+  if (BIAS) {
+    sm_bias[threadIdx.x] = bias_pre[0];
+    if (threadIdx.x + 256 < BIAS_MAX) sm_bias[threadIdx.x + 256] = bias_pre[1];
   }
   __syncthreads();
 
@@ -165,16 +185,22 @@ __global__ __launch_bounds__(256, PAIR ? 1 : 3) void k_attn_mfma(AttnArgs a) {
     // lane (n, g), tile t, register j  <->  key kb*32 + 8g + 4t + j
     const int key0 = kb * 32 + 8 * g;
     float sv[8];
+    float bv[8];
+    if (BIAS) {
+      const int q_off = q_pos + a.bias_off, last = a.bias_len - 1;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) bv[e] = sm_bias[min(max(q_off - (int)kco.s[e], 0), last)];
+    }
     if (kb * 32 + 32 <= lim_all) {
       // every query of the group sees the whole block (the same for all lanes of the wave)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) sv[e] = s[e >> 2][e & 3] * a.scale_log2;
+      for (int e = 0; e < 8; ++e) sv[e] = BIAS ? s[e >> 2][e & 3] * a.scale_log2 + bv[e] : s[e >> 2][e & 3] * a.scale_log2;
     } else {
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         int key = key0 + e;
         bool vis = (key < q_lim) | ((key >= a.L) & (key < n_keys) & ((int)tg.s[e] <= q_sub));
-        sv[e] = vis ? s[e >> 2][e & 3] * a.scale_log2 : -INFINITY;
+        sv[e] = vis ? (BIAS ? s[e >> 2][e & 3] * a.scale_log2 + bv[e] : s[e >> 2][e & 3] * a.scale_log2) : -INFINITY;
       }
     }
     float mloc = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
@@ -330,9 +356,10 @@ static int pick_splits(pd_ctx *c, int units, int nblk) {
 }
 
 int mfma_attention(pd_ctx *c, const LayerPtrs &lw, int A, int nreq, int req0, int kv_override,
-                   hipStream_t s) {
+                   hipStream_t s, const AttnMode *mode) {
   const pd_config &g = c->cfg;
   AttnArgs a;
+  memset(&a, 0, sizeof(a));
   a.q = (const f16_t *)c->q; a.q_lo = (const f16_t *)mfma_lo(c, c->q, g.d_model);
   a.out_lo = mfma_lo(c, c->att, g.d_model); a.kc = (const f16_t *)lw.kc; a.vc = (const f16_t *)lw.vc;
   a.kc_lo = (const f16_t *)lw.kc_lo; a.vc_lo = (const f16_t *)lw.vc_lo;
@@ -341,6 +368,19 @@ int mfma_attention(pd_ctx *c, const LayerPtrs &lw, int A, int nreq, int req0, in
   a.d = g.d_model; a.H = g.n_head; a.kv_cap = c->kv_cap; a.gen_stride = c->gen_stride; a.L = c->L;
   a.A = A; a.nqg = (A + 15) / 16; a.req0 = req0;
   a.scale_log2 = 1.4426950408889634f / sqrtf((float)g.head_dim);
+  if (mode) {
+    PD_REQUIRE(!a.kc_lo, PD_EINVAL, "the encoder-decoder form keeps no pair layers");
+    if (mode->kc) { a.kc = (const f16_t *)mode->kc; a.vc = (const f16_t *)mode->vc; }
+    if (mode->qinfo) a.rt.qinfo = const_cast<int4 *>(mode->qinfo);
+    a.L = mode->L;
+    a.scale_log2 = 1.4426950408889634f * mode->scale;
+    if (mode->bias) {
+      PD_REQUIRE(mode->bias_len >= 1 && mode->bias_len <= BIAS_MAX && mode->coord && mode->coord_stride >= 8,
+                 PD_EINVAL, "relative-position bias table of %d entries (at most %d)", mode->bias_len, BIAS_MAX);
+      a.bias = mode->bias; a.coord = mode->coord; a.bias_len = mode->bias_len; a.bias_off = mode->bias_off;
+      a.coord_stride = mode->coord_stride; a.coord_req_stride = mode->coord_req_stride;
+    }
+  }
   int units = nreq * a.nqg * g.n_head;
   PD_REQUIRE(units <= c->part_units, PD_EINVAL, "too many (request, head, query group) units: %d", units);
   // the most keys this launch can meet: prefill knows it, decode takes the end of the run
@@ -367,7 +407,9 @@ int mfma_attention(pd_ctx *c, const LayerPtrs &lw, int A, int nreq, int req0, in
   hipEvent_t pe0 = attach ? ev0 : nullptr, pe1 = attach ? ev1 : nullptr;
 #define PD_ATTN(HDV)                                                                        \
   do {                                                                                      \
-    if (a.kc_lo && a.q_lo) hipExtLaunchKernelGGL((k_attn_mfma<HDV, true, true>), grid, dim3(256), 0, s, pe0, pe1, 0, a);  \
+    if (a.bias && a.q_lo) hipLaunchKernelGGL((k_attn_mfma<HDV, true, false, true>), grid, dim3(256), 0, s, a);  \
+    else if (a.bias) hipLaunchKernelGGL((k_attn_mfma<HDV, false, false, true>), grid, dim3(256), 0, s, a);      \
+    else if (a.kc_lo && a.q_lo) hipExtLaunchKernelGGL((k_attn_mfma<HDV, true, true>), grid, dim3(256), 0, s, pe0, pe1, 0, a);  \
     else if (a.kc_lo) hipExtLaunchKernelGGL((k_attn_mfma<HDV, false, true>), grid, dim3(256), 0, s, pe0, pe1, 0, a);    \
     else if (attach && a.q_lo) hipExtLaunchKernelGGL((k_attn_mfma<HDV, true, false>), grid, dim3(256), 0, s, ev0, ev1, 0, a);  \
     else if (attach) hipExtLaunchKernelGGL((k_attn_mfma<HDV, false, false>), grid, dim3(256), 0, s, ev0, ev1, 0, a);      \

@@ -53,6 +53,10 @@ static int pack(bf16_t *dst, const void *src, const void *src2, int N_src, int N
   return PD_OK;
 }
 
+int mfma_pack_matrix(bf16_t *dst, const void *src, int N, int K, hipStream_t s) {
+  return pack(dst, src, nullptr, N, (N + 15) / 16 * 16, K, 0, 0, 0, s);
+}
+
 int mfma_pack_weights(pd_ctx *c, hipStream_t s) {
   const pd_config &g = c->cfg;
   int d = g.d_model, ff = g.d_ff, hd = g.head_dim, rc;
@@ -374,7 +378,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int nt, const f
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         float t = acc[i][j];
-        y[j] = 0.5f * t * (1.f + erff(t * 0.70710678118654752f));
+        y[j] = a.act == 1 ? fmaxf(t, 0.f) : 0.5f * t * (1.f + erff(t * 0.70710678118654752f));
       }
       if (r < a.R) store4_split(a.out_bf, a.out_lo, act_off(r, n0, a.ld), y);
     }
@@ -393,7 +397,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int nt, const f
       if (g < 2 && r < a.R) store4_split(a.out_bf, a.out_lo, act_off(r, nt * 8 + 4 * g, a.ld), y);
     }
   } else if (EPI == EPI_QKV || EPI == EPI_QKV_ROPE) {
-    int sec = n0 / a.d, nl = n0 % a.d, h = nl / a.hd;
+    int sec = n0 / a.d + a.sec0, nl = n0 % a.d, h = nl / a.hd;
     int half = a.hd >> 1;
 #pragma unroll
     for (int i = 0; i < RT; ++i) {

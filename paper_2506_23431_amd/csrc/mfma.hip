@@ -8,31 +8,47 @@ bf16_t *mfma_lo(pd_ctx *c, void *buf, size_t cols) {
   return c->packed ? (bf16_t *)buf + 64 : (bf16_t *)buf + (size_t)c->R_pad * cols;
 }
 
-int mfma_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_override, hipStream_t s) {
+// fields every projection of a launch sequence shares
+void mfma_gemm_base(pd_ctx *c, GemmArgs &a, int R) {
   const pd_config &g = c->cfg;
-  const LayerPtrs &lw = c->layers[l];
-  int d = g.d_model, ff = g.d_ff, rc;
-  if ((rc = mfma_norm(c, lw.n1g, lw.n1b, R, s))) return rc;
-  GemmArgs a;
   memset(&a, 0, sizeof(a));
-  a.R = R; a.rt = c->rows; a.d = d; a.H = g.n_head; a.hd = g.head_dim; a.kv_cap = c->kv_cap;
+  a.R = R; a.rt = c->rows; a.d = g.d_model; a.H = g.n_head; a.hd = g.head_dim; a.kv_cap = c->kv_cap;
   a.packed = c->packed;
-  // QKV projection (+ rotary) + KV append
-  a.W = lw.p_wqkv; a.xn = (const bf16_t *)c->xn; a.xn_lo = mfma_lo(c, c->xn, d); a.K = d;
-  a.n_tiles = 3 * d / 16; a.out_bf = (bf16_t *)c->q; a.out_lo = mfma_lo(c, c->q, d); a.kc = (f16_t *)lw.kc; a.vc = (f16_t *)lw.vc; a.rope_cs = c->rope_cs;
-  a.kc_lo = (f16_t *)lw.kc_lo; a.vc_lo = (f16_t *)lw.vc_lo; a.kv_sat = c->kv_sat;
-  if ((rc = mfma_gemm(g.pos_kind == 1 ? EPI_QKV_ROPE : EPI_QKV, a, R, s))) return rc;
-  // context pass, last layer: only its keys and values are ever used (nothing reads the residual
-  // stream of a context token after the last layer)
-  if (kv_override >= 0 && l == g.n_layer - 1) return PD_OK;
-  if ((rc = mfma_attention(c, lw, A, nreq, req0, kv_override, s))) return rc;
-  // output projection + residual
-  a.W = lw.p_wo; a.xn = (const bf16_t *)c->att; a.xn_lo = mfma_lo(c, c->att, d); a.K = d; a.n_tiles = d / 16; a.x = c->ypart; a.ld = d;
+}
+
+// QKV-style projection of the normalised rows in c->xn: queries to c->q, keys and values into the given
+// caches at the rows' slots.  `n_tiles` 16-column tiles of W, whose first d columns are section `sec0`
+// (0: queries, then keys, then values; 1: keys, then values).
+int mfma_qkv(pd_ctx *c, GemmArgs &a, const bf16_t *W, int n_tiles, int sec0, void *kc, void *vc, void *kc_lo,
+             void *vc_lo, int R, hipStream_t s) {
+  const pd_config &g = c->cfg;
+  const int d = g.d_model;
+  a.W = W; a.xn = (const bf16_t *)c->xn; a.xn_lo = mfma_lo(c, c->xn, d); a.K = d;
+  a.n_tiles = n_tiles; a.sec0 = sec0; a.out_bf = (bf16_t *)c->q; a.out_lo = mfma_lo(c, c->q, d);
+  a.kc = (f16_t *)kc; a.vc = (f16_t *)vc; a.rope_cs = c->rope_cs;
+  a.kc_lo = (f16_t *)kc_lo; a.vc_lo = (f16_t *)vc_lo; a.kv_sat = c->kv_sat;
+  return mfma_gemm(g.pos_kind == 1 ? EPI_QKV_ROPE : EPI_QKV, a, R, s);
+}
+
+// output projection of the attention result in c->att, added to the residual stream (as split-K slices
+// that the next norm kernel sums)
+int mfma_out(pd_ctx *c, GemmArgs &a, const bf16_t *p_wo, int R, hipStream_t s) {
+  const int d = c->cfg.d_model;
+  a.W = p_wo; a.xn = (const bf16_t *)c->att; a.xn_lo = mfma_lo(c, c->att, d); a.K = d; a.n_tiles = d / 16; a.x = c->ypart; a.ld = d;
+  a.part_stride = (size_t)c->R_pad * d; a.max_parts = 4; a.parts_out = &c->pend_parts;
+  return mfma_gemm(EPI_RESID, a, R, s);
+}
+
+// output projection + residual, the norm in front of the FFN, the FFN + residual
+int mfma_out_ffn(pd_ctx *c, GemmArgs &a, const bf16_t *p_wo, const LayerPtrs &lw, int R, hipStream_t s) {
+  const pd_config &g = c->cfg;
+  int d = g.d_model, ff = g.d_ff, rc;
+  a.W = p_wo; a.xn = (const bf16_t *)c->att; a.xn_lo = mfma_lo(c, c->att, d); a.K = d; a.n_tiles = d / 16; a.x = c->ypart; a.ld = d;
   a.part_stride = (size_t)c->R_pad * d; a.max_parts = 4; a.parts_out = &c->pend_parts;
   // At most 16 rows: the projection is not cut along K over blocks, so its epilogue holds the final
   // x + y.  It writes x, gain * x as the activation fragments of the FFN, and per-tile row sums; the
   // first FFN projection finishes the norm in its epilogue and the norm kernel in between is gone.
-  const bool fuse = c->opt_fuse_norm && R <= 16 && mfma_gemm_row_tiles(R) == 16;
+  const bool fuse = c->opt_fuse_norm && lw.c1 && R <= 16 && mfma_gemm_row_tiles(R) == 16;
   if (fuse) {
     a.x_res = c->x; a.gain = lw.n2g; a.stats_out = c->nstats;
     a.out_bf = (bf16_t *)c->xn; a.out_lo = mfma_lo(c, c->xn, d);
@@ -50,13 +66,29 @@ int mfma_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_overri
     a.n_tiles = 2 * ff / 16;
     rc = mfma_gemm(EPI_SWIGLU, a, R, s);
   } else {
-    a.n_tiles = ff / 16;
+    a.n_tiles = ff / 16; a.act = g.ffn_kind == 2 ? 1 : 0;
     rc = mfma_gemm(EPI_GELU, a, R, s);
   }
   if (rc) return rc;
   a.stats_in = nullptr;
   a.W = lw.p_w2; a.xn = (const bf16_t *)c->hb; a.xn_lo = mfma_lo(c, c->hb, ff); a.K = ff; a.n_tiles = d / 16; a.x = c->ypart; a.ld = d;
   return mfma_gemm(EPI_RESID, a, R, s);
+}
+
+int mfma_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_override, hipStream_t s) {
+  const pd_config &g = c->cfg;
+  const LayerPtrs &lw = c->layers[l];
+  int rc;
+  if ((rc = mfma_norm(c, lw.n1g, lw.n1b, R, s))) return rc;
+  GemmArgs a;
+  mfma_gemm_base(c, a, R);
+  // QKV projection (+ rotary) + KV append
+  if ((rc = mfma_qkv(c, a, lw.p_wqkv, 3 * g.d_model / 16, 0, lw.kc, lw.vc, lw.kc_lo, lw.vc_lo, R, s))) return rc;
+  // context pass, last layer: only its keys and values are ever used (nothing reads the residual
+  // stream of a context token after the last layer)
+  if (kv_override >= 0 && l == g.n_layer - 1) return PD_OK;
+  if ((rc = mfma_attention(c, lw, A, nreq, req0, kv_override, s))) return rc;
+  return mfma_out_ffn(c, a, lw.p_wo, lw, R, s);
 }
 
 int mfma_head(pd_ctx *c, int R, bool want_logits, hipStream_t s) {

@@ -127,6 +127,8 @@ struct GemmArgs {
   // epilogue applies the norm, y = rstd * (acc - mean * c1[n]) + c2[n], with mean and rstd of every row
   // from stats_in[row][stats_tiles] and c1 = W gain, c2 = W bias (c2 NULL: no bias)
   const float2 *stats_in; int stats_tiles; const float *c1, *c2; int norm_kind, norm_d; float norm_eps;
+  int act;               // EPI_GELU: 0 gelu(erf), 1 relu
+  int sec0;              // EPI_QKV*: section of the weight's first d columns (0: Q, K, V follow; 1: K, V only)
 };
 
 int mfma_gemm(int epi, const GemmArgs &a, int rows, hipStream_t s);
@@ -134,5 +136,23 @@ int mfma_gemm_row_tiles(int rows);            // rows a launch reads/writes: 16 
 int mfma_norm(pd_ctx *c, const float *gain, const float *bias, int R, hipStream_t s);
 // low-part twin of an activation buffer (NULL when the split is switched off)
 bf16_t *mfma_lo(pd_ctx *c, void *buf, size_t cols);
+// pieces of a layer's launch sequence (mfma.hip)
+void mfma_gemm_base(pd_ctx *c, GemmArgs &a, int R);
+int mfma_qkv(pd_ctx *c, GemmArgs &a, const bf16_t *W, int n_tiles, int sec0, void *kc, void *vc, void *kc_lo,
+             void *vc_lo, int R, hipStream_t s);
+int mfma_out(pd_ctx *c, GemmArgs &a, const bf16_t *p_wo, int R, hipStream_t s);
+int mfma_out_ffn(pd_ctx *c, GemmArgs &a, const bf16_t *p_wo, const LayerPtrs &lw, int R, hipStream_t s);
+int mfma_pack_matrix(bf16_t *dst, const void *src, int N, int K, hipStream_t s);   // row-major [N][K] -> fragments
+// What an attention launch of the encoder-decoder form changes (NULL: the decoder-only defaults).
+struct AttnMode {
+  const void *kc, *vc;     // caches to read (NULL: the layer's own)
+  const int4 *qinfo;       // {flags, sub, lim, req} per row (NULL: the step's row table)
+  int L;                   // keys below L are visible up to a row's limit, keys from L on by their tags
+  float scale;             // factor on q.k
+  // relative-position bias (NULL: none): bias[h][clamp(pos[row] - coord[key] + bias_off, 0, bias_len - 1)],
+  // already times log2(e); coord[key] at coord[req * coord_req_stride + key], coord_stride entries readable
+  const float *bias; const uint16_t *coord;
+  int bias_len, bias_off, coord_stride, coord_req_stride;
+};
 int mfma_attention(pd_ctx *c, const LayerPtrs &lw, int A, int nreq, int req0, int kv_override,
-                   hipStream_t s);
+                   hipStream_t s, const AttnMode *mode = nullptr);

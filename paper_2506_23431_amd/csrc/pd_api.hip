@@ -77,7 +77,8 @@ struct Carver {
 };
 
 // Lays the workspace out; with base == NULL only the size is computed.
-static size_t carve(const pd_config *g, char *base, pd_ctx *c) {
+// `e` != NULL: encoder-decoder form (g is the decoder stack's configuration derived from it).
+static size_t carve(const pd_config *g, char *base, pd_ctx *c, const pd_encdec_config *e = nullptr) {
   pd_ctx tmp_ctx;
   pd_ctx *x = c ? c : &tmp_ctx;
   int d = g->d_model, ff = g->d_ff, H = g->n_head, hd = g->head_dim, V = g->vocab;
@@ -86,7 +87,9 @@ static size_t carve(const pd_config *g, char *base, pd_ctx *c) {
   x->pair_layers = resolve_pair_layers(g);
   x->gen_cap = S * (M + 1);
   x->gen_stride = (x->gen_cap + 8 + 7) / 8 * 8;
-  x->kv_cap = (g->max_ctx + x->gen_cap + 63) / 64 * 64;
+  // encoder-decoder form: the decoder's own caches hold generated tokens only and the caches of the
+  // encoder states the input only; one capacity serves both kinds
+  x->kv_cap = ((e ? std::max(g->max_ctx, x->gen_cap) : g->max_ctx + x->gen_cap) + 63) / 64 * 64;
   // Rows of the context pass per launch: as many as give the many-row projection kernel a block
   // per compute unit even for small matrices (measured: the cfg4 context pass takes 0.180 s in chunks
   // of 128 rows, 0.095 s in chunks of 1024, 0.075 s in chunks of 2048 and 0.070 s in chunks of 4096),
@@ -115,6 +118,23 @@ static size_t carve(const pd_config *g, char *base, pd_ctx *c) {
     bool pair = l < x->pair_layers;
     x->layers[l].kc_lo = pair ? cv.take<char>(x->kv_layer_bytes) : nullptr;
     x->layers[l].vc_lo = pair ? cv.take<char>(x->kv_layer_bytes) : nullptr;
+    x->layers[l].xkc = e ? cv.take<char>(x->kv_layer_bytes) : nullptr;
+    x->layers[l].xvc = e ? cv.take<char>(x->kv_layer_bytes) : nullptr;
+  }
+  x->arch = e ? 1 : 0;
+  x->gen_coord = nullptr; x->qinfo_x = nullptr;
+  if (e) {
+    EncDecState &ed = x->ed;
+    ed.n_enc_layer = e->n_enc_layer; ed.rel_buckets = e->rel_buckets; ed.rel_max_distance = e->rel_max_distance;
+    ed.enc_len = 2 * e->rel_max_distance + 1; ed.dec_len = e->rel_max_distance + 1;
+    ed.enc.resize(e->n_enc_layer);
+    // one scratch cache (a single request's keys and values) serves every encoder layer in turn
+    void *ekc = cv.take<char>(x->kv_layer_bytes / B), *evc = cv.take<char>(x->kv_layer_bytes / B);
+    for (LayerPtrs &lp : ed.enc) { lp.kc = ekc; lp.vc = evc; }
+    ed.enc_bias = cv.take<float>((size_t)H * ed.enc_len);
+    ed.dec_bias = cv.take<float>((size_t)H * ed.dec_len);
+    ed.enc_coord = cv.take<uint16_t>(x->kv_cap);
+    x->gen_coord = cv.take<uint16_t>((size_t)B * x->gen_stride);
   }
   size_t Rp = x->R_pad;
   x->x = cv.take<float>(Rp * d);
@@ -144,6 +164,7 @@ static size_t carve(const pd_config *g, char *base, pd_ctx *c) {
   rt.req = cv.take<int32_t>(Rp); rt.sub = cv.take<int32_t>(Rp); rt.tok = cv.take<int32_t>(Rp);
   rt.pos = cv.take<int32_t>(Rp); rt.slot = cv.take<int32_t>(Rp); rt.lim = cv.take<int32_t>(Rp);
   rt.flags = cv.take<int32_t>(Rp); rt.qinfo = cv.take<int4>(Rp); rt.kvinfo = cv.take<int4>(Rp);
+  if (e) x->qinfo_x = cv.take<int4>(Rp);
   SchedState &st = x->sch;
   st.step = cv.take<int32_t>(B); st.k_open = cv.take<int32_t>(B);
   st.n_tok = cv.take<int32_t>((size_t)B * S); st.n_fed = cv.take<int32_t>((size_t)B * S);
@@ -170,6 +191,16 @@ static size_t carve(const pd_config *g, char *base, pd_ctx *c) {
     }
     x->nstats = cv.take<float2>((size_t)16 * (d / 16));
     x->p_lm_head = cv.take<bf16_t>((size_t)x->vocab_pad * d);
+    if (e) {
+      for (LayerPtrs &lp : x->ed.enc) {
+        lp.p_wqkv = cv.take<bf16_t>(3 * dd * d); lp.p_wo = cv.take<bf16_t>(dd * d);
+        lp.p_w1 = cv.take<bf16_t>((size_t)ff * d); lp.p_w2 = cv.take<bf16_t>(dd * ff);
+      }
+      for (int l = 0; l < g->n_layer; ++l) {
+        LayerPtrs &lp = x->layers[l];
+        lp.p_cq = cv.take<bf16_t>(dd * d); lp.p_ckv = cv.take<bf16_t>(2 * dd * d); lp.p_co = cv.take<bf16_t>(dd * d);
+      }
+    }
   }
   return (cv.off + 255) & ~(size_t)255;
 }
@@ -185,6 +216,49 @@ extern "C" size_t pd_workspace_bytes(const pd_config *cfg) {
 __global__ void k_fill_zero(uint4 *p, size_t n16) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
     p[i] = make_uint4(0, 0, 0, 0);
+}
+
+// Second half of context creation, shared by both model forms: options, staging buffer, clearing
+// the workspace, re-packing the weights.  `c` has its configuration, pointers and carve-up.
+static int finish_create(pd_ctx *c, size_t need, void *hip_stream, bool no_alloc, pd_ctx **out) {
+  c->prefilled = false; c->host_steps = 0;
+  c->embed_pending = false; c->packed = false; c->opt_splits = 0; c->opt_graph = 0; c->opt_profile = 0; c->opt_split = 1; c->opt_chunk = 0; c->opt_fuse_norm = 1;
+  c->graph_exec = nullptr; c->graph_ready = false; c->ev_used = 0; c->h_pinned = nullptr;
+  c->B = c->L = c->Lx = c->S = c->dt = c->M = c->time_max = c->A = c->R = 0;
+  hipStream_t s = (hipStream_t)hip_stream;
+  auto fail = [&](int code) { (void)pd_destroy(c); return code; };
+  const size_t n_stage = 2 * (size_t)c->cfg.max_batch * c->cfg.max_sub + 16;
+  hipError_t e = hipSuccess;
+  c->stage_pinned = !no_alloc;
+  if (no_alloc) {
+    c->h_pinned = new (std::nothrow) int32_t[n_stage];
+    if (!c->h_pinned) { pd_set_error("out of host memory"); return fail(PD_ENOMEM); }
+  } else {
+    e = hipHostMalloc((void **)&c->h_pinned, sizeof(int32_t) * n_stage, 0);
+    if (e != hipSuccess) { pd_set_error("hipHostMalloc failed: %s", hipGetErrorString(e)); return fail(PD_EHIP); }
+  }
+  // Clear everything up to the re-packed weights: caches must hold finite values
+  // (masked keys are multiplied by zero), state must start at zero.
+  if (no_alloc) {
+    hipLaunchKernelGGL(k_fill_zero, dim3(1024), dim3(256), 0, s, (uint4 *)c->ws, need / 16);
+    e = hipGetLastError();
+  } else {
+    e = hipMemsetAsync(c->ws, 0, need, s);
+  }
+  if (e != hipSuccess) { pd_set_error("clearing the workspace failed: %s", hipGetErrorString(e)); return fail(PD_EHIP); }
+  int rc;
+  if (c->cfg.pos_kind == 1 && (rc = launch_rope_table(c, s))) return fail(rc);
+  if (c->impl == 1 && (rc = mfma_pack_weights(c, s))) return fail(rc);
+  if (c->impl == 1 && (rc = mfma_fold_norms(c, s))) return fail(rc);
+  if (c->arch == 1) {
+    if ((rc = encdec_pack_weights(c, s))) return fail(rc);
+    // the activation buffer is free at this point: it lends the few hundred ints the table set-up needs
+    if ((rc = encdec_build_tables(c, (int *)c->hb, s))) return fail(rc);
+  }
+  e = hipStreamSynchronize(s);
+  if (e != hipSuccess) { pd_set_error("pd_create: %s", hipGetErrorString(e)); return fail(PD_EHIP); }
+  *out = c;
+  return PD_OK;
 }
 
 // no_alloc: nothing that allocates device or pinned host memory is called (the staging buffer is
@@ -227,43 +301,105 @@ static int create_ctx(const pd_config *cfg, const pd_weights *w, void *dev_works
     lp.n1b = cfg->norm_kind == 0 ? w->norm1_b[l] : nullptr;
     lp.n2b = cfg->norm_kind == 0 ? w->norm2_b[l] : nullptr;
   }
-  c->prefilled = false; c->host_steps = 0;
-  c->embed_pending = false; c->packed = false; c->opt_splits = 0; c->opt_graph = 0; c->opt_profile = 0; c->opt_split = 1; c->opt_chunk = 0; c->opt_fuse_norm = 1;
-  c->graph_exec = nullptr; c->graph_ready = false; c->ev_used = 0; c->h_pinned = nullptr;
-  c->B = c->L = c->S = c->dt = c->M = c->time_max = c->A = c->R = 0;
-  hipStream_t s = (hipStream_t)hip_stream;
-  auto fail = [&](int code) { (void)pd_destroy(c); return code; };
-  const size_t n_stage = 2 * (size_t)cfg->max_batch * cfg->max_sub + 16;
-  hipError_t e = hipSuccess;
-  c->stage_pinned = !no_alloc;
-  if (no_alloc) {
-    c->h_pinned = new (std::nothrow) int32_t[n_stage];
-    if (!c->h_pinned) { pd_set_error("out of host memory"); return fail(PD_ENOMEM); }
-  } else {
-    e = hipHostMalloc((void **)&c->h_pinned, sizeof(int32_t) * n_stage, 0);
-    if (e != hipSuccess) { pd_set_error("hipHostMalloc failed: %s", hipGetErrorString(e)); return fail(PD_EHIP); }
-  }
-  // Clear everything up to the re-packed weights: caches must hold finite values
-  // (masked keys are multiplied by zero), state must start at zero.
-  if (no_alloc) {
-    hipLaunchKernelGGL(k_fill_zero, dim3(1024), dim3(256), 0, s, (uint4 *)c->ws, need / 16);
-    e = hipGetLastError();
-  } else {
-    e = hipMemsetAsync(c->ws, 0, need, s);
-  }
-  if (e != hipSuccess) { pd_set_error("clearing the workspace failed: %s", hipGetErrorString(e)); return fail(PD_EHIP); }
-  if (cfg->pos_kind == 1 && (rc = launch_rope_table(c, s))) return fail(rc);
-  if (c->impl == 1 && (rc = mfma_pack_weights(c, s))) return fail(rc);
-  if (c->impl == 1 && (rc = mfma_fold_norms(c, s))) return fail(rc);
-  e = hipStreamSynchronize(s);
-  if (e != hipSuccess) { pd_set_error("pd_create: %s", hipGetErrorString(e)); return fail(PD_EHIP); }
-  *out = c;
-  return PD_OK;
+  return finish_create(c, need, hip_stream, no_alloc, out);
 }
 
 extern "C" int pd_create(const pd_config *cfg, const pd_weights *w, void *dev_workspace,
                          size_t bytes, void *hip_stream, pd_ctx **out) {
   return create_ctx(cfg, w, dev_workspace, bytes, hip_stream, false, out);
+}
+
+// ---------------------------------------------------------------------------
+// encoder-decoder form
+// ---------------------------------------------------------------------------
+static int check_encdec(const pd_encdec_config *e) {
+  PD_REQUIRE(e != nullptr, PD_EINVAL, "config is NULL");
+  PD_REQUIRE(e->n_enc_layer >= 1 && e->n_dec_layer >= 1 && e->d_model >= 1 && e->n_head >= 1 && e->head_dim >= 1 &&
+                 e->d_ff >= 1 && e->vocab >= 1,
+             PD_EINVAL, "model dimensions must be positive");
+  PD_REQUIRE((int64_t)e->n_head * e->head_dim == e->d_model, PD_EINVAL,
+             "n_head * head_dim (%d * %d) != d_model (%d)", e->n_head, e->head_dim, e->d_model);
+  PD_REQUIRE(e->head_dim % 32 == 0 && e->head_dim <= 128 && e->d_model % 32 == 0 && e->d_ff % 32 == 0, PD_EINVAL,
+             "the encoder-decoder form runs on the matrix-core kernels only: head_dim, d_model and d_ff must be "
+             "multiples of 32 and head_dim <= 128");
+  PD_REQUIRE(e->rel_buckets >= 4 && e->rel_buckets % 4 == 0 && e->rel_buckets <= 256, PD_EINVAL,
+             "rel_buckets must be a multiple of 4 in [4, 256] (got %d)", e->rel_buckets);
+  PD_REQUIRE(e->rel_max_distance > e->rel_buckets / 2 && e->rel_max_distance <= 128, PD_EINVAL,
+             "rel_max_distance must be in (rel_buckets / 2, 128] (got %d)", e->rel_max_distance);
+  PD_REQUIRE(e->norm_eps > 0.f, PD_EINVAL, "norm_eps must be positive");
+  PD_REQUIRE(e->max_batch >= 1 && e->max_ctx >= 1 && e->max_sub >= 1 && e->max_sub_tokens >= 1, PD_EINVAL,
+             "capacities (max_batch, max_ctx, max_sub, max_sub_tokens) must be >= 1");
+  PD_REQUIRE(e->max_ctx <= std::min(4096, 16 * (4096 / e->n_head)), PD_EINVAL,
+             "max_ctx = %d exceeds the %d input tokens one encoder launch sequence takes", e->max_ctx,
+             std::min(4096, 16 * (4096 / e->n_head)));
+  PD_REQUIRE(e->bos_id >= 0 && e->bos_id < e->vocab, PD_EINVAL, "bos_id out of range");
+  PD_REQUIRE(e->eos_id < e->vocab, PD_EINVAL, "eos_id out of range");
+  PD_REQUIRE((int64_t)e->max_sub * (e->max_sub_tokens + 1) < (1 << 24) && e->max_sub <= 65535, PD_EINVAL,
+             "KV capacity too large");
+  return PD_OK;
+}
+
+// the decoder stack as a pd_config of the shared code paths (ffn_kind 2: W2 relu(W1 u); pos_kind 2: no
+// absolute positions) -- values pd_create does not accept from callers
+static pd_config encdec_decoder_config(const pd_encdec_config *e) {
+  pd_config g;
+  memset(&g, 0, sizeof(g));
+  g.n_layer = e->n_dec_layer; g.d_model = e->d_model; g.n_head = e->n_head; g.head_dim = e->head_dim;
+  g.d_ff = e->d_ff; g.vocab = e->vocab; g.ffn_kind = 2; g.norm_kind = 1; g.pos_kind = 2; g.rope_base = 0.f;
+  g.norm_eps = e->norm_eps; g.dtype = 1; g.bos_id = e->bos_id; g.eos_id = e->eos_id;
+  g.max_batch = e->max_batch; g.max_ctx = e->max_ctx; g.max_sub = e->max_sub; g.max_sub_tokens = e->max_sub_tokens;
+  g.max_pos = 65536;          // grid coordinates are kept in 16 bits
+  g.kv_pair_layers = 0;
+  return g;
+}
+
+extern "C" size_t pd_encdec_workspace_bytes(const pd_encdec_config *cfg) {
+  if (check_encdec(cfg) != PD_OK) return 0;
+  pd_config g = encdec_decoder_config(cfg);
+  return carve(&g, nullptr, nullptr, cfg);
+}
+
+extern "C" int pd_encdec_create(const pd_encdec_config *cfg, const pd_encdec_weights *w, void *dev_workspace,
+                                size_t bytes, void *hip_stream, pd_ctx **out) {
+  int rc = check_encdec(cfg);
+  if (rc) return rc;
+  PD_REQUIRE(w && out && dev_workspace, PD_EINVAL, "weights, workspace and out must not be NULL");
+  PD_REQUIRE(((uintptr_t)dev_workspace & 255) == 0, PD_EINVAL, "workspace must be 256-byte aligned");
+  pd_config g = encdec_decoder_config(cfg);
+  size_t need = carve(&g, nullptr, nullptr, cfg);
+  PD_REQUIRE(bytes >= need, PD_ENOMEM, "workspace too small: %zu bytes given, %zu needed", bytes, need);
+  PD_REQUIRE(w->tok_emb && w->lm_head && w->enc_rel_bias && w->dec_rel_bias && w->enc_final_norm_g &&
+                 w->dec_final_norm_g && w->enc_wqkv && w->enc_wo && w->enc_w1 && w->enc_w2 && w->enc_norm1_g &&
+                 w->enc_norm2_g && w->dec_wqkv && w->dec_wo && w->dec_w1 && w->dec_w2 && w->cross_wq &&
+                 w->cross_wkv && w->cross_wo && w->dec_norm1_g && w->dec_norm3_g && w->dec_norm2_g,
+             PD_EINVAL, "a required weight pointer is NULL");
+  for (int l = 0; l < cfg->n_enc_layer; ++l)
+    PD_REQUIRE(w->enc_wqkv[l] && w->enc_wo[l] && w->enc_w1[l] && w->enc_w2[l] && w->enc_norm1_g[l] && w->enc_norm2_g[l],
+               PD_EINVAL, "encoder layer %d: a required weight pointer is NULL", l);
+  for (int l = 0; l < cfg->n_dec_layer; ++l)
+    PD_REQUIRE(w->dec_wqkv[l] && w->dec_wo[l] && w->dec_w1[l] && w->dec_w2[l] && w->cross_wq[l] && w->cross_wkv[l] &&
+                   w->cross_wo[l] && w->dec_norm1_g[l] && w->dec_norm3_g[l] && w->dec_norm2_g[l],
+               PD_EINVAL, "decoder layer %d: a required weight pointer is NULL", l);
+  pd_ctx *c = new (std::nothrow) pd_ctx();
+  PD_REQUIRE(c, PD_ENOMEM, "out of host memory");
+  c->cfg = g;
+  c->ws = (char *)dev_workspace; c->ws_bytes = bytes;
+  carve(&g, c->ws, c, cfg);
+  c->tok_emb = w->tok_emb; c->pos_emb = nullptr; c->lm_head = w->lm_head;
+  c->fng = w->dec_final_norm_g; c->fnb = nullptr;
+  c->ed.enc_fng = w->enc_final_norm_g; c->ed.enc_rel_bias = w->enc_rel_bias; c->ed.dec_rel_bias = w->dec_rel_bias;
+  for (int l = 0; l < cfg->n_enc_layer; ++l) {
+    LayerPtrs &lp = c->ed.enc[l];
+    lp.wqkv = w->enc_wqkv[l]; lp.wo = w->enc_wo[l]; lp.w1 = w->enc_w1[l]; lp.w2 = w->enc_w2[l];
+    lp.n1g = w->enc_norm1_g[l]; lp.n2g = w->enc_norm2_g[l];
+  }
+  for (int l = 0; l < cfg->n_dec_layer; ++l) {
+    LayerPtrs &lp = c->layers[l];
+    lp.wqkv = w->dec_wqkv[l]; lp.wo = w->dec_wo[l]; lp.w1 = w->dec_w1[l]; lp.w2 = w->dec_w2[l];
+    lp.cq = w->cross_wq[l]; lp.ckv = w->cross_wkv[l]; lp.co = w->cross_wo[l];
+    lp.n1g = w->dec_norm1_g[l]; lp.n3g = w->dec_norm3_g[l]; lp.n2g = w->dec_norm2_g[l];
+  }
+  return finish_create(c, need, hip_stream, false, out);
 }
 
 extern "C" int pd_destroy(pd_ctx *c) {
@@ -357,8 +493,9 @@ static int run_layers(pd_ctx *c, int R, int A, int nreq, int req0, int kv_overri
   else if ((rc = launch_embed(c, R, s))) return rc;
   c->pend_parts = 0;
   for (int l = 0; l < c->cfg.n_layer; ++l) {
-    rc = c->impl == 1 ? mfma_layer(c, l, R, A, nreq, req0, kv_override, s)
-                      : simple_layer(c, l, R, A, nreq, req0, kv_override, s);
+    rc = c->arch == 1 ? encdec_decoder_layer(c, l, R, s)
+         : c->impl == 1 ? mfma_layer(c, l, R, A, nreq, req0, kv_override, s)
+                        : simple_layer(c, l, R, A, nreq, req0, kv_override, s);
     if (rc) return rc;
   }
   return PD_OK;
@@ -376,7 +513,8 @@ extern "C" int pd_prefill_context(pd_ctx *c, const int32_t *ctx_tokens, int B, i
              "max_sub_tokens = %d out of range [1, %d]", max_sub_tokens, g.max_sub_tokens);
   PD_REQUIRE(time_max >= 0, PD_EINVAL, "time_max must be >= 0");
   int64_t t_last = std::min<int64_t>(time_max, (int64_t)(n_sub - 1) * delta_t + max_sub_tokens + 1);
-  int64_t p_max = (int64_t)L + std::max<int64_t>(t_last, 1) + n_sub - 2;
+  // encoder-decoder form: a position index is a grid coordinate and does not count the input
+  int64_t p_max = (int64_t)(c->arch == 1 ? 0 : L) + std::max<int64_t>(t_last, 1) + n_sub - 2;
   PD_REQUIRE(p_max < g.max_pos, PD_EINVAL,
              "largest position index %lld does not fit max_pos = %d", (long long)p_max, g.max_pos);
   for (int64_t i = 0; i < (int64_t)B * L; ++i)
@@ -385,7 +523,7 @@ extern "C" int pd_prefill_context(pd_ctx *c, const int32_t *ctx_tokens, int B, i
   hipStream_t s = (hipStream_t)hip_stream;
   c->prefilled = false;
   drop_graph(c);
-  c->B = B; c->L = L; c->S = n_sub; c->dt = delta_t; c->M = max_sub_tokens; c->time_max = time_max;
+  c->B = B; c->L = c->arch == 1 ? 0 : L; c->Lx = c->arch == 1 ? L : 0; c->S = n_sub; c->dt = delta_t; c->M = max_sub_tokens; c->time_max = time_max;
   c->A = std::min(n_sub, max_sub_tokens / delta_t + 1);
   c->R = B * c->A;
   PD_REQUIRE(c->A <= 1024, PD_EINVAL, "%d rows per request exceed the 1024 one step supports", c->A);
@@ -394,11 +532,13 @@ extern "C" int pd_prefill_context(pd_ctx *c, const int32_t *ctx_tokens, int B, i
   PD_CHECK_HIP(hipStreamSynchronize(s));
   int rc;
   if ((rc = launch_reset_state(c, s))) return rc;
-  for (int b = 0; b < B; ++b) {
+  for (int b = 0; b < B && c->arch == 1; ++b)
+    if ((rc = encdec_encode(c, b, s))) return rc;
+  for (int b = 0; b < B && c->arch == 0; ++b) {
     const int chunk = c->opt_chunk > 0 ? c->opt_chunk : c->prefill_chunk;
     for (int p0 = 0; p0 < L; p0 += chunk) {
       int n = std::min(chunk, L - p0);
-      if ((rc = launch_prefill_rows(c, b, p0, n, s))) return rc;
+      if ((rc = launch_prefill_rows(c, b, p0, n, s, c->L, 0, b))) return rc;
       if ((rc = run_layers(c, n, n, 1, b, p0 + n, s))) return rc;
     }
   }

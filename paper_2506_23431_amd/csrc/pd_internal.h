@@ -107,6 +107,23 @@ struct LayerPtrs {
   float *c1, *c2;                                  // p_w1 times the second norm's gain / bias, per packed column
   void *kc, *vc;                                   // KV caches of this layer
   void *kc_lo, *vc_lo;                             // low halves (layers below kv_pair_layers), else NULL
+  // encoder-decoder form, decoder layers: attention over the encoder states
+  const void *cq, *ckv, *co;                       // caller's [d][d], [2d][d] (keys then values), [d][d]
+  const float *n3g;                                // gain of the norm in front of it
+  bf16_t *p_cq, *p_ckv, *p_co;
+  void *xkc, *xvc;                                 // keys / values of the encoder states, this layer's projection
+};
+
+// What pd_encdec_create adds to a context (Eq. 1 as the paper runs it: a stacked encoder, a decoder with
+// attention over its states, relative-position biases on bucketed distances, Section 4.3).
+struct EncDecState {
+  int n_enc_layer, rel_buckets, rel_max_distance;
+  std::vector<LayerPtrs> enc;      // encoder layers (kc / vc: one scratch cache shared by all of them)
+  const float *enc_fng;            // gain of the encoder's final norm
+  const float *enc_rel_bias, *dec_rel_bias;   // caller's [buckets][H] tables (device)
+  float *enc_bias, *dec_bias;      // [H][enc_len] / [H][dec_len]: bias by clamped distance, times log2(e)
+  int enc_len, dec_len;            // 2 * max_distance + 1 (index: query - key + max_distance), max_distance + 1
+  uint16_t *enc_coord;             // [kv_cap] entry j = j: coordinates of the encoder's keys
 };
 
 struct pd_ctx {
@@ -145,6 +162,12 @@ struct pd_ctx {
   int32_t *ctx_tok;         // [B][L] device copy of the context ids
   // decode parameters fixed by prefill
   int B, L, S, dt, M, time_max, A, R;
+  // encoder-decoder form: arch == 1; L above is 0 (the decoder's cache holds generated tokens only)
+  // and Lx is the length of the encoded input
+  int arch, Lx;
+  EncDecState ed;
+  uint16_t *gen_coord;      // [B][gen_stride] grid coordinate (t - 1) + (i - 1) of each generated-side KV slot
+  int4 *qinfo_x;            // [R] row table of the attention over the encoder states
   bool prefilled;
   int host_steps;           // decode steps enqueued since prefill/reset
   // options
@@ -159,7 +182,7 @@ struct pd_ctx {
 // schedule / glue (sched.hip)
 int launch_reset_state(pd_ctx *c, hipStream_t s);
 int launch_tick(pd_ctx *c, hipStream_t s);
-int launch_prefill_rows(pd_ctx *c, int b, int p0, int n, hipStream_t s);
+int launch_prefill_rows(pd_ctx *c, int b, int p0, int n, hipStream_t s, int L, int bidir, int b_cache);
 int launch_embed(pd_ctx *c, int R, hipStream_t s);
 int launch_commit(pd_ctx *c, float *out_logits, hipStream_t s);
 int launch_rope_table(pd_ctx *c, hipStream_t s);
@@ -171,4 +194,9 @@ int mfma_pack_weights(pd_ctx *c, hipStream_t s);
 int mfma_fold_norms(pd_ctx *c, hipStream_t s);
 int mfma_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_override, hipStream_t s);
 int mfma_head(pd_ctx *c, int R, bool want_logits, hipStream_t s);
+// encoder-decoder form (encdec.hip)
+int encdec_pack_weights(pd_ctx *c, hipStream_t s);
+int encdec_build_tables(pd_ctx *c, int *scratch, hipStream_t s);
+int encdec_encode(pd_ctx *c, int b, hipStream_t s);                   // Eq. 1 for request b, then its cross keys / values
+int encdec_decoder_layer(pd_ctx *c, int l, int R, hipStream_t s);
 size_t mfma_packed_weight_bytes(const pd_config *cfg);

@@ -37,8 +37,13 @@ int launch_reset_state(pd_ctx *c, hipStream_t s) {
 // token (coordinate tau = t).  A subsequence that finished in the previous step is
 // fed once more so that its last token enters the KV cache; that row selects no token.
 // ---------------------------------------------------------------------------
+// Encoder-decoder form (qinfo_x != NULL): L is 0 (the decoder's own cache holds generated tokens only);
+// every row also gets an entry of a second table for the attention over the Lx encoder states, and
+// every new key slot its grid coordinate (t - 1) + (i - 1), whose difference between a query and a
+// visible key is their Manhattan distance (Section 4.3).
 __global__ __launch_bounds__(64) void k_tick(SchedState st, RowTables rt, int S, int dt, int M, int L, int A,
-                                             int time_max, int bos, int gen_cap, int gen_stride) {
+                                             int time_max, int bos, int gen_cap, int gen_stride,
+                                             uint16_t *gen_coord, int4 *qinfo_x, int Lx) {
   // one wave per request: lane i looks after subsequences i, i + 64, ...
   __shared__ int s_k, s_t;
   const int b = blockIdx.x, lane = threadIdx.x;
@@ -46,6 +51,7 @@ __global__ __launch_bounds__(64) void k_tick(SchedState st, RowTables rt, int S,
     rt.flags[b * A + a] = 0;
     rt.qinfo[b * A + a] = make_int4(0, -1, 0, b);
     rt.kvinfo[b * A + a] = make_int4(0, b, 0, 0);
+    if (qinfo_x) qinfo_x[b * A + a] = make_int4(0, -1, 0, b);
   }
   for (int i = lane; i < S; i += 64) { st.row_of[b * S + i] = -1; st.step_tok[b * S + i] = -1; }
   if (lane == 0) {
@@ -97,6 +103,10 @@ __global__ __launch_bounds__(64) void k_tick(SchedState st, RowTables rt, int S,
       rt.qinfo[r] = make_int4(fl, i + 1, L, b);
       rt.kvinfo[r] = make_int4(fl, b, L + ng + a, L + (t - 1) + i);
       st.gen_sub[(size_t)b * gen_stride + (L & 7) + ng + a] = (uint16_t)(i + 1);
+      if (qinfo_x) {
+        qinfo_x[r] = make_int4(fl, 0, Lx, b);
+        gen_coord[(size_t)b * gen_stride + ng + a] = (uint16_t)((t - 1) + i);
+      }
       st.n_fed[b * S + i] = nt;
       st.row_of[b * S + i] = r;
     }
@@ -110,25 +120,27 @@ __global__ __launch_bounds__(64) void k_tick(SchedState st, RowTables rt, int S,
 
 int launch_tick(pd_ctx *c, hipStream_t s) {
   hipLaunchKernelGGL(k_tick, dim3(c->B), dim3(64), 0, s, c->sch, c->rows, c->S, c->dt, c->M, c->L,
-                     c->A, c->time_max, c->cfg.bos_id, c->gen_cap, c->gen_stride);
+                     c->A, c->time_max, c->cfg.bos_id, c->gen_cap, c->gen_stride, c->gen_coord, c->qinfo_x, c->Lx);
   PD_CHECK_HIP(hipGetLastError());
   return PD_OK;
 }
 
 // ---------------------------------------------------------------------------
 // prefill rows: context tokens p0 .. p0+n-1 of request b as rows 0 .. n-1.
-// Row for position p sees the keys 0..p (causal prefix), nothing generated.
+// Row for position p sees the keys 0..p (causal prefix), nothing generated; with `bidir` (rows of a
+// bidirectional encoder) all L keys.  Keys and values of the rows go to cache entry `b_cache`.
 // ---------------------------------------------------------------------------
 __global__ void k_prefill_rows(RowTables rt, const int32_t *ctx_tok, int b, int L, int p0, int n,
-                               int R_cap) {
+                               int R_cap, int bidir, int b_cache) {
   int r = blockIdx.x * blockDim.x + threadIdx.x;
   if (r >= R_cap) return;
   if (r < n) {
     int p = p0 + r;
     rt.req[r] = b; rt.sub[r] = 0; rt.tok[r] = ctx_tok[(size_t)b * L + p]; rt.pos[r] = p;
-    rt.slot[r] = p; rt.lim[r] = p + 1; rt.flags[r] = ROW_VALID;
-    rt.qinfo[r] = make_int4(ROW_VALID, 0, p + 1, b);
-    rt.kvinfo[r] = make_int4(ROW_VALID, b, p, p);
+    const int lim = bidir ? L : p + 1;
+    rt.slot[r] = p; rt.lim[r] = lim; rt.flags[r] = ROW_VALID;
+    rt.qinfo[r] = make_int4(ROW_VALID, 0, lim, b_cache);
+    rt.kvinfo[r] = make_int4(ROW_VALID, b_cache, p, p);
   } else {
     rt.flags[r] = 0;
     rt.qinfo[r] = make_int4(0, -1, 0, b);
@@ -136,9 +148,9 @@ __global__ void k_prefill_rows(RowTables rt, const int32_t *ctx_tok, int b, int 
   }
 }
 
-int launch_prefill_rows(pd_ctx *c, int b, int p0, int n, hipStream_t s) {
+int launch_prefill_rows(pd_ctx *c, int b, int p0, int n, hipStream_t s, int L, int bidir, int b_cache) {
   hipLaunchKernelGGL(k_prefill_rows, dim3((c->R_cap + 255) / 256), dim3(256), 0, s, c->rows,
-                     c->ctx_tok, b, c->L, p0, n, c->R_cap);
+                     c->ctx_tok, b, L, p0, n, c->R_cap, bidir, b_cache);
   PD_CHECK_HIP(hipGetLastError());
   return PD_OK;
 }

@@ -8,10 +8,10 @@ oracle and the HIP path are both fed from here and share nothing else.
 
 from .configs import WorkloadConfig, EncDecConfig, CONFIGS, get_config, max_positions
 from .generate import (make_weights, make_context, make_forced_tokens, bf16_round, bf16_bits,
-                       bits_to_f32, tie_lm_head, make_encdec_weights)
+                       bits_to_f32, tie_lm_head, make_encdec_weights, encdec_to_bf16)
 
 __all__ = [
     "WorkloadConfig", "CONFIGS", "get_config", "max_positions",
     "make_weights", "make_context", "make_forced_tokens", "bf16_round", "bf16_bits", "bits_to_f32",
-    "tie_lm_head", "EncDecConfig", "make_encdec_weights",
+    "tie_lm_head", "EncDecConfig", "make_encdec_weights", "encdec_to_bf16",
 ]

@@ -94,7 +94,7 @@ def get_config(name: str) -> WorkloadConfig:
 class EncDecConfig:
     """Encoder-decoder workload (the kind of backbone the paper itself runs, Section 4.3): a stacked
     encoder over the input, a decoder with self-attention over the generated side, cross-attention
-    over the encoder states and bucketed relative-position biases.  Oracle-side only for now."""
+    over the encoder states and bucketed relative-position biases."""
     name: str
     seed: int
     n_enc_layer: int
@@ -113,6 +113,7 @@ class EncDecConfig:
     n_sub: int = 3
     delta_t: int = 1
     sub_tokens: int = 4
+    batch: int = 1
 
     @property
     def time_steps(self) -> int:

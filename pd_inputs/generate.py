@@ -184,3 +184,34 @@ def make_encdec_weights(cfg, threads: int = 2) -> dict:
         w["enc_layers"] = [layer(False) for _ in range(cfg.n_enc_layer)]
         w["dec_layers"] = [layer(True) for _ in range(cfg.n_dec_layer)]
     return w
+
+
+_ENCDEC_MATRICES = ("wq", "wk", "wv", "wo", "w1", "w2", "cq", "ck", "cv", "co")
+
+
+def encdec_to_bf16(weights: dict):
+    """The encoder-decoder weights once as the bf16 kernels take them and once as the values those
+    bit patterns stand for.  Returns (rounded, device): `rounded` has the layout of
+    make_encdec_weights with every matrix rounded to bf16 (float32 arrays); `device` holds the same
+    matrices as uint16 bf16 bit patterns with the three self-attention projections stacked as
+    "wqkv" [3 inner][d] (queries, keys, values) and the key and value projections over the encoder
+    states as "ckv" [2 inner][d]; gains and bias tables stay float32 in both."""
+    rounded = {k: (bf16_round(v) if k in ("tok_emb", "lm_head") else v) for k, v in weights.items()
+               if k not in ("enc_layers", "dec_layers")}
+    device = {k: (bf16_bits(v) if k in ("tok_emb", "lm_head") else v) for k, v in weights.items()
+              if k not in ("enc_layers", "dec_layers")}
+    for group in ("enc_layers", "dec_layers"):
+        rounded[group], device[group] = [], []
+        for lw in weights[group]:
+            r = {k: (bf16_round(v) if k in _ENCDEC_MATRICES else v) for k, v in lw.items()}
+            dv = {k: v for k, v in lw.items() if k not in _ENCDEC_MATRICES}
+            dv["wqkv"] = bf16_bits(np.concatenate([lw["wq"], lw["wk"], lw["wv"]], axis=0))
+            for k in ("wo", "w1", "w2"):
+                dv[k] = bf16_bits(lw[k])
+            if "cq" in lw:
+                dv["cq"] = bf16_bits(lw["cq"])
+                dv["ckv"] = bf16_bits(np.concatenate([lw["ck"], lw["cv"]], axis=0))
+                dv["co"] = bf16_bits(lw["co"])
+            rounded[group].append(r)
+            device[group].append(dv)
+    return rounded, device
