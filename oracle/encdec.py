@@ -3,7 +3,7 @@ encoded once by a stacked encoder into H^E; Eq. 3: the decoder attends to the ge
 the dependency rule of Section 3.2 and to H^E; Section 4.3: the relative position between two
 generated-side tokens, which feeds the backbone's relative-position attention bias, is the
 Manhattan distance |t1 - t2| + |i1 - i2| of their grid coordinates).  Test infrastructure only;
-fp64 numpy; there is no HIP path for this variant yet.
+fp64 numpy.
 
 The backbone is the published text-to-text transformer family the paper names in Section 4.3,
 restated here from its published description:

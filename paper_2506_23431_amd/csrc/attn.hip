@@ -350,6 +350,10 @@ static int pick_splits(pd_ctx *c, int units, int nblk) {
   // One block per compute unit, every wave streaming several key blocks back to back (measured at
   // 16 heads x 8k keys: 16.2 us with 256 blocks, 17.2 with 512 or 768, 18.7 with 320; at 4 x 32 heads
   // x 4k keys 256 blocks are 4 us per launch faster than 768).  Always at least one key block per wave.
+  // Up to 32 key blocks (8 per wave) a single block per (request, head) is faster than splits plus the
+  // merge kernel (measured at 12 heads, 512 + 280 keys: 0.54 against 0.59 ms for a step of 12 layers
+  // with two attentions each; at 1024 + 300 keys one split is slower than the automatic 12).
+  if (nblk <= 32) return 1;
   int want = std::max(1, 256 / units);
   int by_keys = std::max(1, nblk / 4);
   return std::max(1, std::min(std::min(want, by_keys), cap));

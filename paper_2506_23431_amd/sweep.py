@@ -28,6 +28,13 @@ empty (Algorithm 1 keeps opening one every dt steps while any is unfinished).  T
 decisions are forced from the host, one decode step per call; everything else (row bookkeeping,
 early termination, ragged rows) runs on the device as in any other run.  The sequential baseline
 generates the same tokens plus one separator per boundary as a single subsequence.
+
+  python -m paper_2506_23431_amd.sweep --encdec encdec-base [--shape pubmed|wikihowqa|cnndm] [--dt-list 1,2,3]
+
+runs the encoder-decoder form (the form the paper measures, Section 5.1: inference batch size 1, the
+encoder included in the time of an example) on a backbone-shaped model with random weights: targets of
+S subsequences of M tokens, S and M the rounded averages of a dataset of Table 1, sequentially (one
+subsequence of S*M tokens) and pipelined; reports examples per second and the speed-up.
 """
 
 import argparse
@@ -188,6 +195,57 @@ def main_ragged(args):
     return rows
 
 
+def main_encdec(args):
+    import numpy as np
+    import torch
+    import pd_inputs as pi
+    from paper_2506_23431_amd.binding import EncDecPipelinedDecoder
+
+    base = pi.ENCDEC_CONFIGS[args.encdec]
+    if args.layers:
+        base = base.scaled(n_enc_layer=args.layers, n_dec_layer=args.layers)
+    mean_n, mean_words = RAGGED[args.shape]
+    S, M = max(1, round(mean_n)), max(1, round(mean_words * TOKENS_PER_WORD))
+    N = S * M
+    plans = [(1, 1, N)] + [(S, dt, M) for dt in [int(x) for x in args.dt_list.split(",")]]
+    _, weights = pi.encdec_to_bf16(pi.make_encdec_weights(base, threads=8))
+    ctx = pi.make_context(base)
+    rows = []
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        dec = EncDecPipelinedDecoder(base, weights, max_batch=base.batch, max_ctx=base.ctx_len, max_sub=S,
+                                     max_sub_tokens=N)
+        if args.attn_splits:
+            from paper_2506_23431_amd import binding
+            dec.set_option(binding.PD_OPT_ATTN_SPLITS, args.attn_splits)
+        for s_, dt, m_ in plans:
+            T = (s_ - 1) * dt + m_
+            enc_s, dec_s = [], []
+            for _ in range(args.repeats + 1):           # the first pass warms up and is dropped
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                dec.prefill_context(ctx, s_, dt, m_, T)
+                torch.cuda.synchronize()
+                t1 = time.perf_counter()
+                dec.decode_steps(T)
+                torch.cuda.synchronize()
+                t2 = time.perf_counter()
+                enc_s.append(t1 - t0)
+                dec_s.append(t2 - t1)
+            e, d_ = float(np.median(enc_s[1:])), float(np.median(dec_s[1:]))
+            rows.append({"S": s_, "dt": dt, "M": m_, "steps": T, "encode_ms": e * 1e3, "ms_per_step": d_ / T * 1e3,
+                         "examples_per_s": base.batch / (e + d_), "tokens_per_s": base.batch * N / (e + d_)})
+            print(f"S={s_:3d} dt={dt:2d} M={m_:4d}: {T:4d} steps, encode {e * 1e3:6.2f} ms, {d_ / T * 1e3:6.3f} ms/step, "
+                  f"{base.batch / (e + d_):7.2f} examples/s", flush=True)
+        dec.close()
+    for r in rows:
+        r["speedup_vs_sequential"] = r["examples_per_s"] / rows[0]["examples_per_s"]
+    print(json.dumps({"workload": base.name, "layers": [base.n_enc_layer, base.n_dec_layer], "d_model": base.d_model,
+                      "input_tokens": base.ctx_len, "batch": base.batch, "shape": args.shape,
+                      "target_tokens": N, "results": rows}))
+    return rows
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", default="cfg4")
@@ -200,7 +258,15 @@ def main(argv=None):
     ap.add_argument("--ragged", default="", choices=[""] + sorted(RAGGED),
                     help="uneven targets drawn around this dataset's averages (Table 1), <eos>-terminated")
     ap.add_argument("--targets", type=int, default=8, help="ragged mode: seeded targets per request slot")
+    ap.add_argument("--encdec", default="", help="encoder-decoder form on this shape (encdec-small, encdec-base, encdec-large)")
+    ap.add_argument("--shape", default="pubmed", choices=sorted(RAGGED), help="encoder-decoder mode: target shape (Table 1 averages)")
+    ap.add_argument("--repeats", type=int, default=5, help="encoder-decoder mode: timed passes per schedule (median)")
+    ap.add_argument("--attn-splits", type=int, default=0, help="encoder-decoder mode: work-groups per (request, head) in the attention kernel (0: automatic)")
     args = ap.parse_args(argv)
+    if args.encdec:
+        if args.dt_list == "1,2,4,8,16":
+            args.dt_list = "1,2,3"
+        return main_encdec(args)
     if args.kv_pair_layers is None:
         args.kv_pair_layers = -1
     if args.ragged:

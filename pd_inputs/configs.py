@@ -121,3 +121,18 @@ class EncDecConfig:
 
     def scaled(self, **kw) -> "EncDecConfig":
         return replace(self, **kw)
+
+
+def _encdec(name, seed, layers, d, heads, ff):
+    return EncDecConfig(name=name, seed=seed, n_enc_layer=layers, n_dec_layer=layers, d_model=d, n_head=heads,
+                        head_dim=64, d_ff=ff, vocab=32128, rel_buckets=32, rel_max_distance=128, ctx_len=512,
+                        n_sub=8, delta_t=1, sub_tokens=16, batch=1)
+
+
+# Shapes of the backbone family the paper runs (Section 5.1: the base and the large size; inference
+# batch size 1); weights are random, only the dimensions are the family's published ones.
+ENCDEC_CONFIGS = {
+    "encdec-small": _encdec("encdec-small", 71, 6, 512, 8, 2048),
+    "encdec-base": _encdec("encdec-base", 72, 12, 768, 12, 3072),
+    "encdec-large": _encdec("encdec-large", 73, 24, 1024, 16, 4096),
+}

@@ -105,6 +105,57 @@ def test_create_rejects_bad_arguments_without_touching_the_gpu(lib):
     assert lib.pd_decode_steps(None, 1, None) == -1
 
 
+def encdec_struct(cfg, **over):
+    from paper_2506_23431_amd.binding import PdEncDecConfig
+    f = dict(n_enc_layer=cfg.n_enc_layer, n_dec_layer=cfg.n_dec_layer, d_model=cfg.d_model, n_head=cfg.n_head,
+             head_dim=cfg.head_dim, d_ff=cfg.d_ff, vocab=cfg.vocab, rel_buckets=cfg.rel_buckets,
+             rel_max_distance=cfg.rel_max_distance, norm_eps=cfg.norm_eps, bos_id=cfg.bos_id, eos_id=cfg.eos_id,
+             max_batch=cfg.batch, max_ctx=cfg.ctx_len, max_sub=cfg.n_sub, max_sub_tokens=cfg.sub_tokens)
+    f.update(over)
+    return PdEncDecConfig(**f)
+
+
+def test_encoder_decoder_configurations(lib):
+    """Workspace sizes of the backbone-shaped encoder-decoder workloads (they hold the re-packed weights of
+    both stacks and two caches per decoder layer), and what the form does not take."""
+    from paper_2506_23431_amd.binding import PdEncDecWeights
+    for name, cfg in pi.ENCDEC_CONFIGS.items():
+        n = lib.pd_encdec_workspace_bytes(C.byref(encdec_struct(cfg)))
+        d, ff, V = cfg.d_model, cfg.d_ff, cfg.vocab
+        packed = 2 * (cfg.n_enc_layer * (4 * d * d + 2 * d * ff) + cfg.n_dec_layer * (8 * d * d + 2 * d * ff) + V * d)
+        assert packed < n < packed + (256 << 20), (name, n, packed)
+    cfg = pi.ENCDEC_CONFIGS["encdec-small"]
+    for bad in (dict(head_dim=48, n_head=16, d_model=768), dict(rel_max_distance=129), dict(rel_buckets=30),
+                dict(rel_max_distance=16), dict(max_ctx=4097), dict(n_head=32, head_dim=16), dict(n_enc_layer=0),
+                dict(d_ff=2000), dict(bos_id=cfg.vocab), dict(norm_eps=0.0)):
+        assert lib.pd_encdec_workspace_bytes(C.byref(encdec_struct(cfg, **bad))) == 0, bad
+        assert len(lib.pd_last_error()) > 0
+    out = C.c_void_p()
+    c, w = encdec_struct(cfg), PdEncDecWeights()
+    need = lib.pd_encdec_workspace_bytes(C.byref(c))
+    assert lib.pd_encdec_create(C.byref(c), None, None, 0, None, C.byref(out)) == -1
+    assert lib.pd_encdec_create(C.byref(c), C.byref(w), 256, 16, None, C.byref(out)) == -3
+    assert lib.pd_encdec_create(C.byref(c), C.byref(w), 256, need, None, C.byref(out)) == -1
+    assert b"weight pointer is NULL" in lib.pd_last_error()
+
+
+def test_encdec_device_weights_are_the_rounded_ones():
+    """The two views pd_inputs hands out of one set of encoder-decoder weights (bit patterns for the
+    library, rounded values for the oracle) describe the same numbers, with the projections stacked in the
+    order the header states."""
+    cfg = pi.EncDecConfig(name="t", seed=3, n_enc_layer=1, n_dec_layer=1, d_model=32, n_head=1, head_dim=32, d_ff=32,
+                          vocab=11)
+    w = pi.make_encdec_weights(cfg)
+    rounded, device = pi.encdec_to_bf16(w)
+    dl, rl = device["dec_layers"][0], rounded["dec_layers"][0]
+    assert np.array_equal(pi.bits_to_f32(dl["wqkv"]), np.concatenate([rl["wq"], rl["wk"], rl["wv"]]))
+    assert np.array_equal(pi.bits_to_f32(dl["ckv"]), np.concatenate([rl["ck"], rl["cv"]]))
+    assert np.array_equal(pi.bits_to_f32(device["tok_emb"]), rounded["tok_emb"])
+    assert np.array_equal(pi.bits_to_f32(device["enc_layers"][0]["w1"]), rounded["enc_layers"][0]["w1"])
+    assert np.abs(rounded["lm_head"] - w["lm_head"]).max() <= np.abs(w["lm_head"]).max() * 2.0 ** -8
+    assert rl["norm3_g"] is w["dec_layers"][0]["norm3_g"] and device["dec_rel_bias"].dtype == np.float32
+
+
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     from paper_2506_23431_amd import binding
     monkeypatch.setattr(binding, "_lib", None)
