@@ -17,7 +17,9 @@ Modules
                   boolean attention matrix of Fig. 3b
   splitk.py       log-sum-exp merge of softmax partials (exact identity used by the GPU)
   encdec.py       the encoder-decoder form the paper itself runs (Eq. 1 encoder states, cross-attention,
-                  bucketed relative-position bias on the Manhattan distance of Section 4.3); oracle only
+                  bucketed relative-position bias on the Manhattan distance of Section 4.3)
+  training.py     the teacher-forced forward of Section 3.3: the training target of Eq. 5 fed whole under
+                  the matrix of Fig. 3b, and the loss of Eq. 6
 
 Parity status: the logit VALUES on random weights are printed nowhere in the
 paper; they are pinned by (a) an independent dense transformer written with
