@@ -201,6 +201,28 @@ size_t pd_encdec_workspace_bytes(const pd_encdec_config *cfg);
 int pd_encdec_create(const pd_encdec_config *cfg, const pd_encdec_weights *w, void *dev_workspace,
                      size_t bytes, void *hip_stream, pd_ctx **out);
 
+/* Teacher-forced forward of Section 3.3 over the contexts encoded by the last pd_prefill_context (whose
+ * n_sub and delta_t fix the grid): every token of the training targets of Eq. 5 is fed at its grid
+ * coordinate tau = (i-1) delta_t + 1 + j in ONE pass per request under the matrix of Fig. 3b (a token sees
+ * the whole input and the target tokens of subsequences i' <= i at times tau' <= tau), and the loss of
+ * Eq. 6 is returned: the sum of -log P(next token) over every token that has a successor in its
+ * subsequence.  Reading: the closing token of a subsequence has no term of its own but is a key for later
+ * tokens, as Algorithm 1 feeds a finished subsequence's last token once.
+ *   target       host int32 [B][n_sub][max_len]: subsequence i of request b as fed, normally <bos>, Y_i,
+ *                <eos> (and the terminal <bos>, <eos>), padded with -1; empty subsequences only at the end;
+ *                max_len <= max_sub_tokens + 2, and a request's tokens must fit its generated-side cache
+ *                (n_sub * (max_sub_tokens + 1)) and one pass of rows
+ *   out_logits   DEVICE fp32 [B][rows_cap][vocab]: logits of every target token of request b in
+ *                subsequence-major order (row of token j of subsequence i = tokens of the subsequences
+ *                before i, plus j); rows behind a request's last token are left untouched
+ *   out_row_nll  host fp32 [B][rows_cap] or NULL: the term of every row (0 for rows without a successor)
+ *   out_loss     host fp64 [B]: Eq. 6 per request (terms added in row order)
+ *   out_rows     host int32 [B] or NULL: rows of each request
+ * Decoder-only contexts on the matrix-core kernels only.  Uses the generated side of the KV caches and the
+ * schedule state as scratch and leaves the context at t = 0, as pd_reset_decode does.  Synchronises. */
+int pd_teacher_forced(pd_ctx *ctx, const int32_t *target, int max_len, float *out_logits, int rows_cap,
+                      float *out_row_nll, double *out_loss, int32_t *out_rows, void *hip_stream);
+
 /* Runs `n_steps` decode steps (no host inputs or outputs) back to back on the
  * stream; used for timing.  Does not synchronise. */
 int pd_decode_steps(pd_ctx *ctx, int n_steps, void *hip_stream);

@@ -18,7 +18,7 @@ PD_INFO_KERNEL_PATH, PD_INFO_KV_PAIR_LAYERS, PD_INFO_KV_SATURATED = 1, 2, 3
 
 EXPORTS = ["pd_workspace_bytes", "pd_create", "pd_destroy", "pd_prefill_context", "pd_decode_step",
            "pd_generate", "pd_generate_static", "pd_decode_steps", "pd_reset_decode", "pd_set_option", "pd_profile_read",
-           "pd_measure_read_bandwidth", "pd_get_info", "pd_last_error", "pd_encdec_workspace_bytes", "pd_encdec_create"]
+           "pd_measure_read_bandwidth", "pd_get_info", "pd_last_error", "pd_encdec_workspace_bytes", "pd_encdec_create", "pd_teacher_forced"]
 
 
 class PdError(RuntimeError):
@@ -87,6 +87,8 @@ def load():
     lib.pd_measure_read_bandwidth.argtypes = [vp, C.c_size_t, C.c_size_t, C.c_int, vp, C.POINTER(C.c_double)]
     lib.pd_get_info.argtypes = [vp, C.c_int, vp, C.POINTER(C.c_int64)]
     lib.pd_last_error.restype = C.c_char_p
+    lib.pd_teacher_forced.argtypes = [vp, i32p, C.c_int, vp, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_double),
+                                      i32p, vp]
     lib.pd_encdec_workspace_bytes.restype = C.c_size_t
     lib.pd_encdec_workspace_bytes.argtypes = [C.POINTER(PdEncDecConfig)]
     lib.pd_encdec_create.argtypes = [C.POINTER(PdEncDecConfig), C.POINTER(PdEncDecWeights), vp, C.c_size_t, vp,
@@ -233,6 +235,30 @@ class PipelinedDecoder:
                                     steps.ctypes.data_as(i32p), self._stream()))
         self.B, self.S, self.M = B, n_sub, sub_tokens
         return toks, lens, steps
+
+    def teacher_forced(self, targets):
+        """pd_teacher_forced.  targets: per request a list of subsequences (lists of token ids as fed:
+        <bos>, Y_i, <eos>).  Returns (logits: per request a torch fp32 [rows][V] in subsequence-major
+        order, nll: per request float32 [rows], loss float64 [B])."""
+        assert len(targets) == self.B
+        max_len = max(len(s) for t in targets for s in t)
+        rows_cap = max(sum(len(s) for s in t) for t in targets)
+        arr = np.full((self.B, self.S, max_len), -1, dtype=np.int32)
+        for b, t in enumerate(targets):
+            assert len(t) <= self.S
+            for i, s in enumerate(t):
+                arr[b, i, :len(s)] = s
+        logits = self.torch.full((self.B, rows_cap, self.vocab), float("nan"), dtype=self.torch.float32,
+                                 device=self.device)
+        nll = np.zeros((self.B, rows_cap), dtype=np.float32)
+        loss = np.zeros((self.B,), dtype=np.float64)
+        rows = np.zeros((self.B,), dtype=np.int32)
+        i32p = C.POINTER(C.c_int32)
+        _check(self.lib.pd_teacher_forced(self.ctx, arr.ctypes.data_as(i32p), max_len, C.c_void_p(logits.data_ptr()),
+                                          rows_cap, nll.ctypes.data_as(C.POINTER(C.c_float)),
+                                          loss.ctypes.data_as(C.POINTER(C.c_double)), rows.ctypes.data_as(i32p),
+                                          self._stream()))
+        return [logits[b, :rows[b]] for b in range(self.B)], [nll[b, :rows[b]] for b in range(self.B)], loss
 
     # -- helpers ---------------------------------------------------------------
     def decode_steps(self, n):

@@ -32,11 +32,17 @@ struct AttnArgs {
   float *part;
   int d, H, kv_cap, gen_stride, L, A, nqg, req0, nsplit, nblk_static;
   float scale_log2;         // log2(e) / sqrt(hd)
-  // BIAS kernels (relative-position bias of the encoder-decoder form, Section 4.3): the score of query
-  // r and key j gets bias[h][clamp(pos[r] - coord[j] + bias_off, 0, bias_len - 1)] (already times
-  // log2(e)); coord[j] of key slot j is read at coord[req * coord_req_stride + j]
+  // BIAS kernels: every key slot j carries a grid coordinate, coord[req * coord_req_stride + j - coord_off]
+  // = (tau - 1) + (i - 1) for a generated-side token (the encoder: its position), and a query has
+  // c_q = pos[r] - pos0.
+  //  * relative-position bias of the encoder-decoder form (Section 4.3): the score gets
+  //    bias[h][clamp(c_q - coord[j] + bias_off, 0, bias_len - 1)] (already times log2(e));
+  //  * a generated-side key is visible only if it is not later than the query, tau_k <= tau_q, beside
+  //    the subsequence rule.  In a decode step that holds for every key in the cache; in the one-pass
+  //    teacher-forced forward (Fig. 3b) all of the target's keys are there at once and this is the
+  //    time half of the matrix.  tau - 2 = coordinate - subsequence tag on both sides.
   const float *bias; const uint16_t *coord;
-  int bias_len, bias_off, coord_stride, coord_req_stride;
+  int bias_len, bias_off, coord_stride, coord_req_stride, coord_off, pos0;
 };
 constexpr int BIAS_MAX = 264;   // entries of one head's bias table that the kernel keeps in LDS
 
@@ -66,7 +72,7 @@ __global__ __launch_bounds__(256, PAIR ? 1 : 3) void k_attn_mfma(AttnArgs a) {
   int q_pos = 0;
   float bias_pre[2] = {0.f, 0.f};
   if (BIAS) {
-    q_pos = a.rt.pos[r];
+    q_pos = a.rt.pos[r] - a.pos0;
     bias_pre[0] = a.bias[(size_t)h * a.bias_len + min((int)threadIdx.x, a.bias_len - 1)];
     bias_pre[1] = a.bias[(size_t)h * a.bias_len + min((int)threadIdx.x + 256, a.bias_len - 1)];
   }
@@ -112,7 +118,7 @@ __global__ __launch_bounds__(256, PAIR ? 1 : 3) void k_attn_mfma(AttnArgs a) {
   auto load_v = [&](int kbx) {
     // tags of the lane's 8 keys (clamped: context blocks read entry 0 and never use it)
     tg.u = *(const uint4 *)(gs + min(max(kbx * 32 + 8 * g - L8, 0), a.gen_stride - 8));
-    if (BIAS) kco.u = *(const uint4 *)(kcp + min(kbx * 32 + 8 * g, a.coord_stride - 8));
+    if (BIAS) kco.u = *(const uint4 *)(kcp + min(max(kbx * 32 + 8 * g - a.coord_off, 0), a.coord_stride - 8));
 #pragma unroll
     for (int i = 0; i < NHB; ++i) {
       vf[i].u = Vp[((size_t)kbx * NHB + i) * 64];
@@ -199,7 +205,8 @@ __global__ __launch_bounds__(256, PAIR ? 1 : 3) void k_attn_mfma(AttnArgs a) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         int key = key0 + e;
-        bool vis = (key < q_lim) | ((key >= a.L) & (key < n_keys) & ((int)tg.s[e] <= q_sub));
+        bool vis = (key < q_lim) | ((key >= a.L) & (key < n_keys) & ((int)tg.s[e] <= q_sub) &
+                                    (!BIAS || (int)kco.s[e] - (int)tg.s[e] <= q_pos - q_sub));
         sv[e] = vis ? (BIAS ? s[e >> 2][e & 3] * a.scale_log2 + bv[e] : s[e >> 2][e & 3] * a.scale_log2) : -INFINITY;
       }
     }
@@ -383,6 +390,7 @@ int mfma_attention(pd_ctx *c, const LayerPtrs &lw, int A, int nreq, int req0, in
                  PD_EINVAL, "relative-position bias table of %d entries (at most %d)", mode->bias_len, BIAS_MAX);
       a.bias = mode->bias; a.coord = mode->coord; a.bias_len = mode->bias_len; a.bias_off = mode->bias_off;
       a.coord_stride = mode->coord_stride; a.coord_req_stride = mode->coord_req_stride;
+      a.coord_off = mode->coord_off; a.pos0 = mode->pos0;
     }
   }
   int units = nreq * a.nqg * g.n_head;

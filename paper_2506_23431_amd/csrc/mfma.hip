@@ -75,7 +75,8 @@ int mfma_out_ffn(pd_ctx *c, GemmArgs &a, const bf16_t *p_wo, const LayerPtrs &lw
   return mfma_gemm(EPI_RESID, a, R, s);
 }
 
-int mfma_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_override, hipStream_t s) {
+int mfma_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_override, hipStream_t s,
+               const AttnMode *mode) {
   const pd_config &g = c->cfg;
   const LayerPtrs &lw = c->layers[l];
   int rc;
@@ -86,12 +87,12 @@ int mfma_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_overri
   if ((rc = mfma_qkv(c, a, lw.p_wqkv, 3 * g.d_model / 16, 0, lw.kc, lw.vc, lw.kc_lo, lw.vc_lo, R, s))) return rc;
   // context pass, last layer: only its keys and values are ever used (nothing reads the residual
   // stream of a context token after the last layer)
-  if (kv_override >= 0 && l == g.n_layer - 1) return PD_OK;
-  if ((rc = mfma_attention(c, lw, A, nreq, req0, kv_override, s))) return rc;
+  if (kv_override >= 0 && l == g.n_layer - 1 && !mode) return PD_OK;
+  if ((rc = mfma_attention(c, lw, A, nreq, req0, kv_override, s, mode))) return rc;
   return mfma_out_ffn(c, a, lw.p_wo, lw, R, s);
 }
 
-int mfma_head(pd_ctx *c, int R, bool want_logits, hipStream_t s) {
+int mfma_head(pd_ctx *c, int R, bool want_logits, hipStream_t s, float *logits_to) {
   const pd_config &g = c->cfg;
   int rc;
   if ((rc = mfma_norm(c, c->fng, c->fnb, R, s))) return rc;
@@ -100,7 +101,7 @@ int mfma_head(pd_ctx *c, int R, bool want_logits, hipStream_t s) {
   a.R = R; a.rt = c->rows; a.W = c->p_lm_head; a.xn = (const bf16_t *)c->xn; a.packed = c->packed;
   a.xn_lo = mfma_lo(c, c->xn, g.d_model); a.K = g.d_model;
   a.n_tiles = c->vocab_pad / 16; a.V = g.vocab;
-  a.logits = want_logits ? c->logits : nullptr; a.ld_logits = g.vocab;
+  a.logits = want_logits ? (logits_to ? logits_to : c->logits) : nullptr; a.ld_logits = g.vocab;
   a.part_val = c->lm_part_val; a.part_idx = c->lm_part_idx;
   // leaves one winner per 16-column tile; the commit kernel picks the winner of each row
   return mfma_gemm(EPI_LM, a, R, s);

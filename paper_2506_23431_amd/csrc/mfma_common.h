@@ -149,10 +149,12 @@ struct AttnMode {
   const int4 *qinfo;       // {flags, sub, lim, req} per row (NULL: the step's row table)
   int L;                   // keys below L are visible up to a row's limit, keys from L on by their tags
   float scale;             // factor on q.k
-  // relative-position bias (NULL: none): bias[h][clamp(pos[row] - coord[key] + bias_off, 0, bias_len - 1)],
-  // already times log2(e); coord[key] at coord[req * coord_req_stride + key], coord_stride entries readable
+  // Grid coordinates (bias NULL: none, the plain kernel).  coord[key] at coord[req * coord_req_stride +
+  // key - coord_off], coord_stride entries readable; a query's coordinate is pos[row] - pos0.  The score
+  // gets bias[h][clamp(c_q - coord[key] + bias_off, 0, bias_len - 1)] (already times log2(e); a table of
+  // one zero: no bias), and generated-side keys later than the query are masked.
   const float *bias; const uint16_t *coord;
-  int bias_len, bias_off, coord_stride, coord_req_stride;
+  int bias_len, bias_off, coord_stride, coord_req_stride, coord_off, pos0;
 };
 int mfma_attention(pd_ctx *c, const LayerPtrs &lw, int A, int nreq, int req0, int kv_override,
                    hipStream_t s, const AttnMode *mode = nullptr);

@@ -8,7 +8,7 @@
 #include <mutex>
 #include <new>
 
-#include "pd_internal.h"
+#include "mfma_common.h"
 
 static thread_local char g_err[512] = "no error";
 
@@ -134,8 +134,11 @@ static size_t carve(const pd_config *g, char *base, pd_ctx *c, const pd_encdec_c
     ed.enc_bias = cv.take<float>((size_t)H * ed.enc_len);
     ed.dec_bias = cv.take<float>((size_t)H * ed.dec_len);
     ed.enc_coord = cv.take<uint16_t>(x->kv_cap);
-    x->gen_coord = cv.take<uint16_t>((size_t)B * x->gen_stride);
   }
+  x->gen_coord = cv.take<uint16_t>((size_t)B * x->gen_stride);
+  x->bias0 = cv.take<float>(H);
+  x->loss = cv.take<double>(B);
+  x->tf_target = cv.take<int32_t>((size_t)B * S * (M + 2));
   size_t Rp = x->R_pad;
   x->x = cv.take<float>(Rp * d);
   x->xn = cv.take<float>(Rp * d);
@@ -158,6 +161,7 @@ static size_t carve(const pd_config *g, char *base, pd_ctx *c, const pd_encdec_c
   x->lm_part_val = cv.take<float>((size_t)x->lm_parts * Rp);
   x->lm_part_idx = cv.take<int32_t>((size_t)x->lm_parts * Rp);
   x->row_argmax = cv.take<int32_t>(Rp);
+  x->nll = cv.take<float>(Rp);
   x->rope_rows = g->pos_kind == 1 ? g->max_pos : 0;
   x->rope_cs = g->pos_kind == 1 ? cv.take<float>((size_t)x->rope_rows * hd) : nullptr;
   RowTables &rt = x->rows;
@@ -648,6 +652,80 @@ extern "C" int pd_decode_steps(pd_ctx *c, int n_steps, void *hip_stream) {
     if (rc) return rc;
     c->host_steps++;
   }
+  return PD_OK;
+}
+
+// ---------------------------------------------------------------------------
+// teacher-forced forward (Section 3.3)
+// ---------------------------------------------------------------------------
+extern "C" int pd_teacher_forced(pd_ctx *c, const int32_t *target, int max_len, float *out_logits, int rows_cap,
+                                 float *out_row_nll, double *out_loss, int32_t *out_rows, void *hip_stream) {
+  PD_REQUIRE(c && target && out_logits && out_loss, PD_EINVAL, "ctx, target, out_logits or out_loss is NULL");
+  PD_REQUIRE(c->prefilled, PD_ESTATE, "pd_teacher_forced before pd_prefill_context");
+  PD_REQUIRE(c->arch == 0 && c->impl == 1, PD_EINVAL,
+             "the teacher-forced forward runs on decoder-only contexts of the matrix-core kernels (dtype 1, head_dim, "
+             "d_model, d_ff multiples of 32)");
+  const pd_config &g = c->cfg;
+  const int B = c->B, S = c->S, L = c->L;
+  PD_REQUIRE(max_len >= 1 && max_len <= g.max_sub_tokens + 2, PD_EINVAL, "max_len = %d out of range [1, %d]", max_len,
+             g.max_sub_tokens + 2);
+  std::vector<int> rows(B, 0);
+  for (int b = 0; b < B; ++b) {
+    bool ended = false;
+    for (int i = 0; i < S; ++i) {
+      const int32_t *t = target + ((size_t)b * S + i) * max_len;
+      int n = 0;
+      while (n < max_len && t[n] >= 0) ++n;
+      for (int j = 0; j < max_len; ++j) {
+        PD_REQUIRE(t[j] < g.vocab, PD_EINVAL, "request %d subsequence %d token %d = %d out of range", b, i, j, t[j]);
+        PD_REQUIRE(j < n || t[j] < 0, PD_EINVAL, "request %d subsequence %d: token after the padding", b, i);
+      }
+      PD_REQUIRE(!(ended && n > 0), PD_EINVAL, "request %d: subsequence %d follows an empty one", b, i);
+      ended = ended || n == 0;
+      if (n > 0) {
+        int64_t coord = (int64_t)i * c->dt + (n - 1) + i;
+        PD_REQUIRE(coord < 65536 && (g.pos_kind == 1 ? coord + L < (int64_t)c->rope_rows : coord + L < g.max_pos),
+                   PD_EINVAL, "request %d subsequence %d: position index %lld out of range", b, i, (long long)(coord + L));
+      }
+      rows[b] += n;
+    }
+    PD_REQUIRE(rows[b] >= 1, PD_EINVAL, "request %d has an empty target", b);
+    PD_REQUIRE(rows[b] <= c->gen_cap && rows[b] <= c->R_cap && rows[b] <= rows_cap, PD_EINVAL,
+               "request %d: %d target tokens exceed the capacity (%d cache slots, %d rows per pass, %d rows of out_logits)",
+               b, rows[b], c->gen_cap, c->R_cap, rows_cap);
+  }
+  hipStream_t s = (hipStream_t)hip_stream;
+  drop_graph(c);
+  PD_CHECK_HIP(hipMemcpyAsync(c->tf_target, target, sizeof(int32_t) * (size_t)B * S * max_len, hipMemcpyHostToDevice, s));
+  PD_CHECK_HIP(hipStreamSynchronize(s));
+  AttnMode am;
+  memset(&am, 0, sizeof(am));
+  am.L = L; am.scale = 1.f / sqrtf((float)g.head_dim);
+  am.bias = c->bias0; am.bias_len = 1; am.bias_off = 0;
+  am.coord = c->gen_coord; am.coord_stride = c->gen_stride; am.coord_req_stride = c->gen_stride;
+  am.coord_off = L & ~7; am.pos0 = L;
+  int rc;
+  std::vector<float> nll_host;
+  for (int b = 0; b < B; ++b) {
+    const int n = rows[b];
+    if ((rc = launch_teacher_rows(c, c->tf_target, b, max_len, s))) return rc;
+    c->packed = false; c->embed_pending = true; c->pend_parts = 0;
+    for (int l = 0; l < g.n_layer; ++l)
+      if ((rc = mfma_layer(c, l, n, n, 1, b, L + n, s, &am))) return rc;
+    float *lg = out_logits + (size_t)b * rows_cap * g.vocab;
+    if ((rc = mfma_head(c, n, true, s, lg))) return rc;
+    if ((rc = launch_row_nll(c, lg, n, c->loss + b, s))) return rc;
+    if (out_row_nll) {
+      PD_CHECK_HIP(hipMemcpyAsync(out_row_nll + (size_t)b * rows_cap, c->nll, sizeof(float) * n, hipMemcpyDeviceToHost, s));
+      PD_CHECK_HIP(hipStreamSynchronize(s));        // c->nll is reused by the next request
+    }
+  }
+  PD_CHECK_HIP(hipMemcpyAsync(out_loss, c->loss, sizeof(double) * B, hipMemcpyDeviceToHost, s));
+  // the generated side of the caches and the schedule state were used as scratch: back to t = 0
+  c->host_steps = 0;
+  if ((rc = launch_reset_state(c, s))) return rc;
+  PD_CHECK_HIP(hipStreamSynchronize(s));
+  if (out_rows) for (int b = 0; b < B; ++b) out_rows[b] = rows[b];
   return PD_OK;
 }
 

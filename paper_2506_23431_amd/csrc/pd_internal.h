@@ -168,6 +168,11 @@ struct pd_ctx {
   EncDecState ed;
   uint16_t *gen_coord;      // [B][gen_stride] grid coordinate (t - 1) + (i - 1) of each generated-side KV slot
   int4 *qinfo_x;            // [R] row table of the attention over the encoder states
+  // teacher-forced forward (Section 3.3)
+  float *bias0;             // [H] zeros: the one-entry "no bias" table of the kernels that carry coordinates
+  float *nll;               // [R_pad] loss term of each row
+  double *loss;             // [B]
+  int32_t *tf_target;       // [B][S][M + 2] device copy of the training targets
   bool prefilled;
   int host_steps;           // decode steps enqueued since prefill/reset
   // options
@@ -185,6 +190,8 @@ int launch_tick(pd_ctx *c, hipStream_t s);
 int launch_prefill_rows(pd_ctx *c, int b, int p0, int n, hipStream_t s, int L, int bidir, int b_cache);
 int launch_embed(pd_ctx *c, int R, hipStream_t s);
 int launch_commit(pd_ctx *c, float *out_logits, hipStream_t s);
+int launch_teacher_rows(pd_ctx *c, const int32_t *tgt_dev, int b, int ML, hipStream_t s);
+int launch_row_nll(pd_ctx *c, const float *logits, int n, double *loss_dev, hipStream_t s);
 int launch_rope_table(pd_ctx *c, hipStream_t s);
 // fp32-activation path (simple.hip)
 int simple_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_override, hipStream_t s);
@@ -192,8 +199,12 @@ int simple_head(pd_ctx *c, int R, hipStream_t s);
 // MFMA path (mfma.hip)
 int mfma_pack_weights(pd_ctx *c, hipStream_t s);
 int mfma_fold_norms(pd_ctx *c, hipStream_t s);
-int mfma_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_override, hipStream_t s);
-int mfma_head(pd_ctx *c, int R, bool want_logits, hipStream_t s);
+struct AttnMode;
+// mode != NULL: not a context pass (every layer runs to its end) and the attention launch takes the mode
+int mfma_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_override, hipStream_t s,
+               const AttnMode *mode = nullptr);
+// logits_to != NULL: the logits of the R rows go there ([R][vocab]) instead of the internal buffer
+int mfma_head(pd_ctx *c, int R, bool want_logits, hipStream_t s, float *logits_to = nullptr);
 // encoder-decoder form (encdec.hip)
 int encdec_pack_weights(pd_ctx *c, hipStream_t s);
 int encdec_build_tables(pd_ctx *c, int *scratch, hipStream_t s);

@@ -156,6 +156,99 @@ int launch_prefill_rows(pd_ctx *c, int b, int p0, int n, hipStream_t s, int L, i
 }
 
 // ---------------------------------------------------------------------------
+// teacher-forced rows (Section 3.3, Fig. 3b): every token of request b's training target as one row,
+// subsequence-major (row of token j of subsequence i: the lengths before i, plus j), at the grid
+// coordinate Algorithm 1 would feed it, tau = (i-1) dt + 1 + j.  tgt: [B][S][ML] token ids, -1 behind a
+// subsequence's last token.  Row r writes key slot L + r with its subsequence tag and coordinate;
+// next_tok[r] is the token that follows it (-1 behind the last one: a key, but no loss term).
+// One block; the schedule state of the request is used as scratch and is reset by the caller afterwards.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_teacher_rows(RowTables rt, SchedState st, uint16_t *gen_coord,
+                                                      int32_t *next_tok, const int32_t *tgt, int b, int S, int ML,
+                                                      int dt, int L, int gen_stride, int R_cap) {
+  const int32_t *tb = tgt + (size_t)b * S * ML;
+  int32_t *len = st.n_tok + (size_t)b * S, *off = st.n_fed + (size_t)b * S;
+  for (int i = threadIdx.x; i < S; i += blockDim.x) {
+    int n = 0;
+    while (n < ML && tb[(size_t)i * ML + n] >= 0) ++n;
+    len[i] = n;
+  }
+  __syncthreads();
+  __shared__ int s_total;
+  if (threadIdx.x == 0) {
+    int acc = 0;
+    for (int i = 0; i < S; ++i) { off[i] = acc; acc += len[i]; }
+    s_total = acc;
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < S; i += blockDim.x) {
+    for (int j = 0; j < len[i]; ++j) {
+      const int r = off[i] + j;
+      if (r >= R_cap) break;
+      const bool more = j + 1 < len[i];
+      const int fl = ROW_VALID | (more ? ROW_PRODUCE : 0), c = (i * dt + j) + i, p = L + c;
+      rt.req[r] = b; rt.sub[r] = i + 1; rt.tok[r] = tb[(size_t)i * ML + j]; rt.pos[r] = p;
+      rt.slot[r] = L + r; rt.lim[r] = L; rt.flags[r] = fl;
+      rt.qinfo[r] = make_int4(fl, i + 1, L, b);
+      rt.kvinfo[r] = make_int4(fl, b, L + r, p);
+      st.gen_sub[(size_t)b * gen_stride + (L & 7) + r] = (uint16_t)(i + 1);
+      gen_coord[(size_t)b * gen_stride + (L & 7) + r] = (uint16_t)c;
+      next_tok[r] = more ? tb[(size_t)i * ML + j + 1] : -1;
+    }
+  }
+  for (int r = s_total + threadIdx.x; r < R_cap; r += blockDim.x) {
+    rt.flags[r] = 0; rt.qinfo[r] = make_int4(0, -1, 0, b); rt.kvinfo[r] = make_int4(0, b, 0, 0);
+    next_tok[r] = -1;
+  }
+}
+
+int launch_teacher_rows(pd_ctx *c, const int32_t *tgt_dev, int b, int ML, hipStream_t s) {
+  hipLaunchKernelGGL(k_teacher_rows, dim3(1), dim3(256), 0, s, c->rows, c->sch, c->gen_coord, c->row_argmax, tgt_dev,
+                     b, c->S, ML, c->dt, c->L, c->gen_stride, c->R_cap);
+  PD_CHECK_HIP(hipGetLastError());
+  return PD_OK;
+}
+
+// Eq. 6, one row per block: nll[r] = log sum_v exp(logits[r][v]) - logits[r][next_tok[r]], 0 for rows
+// without a successor.
+__global__ __launch_bounds__(256) void k_row_nll(float *nll, const float *logits, size_t ld, int V,
+                                                 const int32_t *next_tok) {
+  __shared__ float sh[4];
+  const int r = blockIdx.x, t = next_tok[r];
+  if (t < 0) { if (threadIdx.x == 0) nll[r] = 0.f; return; }      // the same for the whole block
+  const float *row = logits + (size_t)r * ld;
+  float m = -INFINITY;
+  for (int v = threadIdx.x; v < V; v += 256) m = fmaxf(m, row[v]);
+  for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = m;
+  __syncthreads();
+  m = fmaxf(fmaxf(sh[0], sh[1]), fmaxf(sh[2], sh[3]));
+  __syncthreads();
+  float e = 0.f;
+  for (int v = threadIdx.x; v < V; v += 256) e += expf(row[v] - m);
+  for (int o = 32; o > 0; o >>= 1) e += __shfl_xor(e, o);
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = e;
+  __syncthreads();
+  if (threadIdx.x == 0) nll[r] = m + logf((sh[0] + sh[1]) + (sh[2] + sh[3])) - row[t];
+}
+
+// loss of one request: the rows' terms added in row order, in double precision (deterministic)
+__global__ void k_loss_sum(double *loss, const float *nll, int n) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  double acc = 0.0;
+  for (int r = 0; r < n; ++r) acc += (double)nll[r];
+  *loss = acc;
+}
+
+int launch_row_nll(pd_ctx *c, const float *logits, int n, double *loss_dev, hipStream_t s) {
+  hipLaunchKernelGGL(k_row_nll, dim3(n), dim3(256), 0, s, c->nll, logits, (size_t)c->cfg.vocab, c->cfg.vocab,
+                     c->row_argmax);
+  hipLaunchKernelGGL(k_loss_sum, dim3(1), dim3(64), 0, s, loss_dev, c->nll, n);
+  PD_CHECK_HIP(hipGetLastError());
+  return PD_OK;
+}
+
+// ---------------------------------------------------------------------------
 // embedding: x[r] = E_tok[tok] (+ E_pos[pos]); rows without a token are zeroed
 // ---------------------------------------------------------------------------
 template <typename WT>

@@ -129,3 +129,29 @@ def test_planted_mistakes_change_the_loss():
     # (c) targets shifted by one token
     shifted = [s[:1] + s[2:] + s[1:2] for s in tgt]
     assert abs(training.teacher_forced(model, ctx, shifted, 1)[2] - loss) > 1e-6
+
+
+def test_gpu_cases_can_see_a_wrong_matrix():
+    """The GPU parity cases compare logits at 2e-2.  With either half of Fig. 3b's matrix dropped (a token
+    seeing later tokens of lower subsequences, or tokens of higher subsequences), the oracle's own logits on
+    such a case move by far more than that, so a kernel with that mistake cannot pass."""
+    from oracle import matrix_form
+    from test_gpu_parity import CASES
+    from test_gpu_teacher_forced import draw_targets
+    cfg = CASES["mfma-hd64"]
+    w = pi.make_weights(cfg, threads=2)
+    ctx = pi.make_context(cfg)[0]
+    model = OracleModel(cfg, w)
+    tgt = draw_targets(cfg, 1)[0]
+    right, _, _ = training.teacher_forced(model, ctx, tgt, cfg.delta_t)
+    L = len(ctx)
+    coords = matrix_form.coordinates(tgt, cfg.delta_t)
+    tokens = np.concatenate([ctx, [c[2] for c in coords]])
+    pos = np.concatenate([np.arange(L), [L + (t - 1) + (i - 1) for i, t, _ in coords]])
+    for drop in ("time", "subsequence"):
+        mask = matrix_form.attention_matrix(L, coords)
+        for a, (iq, tq, _) in enumerate(coords):
+            for b, (ik, tk, _) in enumerate(coords):
+                mask[L + a, L + b] = (ik <= iq) if drop == "time" else (tk <= tq)
+        wrong = matrix_form.dense_forward(model, tokens, pos, mask)[L:]
+        assert np.abs(wrong - right).max() > 0.06, drop         # three times the bar
