@@ -34,6 +34,8 @@ int encdec_pack_weights(pd_ctx *c, hipStream_t s) {
     if ((rc = mfma_pack_matrix(lp.p_cq, lp.cq, d, d, s))) return rc;
     if ((rc = mfma_pack_matrix(lp.p_ckv, lp.ckv, 2 * d, d, s))) return rc;
     if ((rc = mfma_pack_matrix(lp.p_co, lp.co, d, d, s))) return rc;
+    // the query projection over the encoder states can finish the norm in front of it
+    if ((rc = mfma_fold(lp.cx1, nullptr, lp.p_cq, lp.n3g, nullptr, d, d, s))) return rc;
   }
   return PD_OK;
 }
@@ -99,6 +101,7 @@ int encdec_encode(pd_ctx *c, int b, hipStream_t s) {
   c->packed = false;
   c->embed_pending = true;
   c->pend_parts = 0;
+  c->norm_fused = false;
   AttnMode am;
   memset(&am, 0, sizeof(am));
   am.L = n; am.scale = 1.f;
@@ -141,11 +144,15 @@ int encdec_decoder_layer(pd_ctx *c, int l, int R, hipStream_t s) {
   self.bias = e.dec_bias; self.bias_len = e.dec_len; self.bias_off = 0;
   self.coord = c->gen_coord; self.coord_stride = c->gen_stride; self.coord_req_stride = c->gen_stride;
   if ((rc = mfma_attention(c, lw, c->A, c->B, 0, -1, s, &self))) return rc;
-  if ((rc = mfma_out(c, a, lw.p_wo, R, s))) return rc;
+  // In steps of at most 16 rows the output projection also prepares the norm that follows it and the
+  // query projection behind that norm finishes it (gemm.hip): no norm kernel in between.
+  if ((rc = mfma_out(c, a, lw.p_wo, R, s, lw.n3g))) return rc;
   // attention over the encoder states: queries from the normalised rows, keys and values from the
   // second cache, every one of the Lx keys visible to every row that carries a token
-  if ((rc = mfma_norm(c, lw.n3g, nullptr, R, s))) return rc;
-  if ((rc = mfma_qkv(c, a, lw.p_cq, d / 16, 0, nullptr, nullptr, nullptr, nullptr, R, s))) return rc;
+  const bool finish = c->norm_fused;
+  if (!finish && (rc = mfma_norm(c, lw.n3g, nullptr, R, s))) return rc;
+  if ((rc = mfma_qkv(c, a, lw.p_cq, d / 16, 0, nullptr, nullptr, nullptr, nullptr, R, s, finish ? lw.cx1 : nullptr)))
+    return rc;
   AttnMode cross;
   memset(&cross, 0, sizeof(cross));
   cross.kc = lw.xkc; cross.vc = lw.xvc; cross.qinfo = c->qinfo_x; cross.L = c->Lx; cross.scale = 1.f;

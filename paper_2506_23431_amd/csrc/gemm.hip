@@ -103,14 +103,20 @@ __global__ __launch_bounds__(64) void k_norm_fold(float *c1, float *c2, const bf
   }
 }
 
+int mfma_fold(float *c1, float *c2, const bf16_t *Wp, const float *gain, const float *bias, int n_out, int K,
+              hipStream_t s) {
+  hipLaunchKernelGGL(k_norm_fold, dim3(n_out / 16), dim3(64), 0, s, c1, bias ? c2 : nullptr, Wp, gain, bias, K / 32);
+  PD_CHECK_HIP(hipGetLastError());
+  return PD_OK;
+}
+
 int mfma_fold_norms(pd_ctx *c, hipStream_t s) {
   const pd_config &g = c->cfg;
   const int n_out = (g.ffn_kind == 1 ? 2 : 1) * g.d_ff;
+  int rc;
   for (int l = 0; l < g.n_layer; ++l) {
     LayerPtrs &lp = c->layers[l];
-    hipLaunchKernelGGL(k_norm_fold, dim3(n_out / 16), dim3(64), 0, s, lp.c1, g.norm_kind == 0 ? lp.c2 : nullptr,
-                       lp.p_w1, lp.n2g, g.norm_kind == 0 ? lp.n2b : nullptr, g.d_model / 32);
-    PD_CHECK_HIP(hipGetLastError());
+    if ((rc = mfma_fold(lp.c1, lp.c2, lp.p_w1, lp.n2g, g.norm_kind == 0 ? lp.n2b : nullptr, n_out, g.d_model, s))) return rc;
   }
   return PD_OK;
 }
@@ -269,7 +275,7 @@ int mfma_norm(pd_ctx *c, const float *gain, const float *bias, int R, hipStream_
 // fragments of the row tiles, then the weight fragments of its tiles) into registers of their own;
 // only then the multiplies run.  A share that is not a multiple of U ends with chunks of 4, 2 and
 // 1 k-tiles, so that no load is ever conditional.
-// This file is compiled once per epilogue (PD_GEMM_EPI = 0..6: kernels and launch code of that
+// This file is compiled once per epilogue (PD_GEMM_EPI = 0..7: kernels and launch code of that
 // epilogue) and once without (weight packing, norm kernel, dispatcher).
 // ---------------------------------------------------------------------------
 // epilogue of one 16-column tile: lane holds y[r][n0 + j], r = i*16 + m, n0 = nt*16 + 4g, j = 0..3
@@ -326,7 +332,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int nt, const f
   floatx4 acc[RT];
 #pragma unroll
   for (int i = 0; i < RT; ++i) acc[i] = acc_in[i];
-  if ((EPI == EPI_GELU || EPI == EPI_SWIGLU) && nrm) {
+  if ((EPI == EPI_GELU || EPI == EPI_SWIGLU || EPI == EPI_QKV_NORM) && nrm) {
     // the activations were gain * x: finish the norm here (columns in the packed order of the weights)
     const float4 c1 = npre ? npre->c1 : *(const float4 *)(a.c1 + n0);
     const float4 c2 = npre ? npre->c2 : (a.c2 ? *(const float4 *)(a.c2 + n0) : make_float4(0.f, 0.f, 0.f, 0.f));
@@ -396,7 +402,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int nt, const f
       }
       if (g < 2 && r < a.R) store4_split(a.out_bf, a.out_lo, act_off(r, nt * 8 + 4 * g, a.ld), y);
     }
-  } else if (EPI == EPI_QKV || EPI == EPI_QKV_ROPE) {
+  } else if (EPI == EPI_QKV || EPI == EPI_QKV_ROPE || EPI == EPI_QKV_NORM) {
     int sec = n0 / a.d + a.sec0, nl = n0 % a.d, h = nl / a.hd;
     int half = a.hd >> 1;
 #pragma unroll
@@ -521,8 +527,8 @@ __global__ __launch_bounds__(64 * NW_K) void k_gemm_s(GemmArgs a) {
   const int gk = blockIdx.y * NW_K + wk;
   const int kt0 = min(gk * a.k_share, KT), kt1 = min(kt0 + a.k_share, KT);
   // row data of the KV-append epilogue, requested now so that it arrives with the weights
-  int4 kvi[(EPI == EPI_QKV || EPI == EPI_QKV_ROPE) ? RT : 1];
-  if (EPI == EPI_QKV || EPI == EPI_QKV_ROPE) {
+  int4 kvi[(EPI == EPI_QKV || EPI == EPI_QKV_ROPE || EPI == EPI_QKV_NORM) ? RT : 1];
+  if (EPI == EPI_QKV || EPI == EPI_QKV_ROPE || EPI == EPI_QKV_NORM) {
 #pragma unroll
     for (int i = 0; i < RT; ++i) kvi[i] = a.rt.kvinfo[i * 16 + m];
   }
@@ -530,7 +536,7 @@ __global__ __launch_bounds__(64 * NW_K) void k_gemm_s(GemmArgs a) {
 #pragma unroll
   for (int t = 0; t < NT; ++t) tile[t] = min(nt0 + t, a.n_tiles - 1);   // tiles past the end repeat the last one
   // one row tile: what the epilogue needs from memory is asked for now, so that it arrives with the weights
-  constexpr bool FUSED_IN = RT == 1 && (EPI == EPI_GELU || EPI == EPI_SWIGLU);
+  constexpr bool FUSED_IN = RT == 1 && (EPI == EPI_GELU || EPI == EPI_SWIGLU || EPI == EPI_QKV_NORM);
   constexpr bool FUSED_OUT = RT == 1 && EPI == EPI_RESID_NORM;
   __shared__ float2 sm_stat[FUSED_IN ? NW_K : 1][16];
   float4 pre_s[PS];
@@ -737,8 +743,8 @@ __global__ __launch_bounds__(64 * NW, OCC) void k_gemm_p(GemmArgs a) {
   const int per_slice = (KT + (int)gridDim.y - 1) / (int)gridDim.y;
   const int kt0 = min((int)blockIdx.y * per_slice, KT), kt1 = min(kt0 + per_slice, KT);
   const int rt0 = blockIdx.z * RT, r0 = rt0 * 16;
-  int4 kvi[(EPI == EPI_QKV || EPI == EPI_QKV_ROPE) ? RT : 1];
-  if (EPI == EPI_QKV || EPI == EPI_QKV_ROPE) {
+  int4 kvi[(EPI == EPI_QKV || EPI == EPI_QKV_ROPE || EPI == EPI_QKV_NORM) ? RT : 1];
+  if (EPI == EPI_QKV || EPI == EPI_QKV_ROPE || EPI == EPI_QKV_NORM) {
 #pragma unroll
     for (int i = 0; i < RT; ++i) kvi[i] = a.rt.kvinfo[r0 + i * 16 + m];
   }
@@ -864,8 +870,8 @@ static int launch_gemm_split(const GemmArgs &a, int rows, hipStream_t s) {
 
 template <int EPI>
 static int launch_gemm(const GemmArgs &a, int rows, hipStream_t s) {
-  if (EPI == EPI_RESID_NORM)
-    PD_REQUIRE(rows <= 16 && a.R <= 16, PD_EINVAL, "the residual projection that also prepares the next norm takes at most 16 rows (%d)", rows);
+  if (EPI == EPI_RESID_NORM || EPI == EPI_QKV_NORM)
+    PD_REQUIRE(rows <= 16 && a.R <= 16, PD_EINVAL, "projections that prepare or finish a norm take at most 16 rows (%d)", rows);
   if (rows > 128) {
     PD_REQUIRE(!a.packed, PD_EINVAL, "packed activations hold at most 8 rows (%d)", rows);
     return a.xn_lo ? launch_gemm_rows<EPI, true>(a, rows, s) : launch_gemm_rows<EPI, false>(a, rows, s);
@@ -894,6 +900,7 @@ int mfma_gemm_epi3(const GemmArgs &a, int rows, hipStream_t s);
 int mfma_gemm_epi4(const GemmArgs &a, int rows, hipStream_t s);
 int mfma_gemm_epi5(const GemmArgs &a, int rows, hipStream_t s);
 int mfma_gemm_epi6(const GemmArgs &a, int rows, hipStream_t s);
+int mfma_gemm_epi7(const GemmArgs &a, int rows, hipStream_t s);
 
 int mfma_gemm(int epi, const GemmArgs &a, int rows, hipStream_t s) {
   switch (epi) {
@@ -904,6 +911,7 @@ int mfma_gemm(int epi, const GemmArgs &a, int rows, hipStream_t s) {
     case EPI_SWIGLU: return mfma_gemm_epi4(a, rows, s);
     case EPI_LM: return mfma_gemm_epi5(a, rows, s);
     case EPI_RESID_NORM: return mfma_gemm_epi6(a, rows, s);
+    case EPI_QKV_NORM: return mfma_gemm_epi7(a, rows, s);
   }
   pd_set_error("unknown epilogue %d", epi);
   return PD_EINVAL;

@@ -96,7 +96,8 @@ __device__ __forceinline__ size_t v_cache_off(int key, int dim, int hd) {
 
 
 // ---- entry points between the sources of the bf16 path -------------------------------------
-enum { EPI_QKV = 0, EPI_QKV_ROPE = 1, EPI_RESID = 2, EPI_GELU = 3, EPI_SWIGLU = 4, EPI_LM = 5, EPI_RESID_NORM = 6 };
+enum { EPI_QKV = 0, EPI_QKV_ROPE = 1, EPI_RESID = 2, EPI_GELU = 3, EPI_SWIGLU = 4, EPI_LM = 5, EPI_RESID_NORM = 6,
+       EPI_QKV_NORM = 7 /* EPI_QKV fed gain * x: finishes the norm in its epilogue (stats_in, c1, c2) */ };
 
 struct GemmArgs {
   const bf16_t *W;       // packed
@@ -138,10 +139,16 @@ int mfma_norm(pd_ctx *c, const float *gain, const float *bias, int R, hipStream_
 bf16_t *mfma_lo(pd_ctx *c, void *buf, size_t cols);
 // pieces of a layer's launch sequence (mfma.hip)
 void mfma_gemm_base(pd_ctx *c, GemmArgs &a, int R);
+// c1 != NULL: the rows in c->xn are gain * x with per-tile sums in c->nstats (c->norm_fused): the epilogue finishes the norm
 int mfma_qkv(pd_ctx *c, GemmArgs &a, const bf16_t *W, int n_tiles, int sec0, void *kc, void *vc, void *kc_lo,
-             void *vc_lo, int R, hipStream_t s);
-int mfma_out(pd_ctx *c, GemmArgs &a, const bf16_t *p_wo, int R, hipStream_t s);
+             void *vc_lo, int R, hipStream_t s, const float *c1 = nullptr, const float *c2 = nullptr);
+// next_gain != NULL (and at most 16 rows): the projection also prepares the norm with that gain for the
+// projection that follows (sets c->norm_fused)
+int mfma_out(pd_ctx *c, GemmArgs &a, const bf16_t *p_wo, int R, hipStream_t s, const float *next_gain = nullptr);
 int mfma_out_ffn(pd_ctx *c, GemmArgs &a, const bf16_t *p_wo, const LayerPtrs &lw, int R, hipStream_t s);
+bool mfma_can_fuse_norm(pd_ctx *c, int R);
+int mfma_fold(float *c1, float *c2, const bf16_t *Wp, const float *gain, const float *bias, int n_out, int K,
+              hipStream_t s);
 int mfma_pack_matrix(bf16_t *dst, const void *src, int N, int K, hipStream_t s);   // row-major [N][K] -> fragments
 // What an attention launch of the encoder-decoder form changes (NULL: the decoder-only defaults).
 struct AttnMode {

@@ -192,6 +192,7 @@ static size_t carve(const pd_config *g, char *base, pd_ctx *c, const pd_encdec_c
       lp.p_w2 = cv.take<bf16_t>(dd * ff);
       lp.c1 = cv.take<float>((g->ffn_kind == 1 ? 2 : 1) * (size_t)ff);
       lp.c2 = cv.take<float>((g->ffn_kind == 1 ? 2 : 1) * (size_t)ff);
+      lp.cx1 = e ? cv.take<float>(dd) : nullptr;
     }
     x->nstats = cv.take<float2>((size_t)16 * (d / 16));
     x->p_lm_head = cv.take<bf16_t>((size_t)x->vocab_pad * d);
@@ -226,7 +227,7 @@ __global__ void k_fill_zero(uint4 *p, size_t n16) {
 // the workspace, re-packing the weights.  `c` has its configuration, pointers and carve-up.
 static int finish_create(pd_ctx *c, size_t need, void *hip_stream, bool no_alloc, pd_ctx **out) {
   c->prefilled = false; c->host_steps = 0;
-  c->embed_pending = false; c->packed = false; c->opt_splits = 0; c->opt_graph = 0; c->opt_profile = 0; c->opt_split = 1; c->opt_chunk = 0; c->opt_fuse_norm = 1;
+  c->embed_pending = false; c->norm_fused = false; c->packed = false; c->opt_splits = 0; c->opt_graph = 0; c->opt_profile = 0; c->opt_split = 1; c->opt_chunk = 0; c->opt_fuse_norm = 1;
   c->graph_exec = nullptr; c->graph_ready = false; c->ev_used = 0; c->h_pinned = nullptr;
   c->B = c->L = c->Lx = c->S = c->dt = c->M = c->time_max = c->A = c->R = 0;
   hipStream_t s = (hipStream_t)hip_stream;
@@ -496,6 +497,7 @@ static int run_layers(pd_ctx *c, int R, int A, int nreq, int req0, int kv_overri
   if (c->impl == 1) c->embed_pending = true;
   else if ((rc = launch_embed(c, R, s))) return rc;
   c->pend_parts = 0;
+  c->norm_fused = false;
   for (int l = 0; l < c->cfg.n_layer; ++l) {
     rc = c->arch == 1 ? encdec_decoder_layer(c, l, R, s)
          : c->impl == 1 ? mfma_layer(c, l, R, A, nreq, req0, kv_override, s)
@@ -709,7 +711,7 @@ extern "C" int pd_teacher_forced(pd_ctx *c, const int32_t *target, int max_len, 
   for (int b = 0; b < B; ++b) {
     const int n = rows[b];
     if ((rc = launch_teacher_rows(c, c->tf_target, b, max_len, s))) return rc;
-    c->packed = false; c->embed_pending = true; c->pend_parts = 0;
+    c->packed = false; c->embed_pending = true; c->pend_parts = 0; c->norm_fused = false;
     for (int l = 0; l < g.n_layer; ++l)
       if ((rc = mfma_layer(c, l, n, n, 1, b, L + n, s, &am))) return rc;
     float *lg = out_logits + (size_t)b * rows_cap * g.vocab;

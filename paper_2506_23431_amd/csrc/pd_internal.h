@@ -105,6 +105,7 @@ struct LayerPtrs {
   // MFMA path: re-packed copies inside the workspace
   bf16_t *p_wqkv, *p_wo, *p_w1, *p_w2;
   float *c1, *c2;                                  // p_w1 times the second norm's gain / bias, per packed column
+  float *cx1;                                      // p_cq times the gain of the norm in front of it
   void *kc, *vc;                                   // KV caches of this layer
   void *kc_lo, *vc_lo;                             // low halves (layers below kv_pair_layers), else NULL
   // encoder-decoder form, decoder layers: attention over the encoder states
@@ -153,6 +154,8 @@ struct pd_ctx {
   bool packed;              // this launch sequence keeps activations as packed pairs (at most 8 rows):
                             // high parts in rows 0-7 of a 16-row fragment, low parts in rows 8-15
   bool embed_pending;       // matrix-core path: the next norm kernel gathers x from the embedding tables
+  bool norm_fused;          // the last residual projection left gain * x and per-tile row sums for the next
+                            // norm: the projection that follows finishes it, no norm kernel runs
   float *lm_part_val; int32_t *lm_part_idx; int lm_parts;
   int32_t *row_argmax;      // [R_cap] argmax of each row's logits
   float *rope_cs;           // [max_pos][hd/2][2] cos, sin
