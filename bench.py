@@ -183,11 +183,32 @@ def main():
             for _ in range(3):
                 dst.copy_(src)
             del src, dst
-        torch.cuda.synchronize()
-        t0 = time.time()
-        dec.prefill_context(ctx, cfg.n_sub, cfg.delta_t, cfg.sub_tokens, T)
-        torch.cuda.synchronize()
-        prefill_s = time.time() - t0
+        # context pass: three calls, the first one cold (its kernels are loaded on first use)
+        prefill_calls = []
+        for _ in range(3):
+            torch.cuda.synchronize()
+            t0 = time.time()
+            dec.prefill_context(ctx, cfg.n_sub, cfg.delta_t, cfg.sub_tokens, T)
+            torch.cuda.synchronize()
+            prefill_calls.append(time.time() - t0)
+        prefill_s = sorted(prefill_calls)[1]
+        context_pairs = bool(dec.get_info(binding.PD_INFO_CONTEXT_PAIRS))
+        # the same pass with single bf16 activations (PD_OPT_CONTEXT_SPLIT_ACT 0: half the multiplies, 5-8 times
+        # the logit error; an option, not what the timed decode below runs on), then the default again
+        prefill_single = None
+        if cfg.dtype == 1:
+            dec.set_option(binding.PD_OPT_CONTEXT_SPLIT_ACT, 0)
+            single_calls = []
+            for _ in range(2):
+                torch.cuda.synchronize()
+                t0 = time.time()
+                dec.prefill_context(ctx, cfg.n_sub, cfg.delta_t, cfg.sub_tokens, T)
+                torch.cuda.synchronize()
+                single_calls.append(time.time() - t0)
+            prefill_single = min(single_calls)
+            dec.set_option(binding.PD_OPT_CONTEXT_SPLIT_ACT, 1)
+            dec.prefill_context(ctx, cfg.n_sub, cfg.delta_t, cfg.sub_tokens, T)
+            torch.cuda.synchronize()
         def advance(n):
             """n decode iterations; under --sync-every in groups with a synchronisation after each."""
             if args.sync_every > 0:
@@ -291,7 +312,9 @@ def main():
                               "reached_by": "untimed decode iterations from t = 1" if t0w > 1 else "start of the run"},
                    "repeats": reps, "repeat_ms_per_step": [x / K * 1e3 for x in times], "statistic": "median",
                    "tokens_generated": tokens, "time_steps_full_run": T,
-                   "prefill_s": prefill_s, "hip_graph": bool(args.graph),
+                   "prefill_s": prefill_s, "prefill_first_call_s": prefill_calls[0],
+                   "context_activations": "bf16 pairs" if context_pairs else "single bf16",
+                   "prefill_s_single_bf16_activations": prefill_single, "hip_graph": bool(args.graph),
                    "kv_pair_layers": pair_layers},
         "full_run": full,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

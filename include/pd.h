@@ -250,13 +250,22 @@ int pd_reset_decode(pd_ctx *ctx, void *hip_stream);
  *                        to the residual stream itself, hands gain * x and per-tile row sums to the
  *                        first FFN projection, and that projection finishes the second norm of the
  *                        layer in its epilogue (one kernel less per layer); 0: a separate norm kernel,
- *                        as in steps with more rows.  Same results up to rounding order.          */
+ *                        as in steps with more rows.  Same results up to rounding order.
+ *   PD_OPT_CONTEXT_SPLIT_ACT  activations of the context pass (pd_prefill_context of a decoder-only context on
+ *                        the matrix-core kernels): 1 (default) as pairs of bf16 values (high + low part, what the
+ *                        decode step uses), 0 as single bf16 values (half the multiplies of its projections).
+ *                        Measured over whole runs against the fp64 oracle: width 1024, 24 layers 4.2e-4 -> 2.6e-3
+ *                        of logit error for 0.032 -> 0.026 s; width 2048, 24 layers 4.8e-4 -> 3.4e-3 for 0.071 ->
+ *                        0.051 s (8192 context tokens), all tokens with a margin above 0.05 unchanged; width
+ *                        4096, 32 layers 9.3e-4 -> 8.6e-2, outside the 2e-2 tolerance: a caller's trade, not the
+ *                        library's.  pd_get_info(PD_INFO_CONTEXT_PAIRS) reports the setting in use.  */
 #define PD_OPT_ATTN_SPLITS 1
 #define PD_OPT_USE_GRAPH   2
 #define PD_OPT_PROFILE     3
 #define PD_OPT_SPLIT_ACT   4
 #define PD_OPT_PREFILL_CHUNK 5
 #define PD_OPT_FUSE_NORM 6
+#define PD_OPT_CONTEXT_SPLIT_ACT 7
 int pd_set_option(pd_ctx *ctx, int key, int value);
 
 /* Average time in microseconds between the two events of the brackets recorded since the
@@ -278,6 +287,8 @@ int pd_measure_read_bandwidth(const void *dev_buf, size_t buf_bytes, size_t chun
  *                           kernels do not cover: head_dim, d_model or d_ff not a multiple of 32, or
  *                           head_dim > 128) -- same results, far slower
  *   PD_INFO_KV_PAIR_LAYERS  layers whose cache holds pairs of halves (kv_pair_layers resolved)
+ *   PD_INFO_CONTEXT_PAIRS   1: the context pass carries its activations as bf16 pairs; 0: as single bf16
+ *                           values (PD_OPT_CONTEXT_SPLIT_ACT resolved)
  *   PD_INFO_KV_SATURATED    keys and values written since pd_create whose magnitude exceeded the
  *                           largest half (65504) and were stored as +-65504 (dtype 1 only; always
  *                           0 for dtype 0).  Non-zero means the 16-bit cache cannot represent
@@ -286,6 +297,7 @@ int pd_measure_read_bandwidth(const void *dev_buf, size_t buf_bytes, size_t chun
 #define PD_INFO_KERNEL_PATH    1
 #define PD_INFO_KV_PAIR_LAYERS 2
 #define PD_INFO_KV_SATURATED   3
+#define PD_INFO_CONTEXT_PAIRS  4
 int pd_get_info(pd_ctx *ctx, int key, void *hip_stream, int64_t *value);
 
 /* Message for the last error on this thread (static storage, never NULL). */

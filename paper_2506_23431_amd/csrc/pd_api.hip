@@ -227,7 +227,7 @@ __global__ void k_fill_zero(uint4 *p, size_t n16) {
 // the workspace, re-packing the weights.  `c` has its configuration, pointers and carve-up.
 static int finish_create(pd_ctx *c, size_t need, void *hip_stream, bool no_alloc, pd_ctx **out) {
   c->prefilled = false; c->host_steps = 0;
-  c->embed_pending = false; c->norm_fused = false; c->packed = false; c->opt_splits = 0; c->opt_graph = 0; c->opt_profile = 0; c->opt_split = 1; c->opt_chunk = 0; c->opt_fuse_norm = 1;
+  c->embed_pending = false; c->norm_fused = false; c->packed = false; c->opt_splits = 0; c->opt_graph = 0; c->opt_profile = 0; c->opt_split = 1; c->opt_chunk = 0; c->opt_fuse_norm = 1; c->opt_ctx_split = 1;
   c->graph_exec = nullptr; c->graph_ready = false; c->ev_used = 0; c->h_pinned = nullptr;
   c->B = c->L = c->Lx = c->S = c->dt = c->M = c->time_max = c->A = c->R = 0;
   hipStream_t s = (hipStream_t)hip_stream;
@@ -422,6 +422,18 @@ extern "C" int pd_destroy(pd_ctx *c) {
 // ---------------------------------------------------------------------------
 // options / instrumentation
 // ---------------------------------------------------------------------------
+// Whether the context pass carries activations as bf16 pairs (high + low part, as the decode step does;
+// the default) or as single bf16 values (PD_OPT_CONTEXT_SPLIT_ACT 0), which halves the multiplies of its
+// projections.  Measured over whole runs against the oracle: width 1024 (cfg3) 4.2e-4 -> 2.6e-3 of logit
+// error and 0.032 -> 0.026 s, width 2048 (cfg4) 4.8e-4 -> 3.4e-3 and 0.071 -> 0.051 s, every token with a
+// margin above 0.05 still equal; width 4096 with 32 layers (cfg5) 9.3e-4 -> 8.6e-2, and a small model with
+// a vocabulary projection of 15 times the usual scale 2.1e-2: outside the 2e-2 tolerance, which is why
+// the library does not choose single values by itself.
+static bool context_pairs(const pd_ctx *c) {
+  if (c->impl != 1 || c->arch == 1) return c->opt_split != 0;
+  return c->opt_split && c->opt_ctx_split;
+}
+
 static void drop_graph(pd_ctx *c) {
   if (c->graph_exec) (void)hipGraphExecDestroy(c->graph_exec);
   c->graph_exec = nullptr; c->graph_ready = false;
@@ -441,6 +453,8 @@ extern "C" int pd_set_option(pd_ctx *c, int key, int value) {
       PD_REQUIRE(value >= 0, PD_EINVAL, "prefill chunk must be >= 0");
       c->opt_chunk = value == 0 ? 0 : std::min((value + 15) / 16 * 16, c->prefill_chunk_cap);
       return PD_OK;
+    case PD_OPT_CONTEXT_SPLIT_ACT:
+      c->opt_ctx_split = value ? 1 : 0; return PD_OK;
     case PD_OPT_FUSE_NORM:
       c->opt_fuse_norm = value ? 1 : 0; drop_graph(c); return PD_OK;
     case PD_OPT_PROFILE:
@@ -472,6 +486,7 @@ extern "C" int pd_get_info(pd_ctx *c, int key, void *hip_stream, int64_t *value)
   switch (key) {
     case PD_INFO_KERNEL_PATH: *value = c->impl; return PD_OK;
     case PD_INFO_KV_PAIR_LAYERS: *value = c->pair_layers; return PD_OK;
+    case PD_INFO_CONTEXT_PAIRS: *value = context_pairs(c) ? 1 : 0; return PD_OK;
     case PD_INFO_KV_SATURATED: {
       hipStream_t s = (hipStream_t)hip_stream;
       PD_CHECK_HIP(hipStreamSynchronize(s));        // the staging buffer may be in flight
@@ -540,14 +555,19 @@ extern "C" int pd_prefill_context(pd_ctx *c, const int32_t *ctx_tokens, int B, i
   if ((rc = launch_reset_state(c, s))) return rc;
   for (int b = 0; b < B && c->arch == 1; ++b)
     if ((rc = encdec_encode(c, b, s))) return rc;
-  for (int b = 0; b < B && c->arch == 0; ++b) {
+  // the context pass may carry its activations as single bf16 values (see context_pairs)
+  const int split_decode = c->opt_split;
+  if (!context_pairs(c)) c->opt_split = 0;
+  for (int b = 0; b < B && c->arch == 0 && !rc; ++b) {
     const int chunk = c->opt_chunk > 0 ? c->opt_chunk : c->prefill_chunk;
-    for (int p0 = 0; p0 < L; p0 += chunk) {
+    for (int p0 = 0; p0 < L && !rc; p0 += chunk) {
       int n = std::min(chunk, L - p0);
-      if ((rc = launch_prefill_rows(c, b, p0, n, s, c->L, 0, b))) return rc;
-      if ((rc = run_layers(c, n, n, 1, b, p0 + n, s))) return rc;
+      if ((rc = launch_prefill_rows(c, b, p0, n, s, c->L, 0, b))) break;
+      rc = run_layers(c, n, n, 1, b, p0 + n, s);
     }
   }
+  c->opt_split = split_decode;
+  if (rc) return rc;
   // leave the row tables empty so that a stray head/commit sees no rows
   if ((rc = launch_reset_state(c, s))) return rc;
   c->prefilled = true;

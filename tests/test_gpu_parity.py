@@ -481,6 +481,27 @@ def test_context_pass_in_several_chunks(chunk):
     dec.close()
 
 
+@pytest.mark.parametrize("name", ["mfma-flat", "mfma-hd128-llama"])
+def test_context_pass_activation_precision(name):
+    """PD_OPT_CONTEXT_SPLIT_ACT 0: the context pass carries single bf16 activations (half the multiplies);
+    on these workloads that stays inside the tolerance, and the default (pairs) is at least as close to the
+    oracle."""
+    from paper_2506_23431_amd import binding
+    cfg = CASES[name]
+    w = pi.make_weights(cfg, threads=4)
+    ctx = pi.make_context(cfg)
+    outs = oracle_run(cfg, w, ctx)
+    dec = make_decoder(cfg, w)
+    assert dec.get_info(binding.PD_INFO_CONTEXT_PAIRS) == 1
+    worst = {}
+    for val in (0, 1):
+        dec.set_option(binding.PD_OPT_CONTEXT_SPLIT_ACT, val)
+        assert dec.get_info(binding.PD_INFO_CONTEXT_PAIRS) == val
+        worst[val] = compare_teacher_forced(cfg, w, ctx, dec, outs, log=say)["worst"]
+    assert worst[1] <= worst[0] * 1.5
+    dec.close()
+
+
 def test_options_do_not_change_results():
     """HIP-graph replay of the step, other attention split counts, other chunk sizes of the context
     pass (the default here is all 150 rows at once, in the many-row projection kernel) and
