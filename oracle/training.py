@@ -13,16 +13,22 @@ Reading where the paper is silent: the closing <eos> of a subsequence has no los
 >= i from its own time on, exactly as Algorithm 1 feeds a finished subsequence's last token once.
 So every token of the target is a row and a key; the last token of each subsequence is a key only.
 
+The encoder-decoder form (teacher_forced_encdec) is the same pass through oracle/encdec.py's dense
+decoder: the matrix of Fig. 3b over the target's tokens, the Manhattan distance of Section 4.3 between
+every visible pair, the encoder states of Eq. 1 behind the second attention.
+
 Parity status: pinned in tests/test_oracle_training.py by Fig. 3b's worked example (the target and
 its 8 loss terms), by Algorithm 1 run with the target's tokens forced (the incremental decoder of
 oracle/pipelined.py gives the same distributions step by step), by an independent PyTorch library
 model with its library cross-entropy under a mask enumerated in the test (any schedule; one
-subsequence = ordinary language-model loss), and by planted mistakes.
+subsequence = ordinary language-model loss), and by planted mistakes; the encoder-decoder form by
+Algorithm 1 with the target forced through the incremental encoder-decoder decoder and by the
+independent PyTorch encoder-decoder of tests/torch_encdec.py with the library's cross-entropy.
 """
 
 import numpy as np
 
-from . import matrix_form
+from . import encdec, matrix_form
 
 F = np.float64
 
@@ -53,4 +59,29 @@ def teacher_forced(model, ctx_tokens, target, delta_t):
                 m = row.max()
                 nll[r] = m + np.log(np.exp(row - m).sum()) - row[sub[j + 1]]
             r += 1
+    return logits, nll, float(nll.sum())
+
+
+def _nll(logits, target):
+    nll = np.zeros(logits.shape[0], dtype=F)
+    r = 0
+    for sub in target:
+        for j in range(len(sub)):
+            if j + 1 < len(sub):
+                row = logits[r]
+                m = row.max()
+                nll[r] = m + np.log(np.exp(row - m).sum()) - row[sub[j + 1]]
+            r += 1
+    return nll
+
+
+def teacher_forced_encdec(model, ctx_tokens, target, delta_t):
+    """The same for an oracle.encdec.EncDecModel: returns (logits [N, V], nll [N], loss)."""
+    coords = matrix_form.coordinates(target, delta_t)
+    ii = np.array([c[0] for c in coords])
+    tt = np.array([c[1] for c in coords])
+    mask = (ii[None, :] <= ii[:, None]) & (tt[None, :] <= tt[:, None])
+    distance = np.abs(tt[:, None] - tt[None, :]) + np.abs(ii[:, None] - ii[None, :])
+    logits = encdec.dense_decoder_forward(model, model.encode(ctx_tokens), [c[2] for c in coords], mask, distance)
+    nll = _nll(logits, target)
     return logits, nll, float(nll.sum())

@@ -403,7 +403,7 @@ int mfma_attention(pd_ctx *c, const LayerPtrs &lw, int A, int nreq, int req0, in
   // measurement: mode 1 attaches a start and a stop event to the dispatch of the main kernel itself
   // (their difference is the kernel's execution time), mode 2 records events before the main kernel
   // and after the merge kernel
-  bool prof = c->opt_profile && kv_override < 0;
+  bool prof = c->opt_profile && kv_override < 0 && !a.bias;    // (the instantiations with coordinates take no events)
   hipEvent_t ev0 = nullptr, ev1 = nullptr;
   if (prof) {
     while (c->ev_pool.size() < c->ev_used + 2) {

@@ -155,3 +155,72 @@ def test_gpu_cases_can_see_a_wrong_matrix():
                 mask[L + a, L + b] = (ik <= iq) if drop == "time" else (tk <= tq)
         wrong = matrix_form.dense_forward(model, tokens, pos, mask)[L:]
         assert np.abs(wrong - right).max() > 0.06, drop         # three times the bar
+
+
+# --------------------------------------------------------------------------
+# encoder-decoder form
+# --------------------------------------------------------------------------
+ED = pi.EncDecConfig(name="encdec-train", seed=57, n_enc_layer=2, n_dec_layer=2, d_model=32, n_head=4, head_dim=6,
+                     d_ff=48, vocab=83, rel_buckets=8, rel_max_distance=20, ctx_len=17, eos_id=1)
+
+
+def ed_setup():
+    from oracle import encdec
+    w = pi.make_encdec_weights(ED)
+    g = np.random.Generator(np.random.Philox(key=[(ED.seed << 32) | 0xC0DE, 1]))
+    return encdec.EncDecModel(ED, w), w, g.integers(0, ED.vocab, size=ED.ctx_len)
+
+
+@pytest.mark.parametrize("lengths,dt", [([3, 2], 1), ([4, 2, 3], 2), ([5, 3, 4, 3], 3)])
+def test_encdec_loss_terms_are_the_distributions_of_algorithm_1(lengths, dt):
+    from oracle import encdec
+    model, w, ctx = ed_setup()
+    tgt = training.training_target(draw_target(ED, lengths), ED.bos_id, ED.eos_id)
+    n = len(tgt)
+    T = max(i * dt + len(s) - 1 for i, s in enumerate(tgt))
+    force = np.full((T, n), -1, dtype=np.int64)
+    for i, s in enumerate(tgt):
+        for j in range(1, len(s)):
+            force[i * dt + j - 1, i] = s[j]
+    dec = encdec.EncDecPerQueryDecoder(model, ctx, force=force)
+    result, steps, _ = controller.pipelined_decode(dec, dt, 10 ** 6, n, ED.bos_id, ED.eos_id, 10 ** 6)
+    assert result == [s[1:-1] for s in tgt] and steps == T
+    logits, nll, loss = training.teacher_forced_encdec(model, ctx, tgt, dt)
+    offset = np.concatenate([[0], np.cumsum([len(s) for s in tgt])])
+    seen = 0
+    for rec in dec.trace:
+        for r, i in enumerate(rec["rows"]):
+            row = offset[i - 1] + rec["t"] - ((i - 1) * dt + 1)
+            np.testing.assert_allclose(rec["logits"][r], logits[row], rtol=0, atol=1e-10)
+            seen += 1
+    assert seen == sum(1 for i, s in enumerate(tgt) for j in range(len(s)) if i * dt + 1 + j <= T)
+    assert int((nll > 0).sum()) == sum(len(s) - 1 for s in tgt) and loss == pytest.approx(nll.sum())
+
+
+def test_encdec_loss_against_library_cross_entropy():
+    from torch_encdec import encode as torch_encode, decode_logits
+    model, w, ctx = ed_setup()
+    dt = 2
+    tgt = training.training_target(draw_target(ED, [4, 3, 2], seed=3), ED.bos_id, ED.eos_id)
+    fed = [(i, i * dt + j, tok) for i, s in enumerate(tgt) for j, tok in enumerate(s)]
+    N = len(fed)
+    mask = np.zeros((N, N), dtype=bool)
+    dist = np.zeros((N, N), dtype=np.int64)
+    for a, (iq, tq, _) in enumerate(fed):
+        for b, (ik, tk, _) in enumerate(fed):
+            mask[a, b] = ik <= iq and tk <= tq
+            dist[a, b] = abs(tq - tk) + abs(iq - ik)
+    lg = decode_logits(ED, w, torch_encode(ED, w, ctx), [f[2] for f in fed], mask, dist)
+    rows, nxt, r = [], [], 0
+    for s in tgt:
+        for j in range(len(s)):
+            if j + 1 < len(s):
+                rows.append(r)
+                nxt.append(s[j + 1])
+            r += 1
+    want = torch.nn.functional.cross_entropy(torch.as_tensor(np.asarray(lg)[rows]), torch.as_tensor(nxt),
+                                             reduction="none").numpy()
+    logits, nll, loss = training.teacher_forced_encdec(model, ctx, tgt, dt)
+    np.testing.assert_allclose(logits, np.asarray(lg), rtol=0, atol=1e-10)
+    np.testing.assert_allclose(nll[rows], want, rtol=0, atol=1e-10)
+    assert loss == pytest.approx(float(want.sum()), abs=1e-9)
