@@ -218,8 +218,10 @@ int pd_encdec_create(const pd_encdec_config *cfg, const pd_encdec_weights *w, vo
  *   out_row_nll  host fp32 [B][rows_cap] or NULL: the term of every row (0 for rows without a successor)
  *   out_loss     host fp64 [B]: Eq. 6 per request (terms added in row order)
  *   out_rows     host int32 [B] or NULL: rows of each request
- * Decoder-only contexts on the matrix-core kernels only.  Uses the generated side of the KV caches and the
- * schedule state as scratch and leaves the context at t = 0, as pd_reset_decode does.  Synchronises. */
+ * Both model forms, on the matrix-core kernels only (the encoder-decoder form adds the Manhattan-distance
+ * bias of Section 4.3 between every visible pair and the attention over the encoder states).  Uses the
+ * generated side of the KV caches and the schedule state as scratch and leaves the context at t = 0, as
+ * pd_reset_decode does.  Synchronises. */
 int pd_teacher_forced(pd_ctx *ctx, const int32_t *target, int max_len, float *out_logits, int rows_cap,
                       float *out_row_nll, double *out_loss, int32_t *out_rows, void *hip_stream);
 

@@ -128,7 +128,11 @@ int encdec_encode(pd_ctx *c, int b, hipStream_t s) {
 
 // One decoder layer of a decode step (Eq. 3): self-attention over the generated side under the
 // dependency rule with the Manhattan-distance bias, attention over the encoder states, feed-forward.
-int encdec_decoder_layer(pd_ctx *c, int l, int R, hipStream_t s) {
+// A rows per request, nreq requests from req0 on.  kv_self < 0: a decode step (each request's keys so far);
+// otherwise the number of generated-side keys to consider (the one-pass teacher-forced forward, where the
+// time half of the matrix is the attention kernel's own check).
+int encdec_decoder_layer(pd_ctx *c, int l, int R, hipStream_t s, int A, int nreq, int req0, int kv_self) {
+  if (A <= 0) { A = c->A; nreq = c->B; req0 = 0; kv_self = -1; }
   const pd_config &g = c->cfg;
   EncDecState &e = c->ed;
   const LayerPtrs &lw = c->layers[l];
@@ -143,7 +147,7 @@ int encdec_decoder_layer(pd_ctx *c, int l, int R, hipStream_t s) {
   self.L = 0; self.scale = 1.f;
   self.bias = e.dec_bias; self.bias_len = e.dec_len; self.bias_off = 0;
   self.coord = c->gen_coord; self.coord_stride = c->gen_stride; self.coord_req_stride = c->gen_stride;
-  if ((rc = mfma_attention(c, lw, c->A, c->B, 0, -1, s, &self))) return rc;
+  if ((rc = mfma_attention(c, lw, A, nreq, req0, kv_self, s, &self))) return rc;
   // In steps of at most 16 rows the output projection also prepares the norm that follows it and the
   // query projection behind that norm finishes it (gemm.hip): no norm kernel in between.
   if ((rc = mfma_out(c, a, lw.p_wo, R, s, lw.n3g))) return rc;
@@ -156,6 +160,6 @@ int encdec_decoder_layer(pd_ctx *c, int l, int R, hipStream_t s) {
   AttnMode cross;
   memset(&cross, 0, sizeof(cross));
   cross.kc = lw.xkc; cross.vc = lw.xvc; cross.qinfo = c->qinfo_x; cross.L = c->Lx; cross.scale = 1.f;
-  if ((rc = mfma_attention(c, lw, c->A, c->B, 0, c->Lx, s, &cross))) return rc;
+  if ((rc = mfma_attention(c, lw, A, nreq, req0, c->Lx, s, &cross))) return rc;
   return mfma_out_ffn(c, a, lw.p_co, lw, R, s);
 }

@@ -684,9 +684,9 @@ extern "C" int pd_teacher_forced(pd_ctx *c, const int32_t *target, int max_len, 
                                  float *out_row_nll, double *out_loss, int32_t *out_rows, void *hip_stream) {
   PD_REQUIRE(c && target && out_logits && out_loss, PD_EINVAL, "ctx, target, out_logits or out_loss is NULL");
   PD_REQUIRE(c->prefilled, PD_ESTATE, "pd_teacher_forced before pd_prefill_context");
-  PD_REQUIRE(c->arch == 0 && c->impl == 1, PD_EINVAL,
-             "the teacher-forced forward runs on decoder-only contexts of the matrix-core kernels (dtype 1, head_dim, "
-             "d_model, d_ff multiples of 32)");
+  PD_REQUIRE(c->impl == 1, PD_EINVAL,
+             "the teacher-forced forward runs on the matrix-core kernels (dtype 1, head_dim, d_model, d_ff multiples "
+             "of 32)");
   const pd_config &g = c->cfg;
   const int B = c->B, S = c->S, L = c->L;
   PD_REQUIRE(max_len >= 1 && max_len <= g.max_sub_tokens + 2, PD_EINVAL, "max_len = %d out of range [1, %d]", max_len,
@@ -733,7 +733,8 @@ extern "C" int pd_teacher_forced(pd_ctx *c, const int32_t *target, int max_len, 
     if ((rc = launch_teacher_rows(c, c->tf_target, b, max_len, s))) return rc;
     c->packed = false; c->embed_pending = true; c->pend_parts = 0; c->norm_fused = false;
     for (int l = 0; l < g.n_layer; ++l)
-      if ((rc = mfma_layer(c, l, n, n, 1, b, L + n, s, &am))) return rc;
+      if ((rc = c->arch == 1 ? encdec_decoder_layer(c, l, n, s, n, 1, b, n) : mfma_layer(c, l, n, n, 1, b, L + n, s, &am)))
+        return rc;
     float *lg = out_logits + (size_t)b * rows_cap * g.vocab;
     if ((rc = mfma_head(c, n, true, s, lg))) return rc;
     if ((rc = launch_row_nll(c, lg, n, c->loss + b, s))) return rc;

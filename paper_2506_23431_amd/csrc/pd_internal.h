@@ -212,5 +212,5 @@ int mfma_head(pd_ctx *c, int R, bool want_logits, hipStream_t s, float *logits_t
 int encdec_pack_weights(pd_ctx *c, hipStream_t s);
 int encdec_build_tables(pd_ctx *c, int *scratch, hipStream_t s);
 int encdec_encode(pd_ctx *c, int b, hipStream_t s);                   // Eq. 1 for request b, then its cross keys / values
-int encdec_decoder_layer(pd_ctx *c, int l, int R, hipStream_t s);
+int encdec_decoder_layer(pd_ctx *c, int l, int R, hipStream_t s, int A = 0, int nreq = 0, int req0 = 0, int kv_self = -1);
 size_t mfma_packed_weight_bytes(const pd_config *cfg);

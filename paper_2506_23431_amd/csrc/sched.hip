@@ -165,7 +165,8 @@ int launch_prefill_rows(pd_ctx *c, int b, int p0, int n, hipStream_t s, int L, i
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_teacher_rows(RowTables rt, SchedState st, uint16_t *gen_coord,
                                                       int32_t *next_tok, const int32_t *tgt, int b, int S, int ML,
-                                                      int dt, int L, int gen_stride, int R_cap) {
+                                                      int dt, int L, int gen_stride, int R_cap, int4 *qinfo_x,
+                                                      int Lx) {
   const int32_t *tb = tgt + (size_t)b * S * ML;
   int32_t *len = st.n_tok + (size_t)b * S, *off = st.n_fed + (size_t)b * S;
   for (int i = threadIdx.x; i < S; i += blockDim.x) {
@@ -194,17 +195,19 @@ __global__ __launch_bounds__(256) void k_teacher_rows(RowTables rt, SchedState s
       st.gen_sub[(size_t)b * gen_stride + (L & 7) + r] = (uint16_t)(i + 1);
       gen_coord[(size_t)b * gen_stride + (L & 7) + r] = (uint16_t)c;
       next_tok[r] = more ? tb[(size_t)i * ML + j + 1] : -1;
+      if (qinfo_x) qinfo_x[r] = make_int4(fl, 0, Lx, b);     // encoder-decoder form: all Lx encoder states
     }
   }
   for (int r = s_total + threadIdx.x; r < R_cap; r += blockDim.x) {
     rt.flags[r] = 0; rt.qinfo[r] = make_int4(0, -1, 0, b); rt.kvinfo[r] = make_int4(0, b, 0, 0);
     next_tok[r] = -1;
+    if (qinfo_x) qinfo_x[r] = make_int4(0, -1, 0, b);
   }
 }
 
 int launch_teacher_rows(pd_ctx *c, const int32_t *tgt_dev, int b, int ML, hipStream_t s) {
   hipLaunchKernelGGL(k_teacher_rows, dim3(1), dim3(256), 0, s, c->rows, c->sch, c->gen_coord, c->row_argmax, tgt_dev,
-                     b, c->S, ML, c->dt, c->L, c->gen_stride, c->R_cap);
+                     b, c->S, ML, c->dt, c->L, c->gen_stride, c->R_cap, c->qinfo_x, c->Lx);
   PD_CHECK_HIP(hipGetLastError());
   return PD_OK;
 }

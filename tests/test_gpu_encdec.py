@@ -77,6 +77,42 @@ def test_encoder_decoder_parity(name):
     dec.close()
 
 
+@pytest.mark.parametrize("name", ["encdec-hd64", "encdec-hd32-short-reach", "encdec-hd128-packed", "encdec-manyrows"])
+def test_encoder_decoder_teacher_forced_forward(name):
+    """Section 3.3 on the encoder-decoder form: whole training targets in one pass (the time half of Fig. 3b's
+    matrix is the attention kernel's own check here, and distances reach beyond max_distance in the second
+    case); logits, loss terms and loss against oracle/training.py."""
+    from oracle import training
+    cfg = CASES[name].scaled(eos_id=1)
+    rounded, ctx, dec = make(cfg)
+    model = encdec.EncDecModel(cfg, rounded)
+    g = np.random.Generator(np.random.Philox(key=[cfg.seed, 0x7EAC]))
+    targets = []
+    for _ in range(cfg.batch):
+        Y = [[int(t) for t in g.integers(2, cfg.vocab, size=int(g.integers(1, cfg.sub_tokens)))]
+             for _ in range(int(g.integers(2, cfg.n_sub)))]
+        while sum(len(y) + 2 for y in Y) + 2 > 120:
+            Y.pop()
+        targets.append(training.training_target(Y, cfg.bos_id, cfg.eos_id))
+    dec.prefill_context(ctx, cfg.n_sub, cfg.delta_t, cfg.sub_tokens, cfg.time_steps)
+    logits, nll, loss = dec.teacher_forced(targets)
+    worst = worst_nll = 0.0
+    for b, tgt in enumerate(targets):
+        want_logits, want_nll, want_loss = training.teacher_forced_encdec(model, ctx[b], tgt, cfg.delta_t)
+        err = np.abs(logits[b].cpu().numpy().astype(np.float64) - want_logits).max()
+        assert np.isfinite(err) and err <= 2e-2, f"request {b}: max|logit diff| = {err:.3e}"
+        e2 = np.abs(nll[b] - want_nll).max()
+        assert e2 <= 4e-2 and np.array_equal(nll[b] == 0, want_nll == 0)
+        assert abs(loss[b] - want_loss) <= 4e-2 * int((want_nll != 0).sum())
+        worst, worst_nll = max(worst, err), max(worst_nll, e2)
+    say(f"[teacher-forced] {name}: {sum(len(x) for x in nll)} rows, max|logit diff| = {worst:.3e}, "
+        f"max|term diff| = {worst_nll:.3e}")
+    # the context decodes as before afterwards
+    outs = oracle_run(cfg.scaled(eos_id=-1), rounded, ctx)
+    compare_teacher_forced(cfg.scaled(eos_id=-1), None, ctx, dec, outs, tol=2e-2, log=say)
+    dec.close()
+
+
 def test_encoder_decoder_forced_tokens_and_eos():
     """Arbitrary forced tokens (the model's own choices never enter the history) with <eos> among them:
     subsequences end early, requests end at different steps."""
