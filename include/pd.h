@@ -239,7 +239,11 @@ int pd_reset_decode(pd_ctx *ctx, void *hip_stream);
  *   PD_OPT_PROFILE       1: bracket the attention kernel of every layer (the kernel that streams the
  *                        keys and values; not the small kernel that merges its partial results) with
  *                        HIP events;  2: bracket the pair of kernels  (adds event overhead to the
- *                        step; for measurement only)
+ *                        step; for measurement only);  3: no events: every decode step launches that
+ *                        kernel one extra time, first, on the cache of the layer half the stack away
+ *                        (other bytes of the same size) and into the same outputs, which the real launch
+ *                        overwrites -- the time a run of steps gains by it, per launch, is what the kernel
+ *                        costs where it runs (results unchanged; not for layers that keep pairs of halves)
  *   PD_OPT_SPLIT_ACT     bf16 path: 1 (default) carries every activation that enters a matrix
  *                        multiply as a pair of bf16 values (about 16 mantissa bits) and runs two
  *                        matrix-core passes per weight / key / value fragment; 0 uses plain bf16

@@ -458,7 +458,7 @@ extern "C" int pd_set_option(pd_ctx *c, int key, int value) {
     case PD_OPT_FUSE_NORM:
       c->opt_fuse_norm = value ? 1 : 0; drop_graph(c); return PD_OK;
     case PD_OPT_PROFILE:
-      c->opt_profile = value == 2 ? 2 : (value ? 1 : 0); drop_graph(c); c->ev_used = 0; return PD_OK;
+      c->opt_profile = (value == 2 || value == 3) ? value : (value ? 1 : 0); drop_graph(c); c->ev_used = 0; return PD_OK;
     default:
       pd_set_error("unknown option key %d", key);
       return PD_EINVAL;
