@@ -158,26 +158,33 @@ def make_encdec_weights(cfg, threads: int = 2) -> dict:
     [buckets, H] (one table per stack, used by all its layers), "enc_final_g"/"dec_final_g" [d],
     "enc_layers": dicts with "wq","wk","wv" [H*hd,d], "wo" [d,H*hd], "w1" [ff,d], "w2" [d,ff],
     "norm1_g","norm2_g" [d]; "dec_layers": the same plus "cq","ck","cv","co" (cross-attention) and
-    "norm3_g".  Matrices N(0, 0.05), biases N(0, 0.5), gains 1 + N(0, 0.1)."""
+    "norm3_g".
+    Scales follow the published initialisation of the backbone family, which is what keeps its
+    unscaled attention scores (no 1/sqrt(head_dim) factor) of order one: query projections
+    N(0, 1/(d*hd)), every other projection N(0, 1/fan_in), embeddings N(0, 1), the vocabulary
+    projection N(0, 1/d); biases N(0, 0.5), gains 1 + N(0, 0.1)."""
     d, ff, V, inner = cfg.d_model, cfg.d_ff, cfg.vocab, cfg.n_head * cfg.head_dim
     with ThreadPoolExecutor(max_workers=threads) as pool:
         tid = iter(range(1, 1 << 20))
 
-        def mat(*shape, std=0.05):
+        def mat(*shape, std):
             return _normal(shape, cfg.seed, next(tid), False, pool, std=std)
 
         def gain():
             return _normal((d,), cfg.seed, next(tid), False, pool, std=0.1, mean=1.0)
 
+        sq, sd, sf, si = (d * cfg.head_dim) ** -0.5, d ** -0.5, ff ** -0.5, inner ** -0.5
+
         def layer(cross):
-            lw = {"wq": mat(inner, d), "wk": mat(inner, d), "wv": mat(inner, d), "wo": mat(d, inner),
-                  "w1": mat(ff, d), "w2": mat(d, ff), "norm1_g": gain(), "norm2_g": gain()}
+            lw = {"wq": mat(inner, d, std=sq), "wk": mat(inner, d, std=sd), "wv": mat(inner, d, std=sd),
+                  "wo": mat(d, inner, std=si), "w1": mat(ff, d, std=sd), "w2": mat(d, ff, std=sf),
+                  "norm1_g": gain(), "norm2_g": gain()}
             if cross:
-                lw.update({"cq": mat(inner, d), "ck": mat(inner, d), "cv": mat(inner, d),
-                           "co": mat(d, inner), "norm3_g": gain()})
+                lw.update({"cq": mat(inner, d, std=sq), "ck": mat(inner, d, std=sd), "cv": mat(inner, d, std=sd),
+                           "co": mat(d, inner, std=si), "norm3_g": gain()})
             return lw
 
-        w = {"tok_emb": mat(V, d, std=1.0), "lm_head": mat(V, d),
+        w = {"tok_emb": mat(V, d, std=1.0), "lm_head": mat(V, d, std=sd),
              "enc_rel_bias": mat(cfg.rel_buckets, cfg.n_head, std=0.5),
              "dec_rel_bias": mat(cfg.rel_buckets, cfg.n_head, std=0.5),
              "enc_final_g": gain(), "dec_final_g": gain()}

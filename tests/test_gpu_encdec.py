@@ -113,6 +113,33 @@ def test_encoder_decoder_teacher_forced_forward(name):
     dec.close()
 
 
+def _random_case(k):
+    """Seeded random small encoder-decoder workload k: head sizes 32 / 64 / 96 / 128, one to three heads, bucket
+    counts and reaches on both sides of the distances that occur, ragged inputs, one to five row tiles per
+    step, delays longer than a subsequence (Algorithm 1 then stops early)."""
+    rng = np.random.default_rng(2000 + k)
+    hd = int(rng.choice([32, 64, 96, 128]))
+    nh = int(rng.integers(1, 4))
+    buckets = int(rng.choice([4, 8, 16, 32]))
+    return E(f"encdec-random-{k}", 80 + k, n_enc_layer=int(rng.integers(1, 3)), n_dec_layer=int(rng.integers(1, 3)),
+             d_model=hd * nh, n_head=nh, head_dim=hd, d_ff=int(rng.choice([96, 160, 224, 320])),
+             vocab=int(rng.integers(130, 900)), rel_buckets=buckets,
+             rel_max_distance=int(rng.integers(buckets // 2 + 1, 129)), ctx_len=int(rng.integers(1, 300)),
+             n_sub=int(rng.integers(1, 12)), delta_t=int(rng.integers(1, 6)), sub_tokens=int(rng.integers(1, 10)),
+             batch=int(rng.integers(1, 6)))
+
+
+@pytest.mark.parametrize("k", range(10))
+def test_encoder_decoder_random_small_workloads(k):
+    cfg = _random_case(k)
+    say(f"[case] {cfg}")
+    rounded, ctx, dec = make(cfg)
+    outs = oracle_run(cfg, rounded, ctx)
+    stats = compare_teacher_forced(cfg, None, ctx, dec, outs, tol=2e-2, log=say)
+    assert stats["rows"] > 0
+    dec.close()
+
+
 def test_encoder_decoder_forced_tokens_and_eos():
     """Arbitrary forced tokens (the model's own choices never enter the history) with <eos> among them:
     subsequences end early, requests end at different steps."""
