@@ -515,9 +515,12 @@ __device__ __forceinline__ void gemm_chunk(floatx4 (&acc)[NT][RT][NA], const uin
 // PACK (one row tile, at most 8 rows): the activation fragment carries the high parts in rows 0-7
 // and the low parts of the same 8 rows in rows 8-15, so one fragment and one multiply per k-tile
 // do the work of two; the two halves of the output tile are added before the epilogue.
-template <int RT, int NT, int NW_K, int U, int EPI, bool SPLIT, bool PACK>
+// ZROWS: the block serves row tiles blockIdx.z * RT .. + RT - 1 only (launches that spread the row tiles of a
+// step over blocks, see launch_gemm_zrows).
+template <int RT, int NT, int NW_K, int U, int EPI, bool SPLIT, bool PACK, bool ZROWS = false>
 __global__ __launch_bounds__(64 * NW_K) void k_gemm_s(GemmArgs a) {
   static_assert(!PACK || (RT == 1 && !SPLIT), "packed activations: one row tile, one fragment");
+  const int rz = ZROWS ? (int)blockIdx.z * RT : 0;          // first row tile of this block
   __shared__ floatx4 red[NW_K > 1 ? NW_K * NT * RT * 64 : 1];
   const int wk = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int nt0 = blockIdx.x * NT;
@@ -530,7 +533,7 @@ __global__ __launch_bounds__(64 * NW_K) void k_gemm_s(GemmArgs a) {
   int4 kvi[(EPI == EPI_QKV || EPI == EPI_QKV_ROPE || EPI == EPI_QKV_NORM) ? RT : 1];
   if (EPI == EPI_QKV || EPI == EPI_QKV_ROPE || EPI == EPI_QKV_NORM) {
 #pragma unroll
-    for (int i = 0; i < RT; ++i) kvi[i] = a.rt.kvinfo[i * 16 + m];
+    for (int i = 0; i < RT; ++i) kvi[i] = a.rt.kvinfo[(rz + i) * 16 + m];
   }
   int tile[NT];
 #pragma unroll
@@ -563,8 +566,8 @@ __global__ __launch_bounds__(64 * NW_K) void k_gemm_s(GemmArgs a) {
 #pragma unroll
     for (int i = 0; i < RT; ++i) acc2[t][i][0] = acc2[t][i][NA - 1] = floatx4{0.f, 0.f, 0.f, 0.f};
   const uint4 *wp = (const uint4 *)a.W + lane;
-  const uint4 *xp = (const uint4 *)a.xn + lane;
-  const uint4 *xl = SPLIT ? (const uint4 *)a.xn_lo + lane : nullptr;
+  const uint4 *xp = (const uint4 *)a.xn + lane + (size_t)rz * KT * 64;
+  const uint4 *xl = SPLIT ? (const uint4 *)a.xn_lo + lane + (size_t)rz * KT * 64 : nullptr;
   int kt = kt0;
   while (kt + U <= kt1) { gemm_chunk<RT, NT, U, SPLIT, NA>(acc2, wp, xp, xl, KT, tile, kt); kt += U; }
   if (U > 4 && kt + 4 <= kt1) { gemm_chunk<RT, NT, 4, SPLIT, NA>(acc2, wp, xp, xl, KT, tile, kt); kt += 4; }
@@ -608,7 +611,7 @@ __global__ __launch_bounds__(64 * NW_K) void k_gemm_s(GemmArgs a) {
       for (int w = 1; w < NW_K; ++w)
 #pragma unroll
         for (int i = 0; i < RT; ++i) sum[i] += red[((w * NT + t) * RT + i) * 64 + lane];
-      gemm_epilogue<RT, EPI>(a, nt0 + t, sum, kvi, lane, 0, fused_norm ? nrm : nullptr,
+      gemm_epilogue<RT, EPI>(a, nt0 + t, sum, kvi, lane, rz * 16, fused_norm ? nrm : nullptr,
                              (FUSED_OUT && t == wk) ? &pre_r : nullptr, (fused_norm && t == wk) ? &pre_n : nullptr);
     }
   } else {
@@ -617,7 +620,7 @@ __global__ __launch_bounds__(64 * NW_K) void k_gemm_s(GemmArgs a) {
 #pragma unroll
     for (int t = 0; t < NT; ++t)
       if (nt0 + t < a.n_tiles)
-        gemm_epilogue<RT, EPI>(a, nt0 + t, acc[t], kvi, lane, 0, fused_norm ? nrm : nullptr,
+        gemm_epilogue<RT, EPI>(a, nt0 + t, acc[t], kvi, lane, rz * 16, fused_norm ? nrm : nullptr,
                                (FUSED_OUT && t == 0) ? &pre_r : nullptr, (fused_norm && t == 0) ? &pre_n : nullptr);
   }
 }
@@ -857,8 +860,46 @@ static int launch_gemm_rows(const GemmArgs &a, int rows, hipStream_t s) {
   return launch_gemm_rows_nt<2, EPI, SPLIT>(a, rows, s);
 }
 
+// 17-128 rows against a small weight matrix (at most 16 MB: what the L2 caches hold with room to spare).  One
+// row tile and four column tiles per block instead of all row tiles and one column tile: a k-tile then costs a
+// wave 4 weight + 2 activation requests for 4 output tiles, not 1 + 2 RT for RT, so the busiest compute unit
+// issues about half the requests (its vector-memory pipeline is what bounds these launches), all requests
+// of a wave go out in one batch, and 5 x 48 blocks fill the chip where 192 did not.  The weights are read
+// once per row tile; block ids that differ by a multiple of 8 run on the same XCD (work-groups go to the
+// XCDs round-robin), so with a number of column groups that is a multiple of 8 the row tiles of a group
+// share one L2 and the repeats stay out of HBM.  Measured at 72 rows, width 1024 (cfg3): QKV 10.9 -> 6.9 us, first
+// FFN projection 11.5 -> 9.5, output projection 4.0 (K slices of 8 k-tiles), second FFN projection 8.4 -> 7.7;
+// 0.83 -> 0.76 ms per step.
+template <int EPI, bool SPLIT>
+static int launch_gemm_zrows(GemmArgs a, int rows, hipStream_t s) {
+  constexpr int NT = 4, U = 4;
+  const int KT = a.K / 32, groups = (a.n_tiles + NT - 1) / NT, rts = (rows + 15) / 16;
+  // the residual projections also cut K into slices over blocks (summed by the next norm kernel) until the
+  // launch has a block per compute unit
+  int ks = 1;
+  if (EPI == EPI_RESID)
+    while (ks < a.max_parts && groups * rts * ks < 256 && KT / (2 * ks) >= 4) ks *= 2;
+  const int per_block = (KT + ks - 1) / ks;
+  int nwk = NT;
+  while (nwk < 16 && (per_block + nwk - 1) / nwk > 4) nwk *= 2;      // one batch of at most 4 k-tiles per wave
+  a.k_share = (per_block + nwk - 1) / nwk;
+  dim3 grid(groups, ks, rts);
+  switch (nwk) {
+    case 4: hipLaunchKernelGGL((k_gemm_s<1, NT, 4, U, EPI, SPLIT, false, true>), grid, dim3(256), 0, s, a); break;
+    case 8: hipLaunchKernelGGL((k_gemm_s<1, NT, 8, U, EPI, SPLIT, false, true>), grid, dim3(512), 0, s, a); break;
+    default: hipLaunchKernelGGL((k_gemm_s<1, NT, 16, U, EPI, SPLIT, false, true>), grid, dim3(1024), 0, s, a); break;
+  }
+  PD_CHECK_HIP(hipGetLastError());
+  if (EPI == EPI_RESID && a.parts_out) *a.parts_out = ks;
+  return PD_OK;
+}
+
 template <int EPI, bool SPLIT>
 static int launch_gemm_split(const GemmArgs &a, int rows, hipStream_t s) {
+  constexpr bool zrows = EPI == EPI_QKV || EPI == EPI_QKV_ROPE || EPI == EPI_GELU || EPI == EPI_SWIGLU || EPI == EPI_RESID;
+  if (zrows && rows > 16 && (size_t)a.n_tiles * 16 * a.K * 2 <= ((size_t)16 << 20) &&
+      a.K / 32 <= 64 * (EPI == EPI_RESID ? a.max_parts : 1))
+    return launch_gemm_zrows<EPI, SPLIT>(a, rows, s);
   switch (mfma_gemm_row_tiles(rows)) {
     case 16: return launch_gemm_small<1, EPI, SPLIT, false>(a, s);
     case 32: return launch_gemm_wide<2, EPI, SPLIT>(a, s);
