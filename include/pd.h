@@ -257,6 +257,13 @@ int pd_reset_decode(pd_ctx *ctx, void *hip_stream);
  *                        first FFN projection, and that projection finishes the second norm of the
  *                        layer in its epilogue (one kernel less per layer); 0: a separate norm kernel,
  *                        as in steps with more rows.  Same results up to rounding order.
+ *   PD_OPT_STREAM_LOADS  1: decode steps load weights, keys and values with the non-temporal hint; 0: ordinary
+ *                        loads.  Chosen at creation from the configuration: 1 when the bytes a step reads at
+ *                        full capacity (every weight, every request's keys and values) exceed the 256 MB
+ *                        last-level cache, so that nothing of them would be found there a step later (cfg4:
+ *                        1.37 -> 1.31 ms per step, cfg5 6.55 -> 6.09); 0 for models the cache serves step after
+ *                        step (cfg2: 0.187 ms, 0.202 with the hint).  Same results bit for bit.
+ *                        pd_get_info(PD_INFO_STREAM_LOADS) reports the setting.
  *   PD_OPT_CONTEXT_SPLIT_ACT  activations of the context pass (pd_prefill_context of a decoder-only context on
  *                        the matrix-core kernels): 1 (default) as pairs of bf16 values (high + low part, what the
  *                        decode step uses), 0 as single bf16 values (half the multiplies of its projections).
@@ -272,6 +279,7 @@ int pd_reset_decode(pd_ctx *ctx, void *hip_stream);
 #define PD_OPT_PREFILL_CHUNK 5
 #define PD_OPT_FUSE_NORM 6
 #define PD_OPT_CONTEXT_SPLIT_ACT 7
+#define PD_OPT_STREAM_LOADS 8
 int pd_set_option(pd_ctx *ctx, int key, int value);
 
 /* Average time in microseconds between the two events of the brackets recorded since the
@@ -295,6 +303,7 @@ int pd_measure_read_bandwidth(const void *dev_buf, size_t buf_bytes, size_t chun
  *   PD_INFO_KV_PAIR_LAYERS  layers whose cache holds pairs of halves (kv_pair_layers resolved)
  *   PD_INFO_CONTEXT_PAIRS   1: the context pass carries its activations as bf16 pairs; 0: as single bf16
  *                           values (PD_OPT_CONTEXT_SPLIT_ACT resolved)
+ *   PD_INFO_STREAM_LOADS    1: decode steps use the non-temporal hint (PD_OPT_STREAM_LOADS)
  *   PD_INFO_KV_SATURATED    keys and values written since pd_create whose magnitude exceeded the
  *                           largest half (65504) and were stored as +-65504 (dtype 1 only; always
  *                           0 for dtype 0).  Non-zero means the 16-bit cache cannot represent
@@ -304,6 +313,7 @@ int pd_measure_read_bandwidth(const void *dev_buf, size_t buf_bytes, size_t chun
 #define PD_INFO_KV_PAIR_LAYERS 2
 #define PD_INFO_KV_SATURATED   3
 #define PD_INFO_CONTEXT_PAIRS  4
+#define PD_INFO_STREAM_LOADS   5
 int pd_get_info(pd_ctx *ctx, int key, void *hip_stream, int64_t *value);
 
 /* Message for the last error on this thread (static storage, never NULL). */

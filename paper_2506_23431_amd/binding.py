@@ -15,7 +15,9 @@ LIB_PATH = os.path.join(HERE, "libpd.so")
 PD_OPT_ATTN_SPLITS, PD_OPT_USE_GRAPH, PD_OPT_PROFILE, PD_OPT_SPLIT_ACT, PD_OPT_PREFILL_CHUNK = 1, 2, 3, 4, 5
 PD_OPT_FUSE_NORM = 6
 PD_OPT_CONTEXT_SPLIT_ACT = 7
+PD_OPT_STREAM_LOADS = 8
 PD_INFO_KERNEL_PATH, PD_INFO_KV_PAIR_LAYERS, PD_INFO_KV_SATURATED, PD_INFO_CONTEXT_PAIRS = 1, 2, 3, 4
+PD_INFO_STREAM_LOADS = 5
 
 EXPORTS = ["pd_workspace_bytes", "pd_create", "pd_destroy", "pd_prefill_context", "pd_decode_step",
            "pd_generate", "pd_generate_static", "pd_decode_steps", "pd_reset_decode", "pd_set_option", "pd_profile_read",

@@ -49,7 +49,16 @@ constexpr int BIAS_MAX = 264;   // entries of one head's bias table that the ker
 // PAIR: the layer keeps keys and values as high + low halves.  Scores add q_hi K_lo (q_lo K_lo is
 // below the rounding of everything else), outputs add P V_lo; the kernel holds twice the fragments
 // and is built for one block per compute unit.
-template <int HD, bool SPLIT, bool PAIR, bool BIAS = false>
+// STREAM: keys and values are loaded with the non-temporal hint.  In a decode step every key/value byte is read
+// once per launch and nothing reads it again before the caches have turned over, so keeping it out of the
+// caches' way pays (cfg4: 15.9 -> 15.0 us per launch, cfg5: 60.5 -> 52.8); in the context pass the 16-query
+// groups of a chunk re-read the same keys from L2, and there the hint costs a third of the pass.
+template <bool STREAM>
+__device__ __forceinline__ f16x8 ld_kv(const uint4 *p) {
+  return STREAM ? __builtin_nontemporal_load((const f16x8 *)p) : *(const f16x8 *)p;
+}
+
+template <int HD, bool SPLIT, bool PAIR, bool BIAS = false, bool STREAM = false>
 __global__ __launch_bounds__(256, PAIR ? 1 : 3) void k_attn_mfma(AttnArgs a) {
   constexpr int NC = HD / 32, NHB = HD / 16, PSTR = HD + 2;   // partial: m, l, O[HD] per query
   __shared__ float sm_m[4][16], sm_l[4][16];
@@ -111,8 +120,8 @@ __global__ __launch_bounds__(256, PAIR ? 1 : 3) void k_attn_mfma(AttnArgs a) {
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int c = 0; c < NC; ++c) {
-        kf[t][c].u = Kp[((size_t)(kbx * 2 + t) * NC + c) * 64];
-        if (PAIR) kl[t][c].u = Kl[((size_t)(kbx * 2 + t) * NC + c) * 64];
+        kf[t][c].hv = ld_kv<STREAM>(&Kp[((size_t)(kbx * 2 + t) * NC + c) * 64]);
+        if (PAIR) kl[t][c].hv = ld_kv<STREAM>(&Kl[((size_t)(kbx * 2 + t) * NC + c) * 64]);
       }
   };
   auto load_v = [&](int kbx) {
@@ -121,8 +130,8 @@ __global__ __launch_bounds__(256, PAIR ? 1 : 3) void k_attn_mfma(AttnArgs a) {
     if (BIAS) kco.u = *(const uint4 *)(kcp + min(max(kbx * 32 + 8 * g - a.coord_off, 0), a.coord_stride - 8));
 #pragma unroll
     for (int i = 0; i < NHB; ++i) {
-      vf[i].u = Vp[((size_t)kbx * NHB + i) * 64];
-      if (PAIR) vl[i].u = Vl[((size_t)kbx * NHB + i) * 64];
+      vf[i].hv = ld_kv<STREAM>(&Vp[((size_t)kbx * NHB + i) * 64]);
+      if (PAIR) vl[i].hv = ld_kv<STREAM>(&Vl[((size_t)kbx * NHB + i) * 64]);
     }
   };
   // requested unconditionally (a wave beyond the last block fetches that block and ignores it), so
@@ -366,6 +375,12 @@ static int pick_splits(pd_ctx *c, int units, int nblk) {
   return std::max(1, std::min(std::min(want, by_keys), cap));
 }
 
+template <int HD, bool SPLIT, bool PAIR, bool BIAS, bool STREAM>
+static void launch_attn(dim3 grid, hipStream_t s, hipEvent_t e0, hipEvent_t e1, const AttnArgs &a) {
+  if (e0 || e1) hipExtLaunchKernelGGL((k_attn_mfma<HD, SPLIT, PAIR, BIAS, STREAM>), grid, dim3(256), 0, s, e0, e1, 0, a);
+  else hipLaunchKernelGGL((k_attn_mfma<HD, SPLIT, PAIR, BIAS, STREAM>), grid, dim3(256), 0, s, a);
+}
+
 int mfma_attention(pd_ctx *c, const LayerPtrs &lw, int A, int nreq, int req0, int kv_override,
                    hipStream_t s, const AttnMode *mode) {
   const pd_config &g = c->cfg;
@@ -428,25 +443,29 @@ int mfma_attention(pd_ctx *c, const LayerPtrs &lw, int A, int nreq, int req0, in
   }
   const bool attach = prof && c->opt_profile == 1;
   hipEvent_t pe0 = attach ? ev0 : nullptr, pe1 = attach ? ev1 : nullptr;
-#define PD_ATTN(HDV)                                                                        \
-  do {                                                                                      \
-    if (a.bias && a.q_lo) hipLaunchKernelGGL((k_attn_mfma<HDV, true, false, true>), grid, dim3(256), 0, s, a);  \
-    else if (a.bias) hipLaunchKernelGGL((k_attn_mfma<HDV, false, false, true>), grid, dim3(256), 0, s, a);      \
-    else if (a.kc_lo && a.q_lo) hipExtLaunchKernelGGL((k_attn_mfma<HDV, true, true>), grid, dim3(256), 0, s, pe0, pe1, 0, a);  \
-    else if (a.kc_lo) hipExtLaunchKernelGGL((k_attn_mfma<HDV, false, true>), grid, dim3(256), 0, s, pe0, pe1, 0, a);    \
-    else if (twice && a.q_lo) {                                                             \
-      hipLaunchKernelGGL((k_attn_mfma<HDV, true, false>), grid, dim3(256), 0, s, a_extra);  \
-      hipLaunchKernelGGL((k_attn_mfma<HDV, true, false>), grid, dim3(256), 0, s, a);        \
-    } else if (twice) {                                                                     \
-      hipLaunchKernelGGL((k_attn_mfma<HDV, false, false>), grid, dim3(256), 0, s, a_extra); \
-      hipLaunchKernelGGL((k_attn_mfma<HDV, false, false>), grid, dim3(256), 0, s, a);       \
-    }                                                                                       \
-    else if (attach && a.q_lo) hipExtLaunchKernelGGL((k_attn_mfma<HDV, true, false>), grid, dim3(256), 0, s, ev0, ev1, 0, a);  \
-    else if (attach) hipExtLaunchKernelGGL((k_attn_mfma<HDV, false, false>), grid, dim3(256), 0, s, ev0, ev1, 0, a);      \
-    else if (a.q_lo) hipLaunchKernelGGL((k_attn_mfma<HDV, true, false>), grid, dim3(256), 0, s, a);  \
-    else hipLaunchKernelGGL((k_attn_mfma<HDV, false, false>), grid, dim3(256), 0, s, a);           \
-    if (a.nsplit > 1)                                                                       \
-      hipLaunchKernelGGL(k_attn_merge<HDV>, dim3(units, HDV / 16), dim3(256), 0, s, a);            \
+  // decode steps of the decoder-only form stream their keys and values (see STREAM); the context pass, the
+  // teacher-forced forward and the encoder-decoder launches (small or re-read key sets) do not
+  const bool stream = kv_override < 0 && !mode && c->stream_loads;
+#define PD_ATTN_ONE(HDV, ARGS)                                                                         \
+  do {                                                                                                 \
+    const bool sp = a.q_lo != nullptr, pr = a.kc_lo != nullptr, bi = a.bias != nullptr;                \
+    if (bi && sp) launch_attn<HDV, true, false, true, false>(grid, s, pe0, pe1, ARGS);                 \
+    else if (bi) launch_attn<HDV, false, false, true, false>(grid, s, pe0, pe1, ARGS);                 \
+    else if (pr && sp && stream) launch_attn<HDV, true, true, false, true>(grid, s, pe0, pe1, ARGS);   \
+    else if (pr && sp) launch_attn<HDV, true, true, false, false>(grid, s, pe0, pe1, ARGS);            \
+    else if (pr && stream) launch_attn<HDV, false, true, false, true>(grid, s, pe0, pe1, ARGS);        \
+    else if (pr) launch_attn<HDV, false, true, false, false>(grid, s, pe0, pe1, ARGS);                 \
+    else if (sp && stream) launch_attn<HDV, true, false, false, true>(grid, s, pe0, pe1, ARGS);        \
+    else if (sp) launch_attn<HDV, true, false, false, false>(grid, s, pe0, pe1, ARGS);                 \
+    else if (stream) launch_attn<HDV, false, false, false, true>(grid, s, pe0, pe1, ARGS);             \
+    else launch_attn<HDV, false, false, false, false>(grid, s, pe0, pe1, ARGS);                        \
+  } while (0)
+#define PD_ATTN(HDV)                                                                                   \
+  do {                                                                                                 \
+    if (twice) PD_ATTN_ONE(HDV, a_extra);                                                              \
+    PD_ATTN_ONE(HDV, a);                                                                               \
+    if (a.nsplit > 1)                                                                                  \
+      hipLaunchKernelGGL(k_attn_merge<HDV>, dim3(units, HDV / 16), dim3(256), 0, s, a);                \
   } while (0)
   switch (g.head_dim) {
     case 32: PD_ATTN(32); break;
@@ -456,6 +475,7 @@ int mfma_attention(pd_ctx *c, const LayerPtrs &lw, int A, int nreq, int req0, in
     default: pd_set_error("head_dim %d not supported by the MFMA attention", g.head_dim); return PD_EINVAL;
   }
 #undef PD_ATTN
+#undef PD_ATTN_ONE
   PD_CHECK_HIP(hipGetLastError());
   if (prof) {
     if (c->opt_profile != 1) PD_CHECK_HIP(hipEventRecord(c->ev_pool[c->ev_used + 1], s));

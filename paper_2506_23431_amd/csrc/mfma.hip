@@ -14,6 +14,7 @@ void mfma_gemm_base(pd_ctx *c, GemmArgs &a, int R) {
   memset(&a, 0, sizeof(a));
   a.R = R; a.rt = c->rows; a.d = g.d_model; a.H = g.n_head; a.hd = g.head_dim; a.kv_cap = c->kv_cap;
   a.packed = c->packed;
+  a.stream_w = c->stream_loads;
 }
 
 // QKV-style projection of the normalised rows in c->xn: queries to c->q, keys and values into the given
@@ -121,6 +122,7 @@ int mfma_head(pd_ctx *c, int R, bool want_logits, hipStream_t s, float *logits_t
   GemmArgs a;
   memset(&a, 0, sizeof(a));
   a.R = R; a.rt = c->rows; a.W = c->p_lm_head; a.xn = (const bf16_t *)c->xn; a.packed = c->packed;
+  a.stream_w = c->stream_loads;
   a.xn_lo = mfma_lo(c, c->xn, g.d_model); a.K = g.d_model;
   a.n_tiles = c->vocab_pad / 16; a.V = g.vocab;
   a.logits = want_logits ? (logits_to ? logits_to : c->logits) : nullptr; a.ld_logits = g.vocab;

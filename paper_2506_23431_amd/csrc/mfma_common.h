@@ -130,6 +130,7 @@ struct GemmArgs {
   const float2 *stats_in; int stats_tiles; const float *c1, *c2; int norm_kind, norm_d; float norm_eps;
   int act;               // EPI_GELU: 0 gelu(erf), 1 relu
   int sec0;              // EPI_QKV*: section of the weight's first d columns (0: Q, K, V follow; 1: K, V only)
+  int stream_w;          // 1: load the weights with the non-temporal hint (a step's bytes exceed the last-level cache)
 };
 
 int mfma_gemm(int epi, const GemmArgs &a, int rows, hipStream_t s);

@@ -230,6 +230,16 @@ static int finish_create(pd_ctx *c, size_t need, void *hip_stream, bool no_alloc
   c->embed_pending = false; c->norm_fused = false; c->packed = false; c->opt_splits = 0; c->opt_graph = 0; c->opt_profile = 0; c->opt_split = 1; c->opt_chunk = 0; c->opt_fuse_norm = 1; c->opt_ctx_split = 1;
   c->graph_exec = nullptr; c->graph_ready = false; c->ev_used = 0; c->h_pinned = nullptr;
   c->B = c->L = c->Lx = c->S = c->dt = c->M = c->time_max = c->A = c->R = 0;
+  {
+    // what a decode step reads at full capacity: every weight once, every request's keys and values once per
+    // layer.  Beyond the 256 MB last-level cache nothing survives from one step to the next and the loads
+    // take the non-temporal hint (PD_OPT_STREAM_LOADS overrides).
+    const pd_config &g = c->cfg;
+    const double wbytes = 2.0 * ((double)g.n_layer * (4.0 * g.d_model * g.d_model + (g.ffn_kind == 1 ? 3.0 : 2.0) * g.d_model * g.d_ff) +
+                                 (double)g.vocab * g.d_model);
+    const double kvbytes = 2.0 * g.max_batch * (double)g.n_layer * 2.0 * c->kv_cap * g.d_model;
+    c->stream_loads = (c->impl == 1 && c->arch == 0 && wbytes + kvbytes > 256.0 * (1 << 20)) ? 1 : 0;
+  }
   hipStream_t s = (hipStream_t)hip_stream;
   auto fail = [&](int code) { (void)pd_destroy(c); return code; };
   const size_t n_stage = 2 * (size_t)c->cfg.max_batch * c->cfg.max_sub + 16;
@@ -455,6 +465,8 @@ extern "C" int pd_set_option(pd_ctx *c, int key, int value) {
       return PD_OK;
     case PD_OPT_CONTEXT_SPLIT_ACT:
       c->opt_ctx_split = value ? 1 : 0; return PD_OK;
+    case PD_OPT_STREAM_LOADS:
+      c->stream_loads = value ? 1 : 0; drop_graph(c); return PD_OK;
     case PD_OPT_FUSE_NORM:
       c->opt_fuse_norm = value ? 1 : 0; drop_graph(c); return PD_OK;
     case PD_OPT_PROFILE:
@@ -487,6 +499,7 @@ extern "C" int pd_get_info(pd_ctx *c, int key, void *hip_stream, int64_t *value)
     case PD_INFO_KERNEL_PATH: *value = c->impl; return PD_OK;
     case PD_INFO_KV_PAIR_LAYERS: *value = c->pair_layers; return PD_OK;
     case PD_INFO_CONTEXT_PAIRS: *value = context_pairs(c) ? 1 : 0; return PD_OK;
+    case PD_INFO_STREAM_LOADS: *value = c->stream_loads; return PD_OK;
     case PD_INFO_KV_SATURATED: {
       hipStream_t s = (hipStream_t)hip_stream;
       PD_CHECK_HIP(hipStreamSynchronize(s));        // the staging buffer may be in flight

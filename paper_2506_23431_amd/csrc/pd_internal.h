@@ -154,6 +154,8 @@ struct pd_ctx {
   bool packed;              // this launch sequence keeps activations as packed pairs (at most 8 rows):
                             // high parts in rows 0-7 of a 16-row fragment, low parts in rows 8-15
   bool embed_pending;       // matrix-core path: the next norm kernel gathers x from the embedding tables
+  int stream_loads;         // 1: a decode step touches more bytes than the last-level cache holds: weights, keys and
+                            // values are loaded with the non-temporal hint (PD_OPT_STREAM_LOADS)
   bool norm_fused;          // the last residual projection left gain * x and per-tile row sums for the next
                             // norm: the projection that follows finishes it, no norm kernel runs
   float *lm_part_val; int32_t *lm_part_idx; int lm_parts;

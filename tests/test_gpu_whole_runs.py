@@ -70,6 +70,7 @@ def test_whole_run_against_stored_oracle_results(workload):
     dec = make_decoder(cfg, w)
     from paper_2506_23431_amd import binding
     assert dec.get_info(binding.PD_INFO_CONTEXT_PAIRS) == 1
+    assert dec.get_info(binding.PD_INFO_STREAM_LOADS) == 1        # a step of these workloads reads 1.3-14 GB
     dec.prefill_context(ctx, S, cfg.delta_t, cfg.sub_tokens, T)
     say(f"[{cfg.name}] contexts encoded; requests with stored oracle results: {sorted(gold)} of {B}")
     worst, n_rows, n_free, n_forced = 0.0, 0, 0, 0
