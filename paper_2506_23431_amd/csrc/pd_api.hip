@@ -235,10 +235,14 @@ static int finish_create(pd_ctx *c, size_t need, void *hip_stream, bool no_alloc
     // layer.  Beyond the 256 MB last-level cache nothing survives from one step to the next and the loads
     // take the non-temporal hint (PD_OPT_STREAM_LOADS overrides).
     const pd_config &g = c->cfg;
-    const double wbytes = 2.0 * ((double)g.n_layer * (4.0 * g.d_model * g.d_model + (g.ffn_kind == 1 ? 3.0 : 2.0) * g.d_model * g.d_ff) +
+    // (encoder-decoder form: a decoder layer also reads the two d x d projections around its attention over
+    // the encoder states, and that attention's keys and values)
+    const double attn_mats = c->arch == 1 ? 6.0 : 4.0, caches = c->arch == 1 ? 2.0 : 1.0;
+    const double wbytes = 2.0 * ((double)g.n_layer * (attn_mats * g.d_model * g.d_model +
+                                                      (g.ffn_kind == 1 ? 3.0 : 2.0) * g.d_model * g.d_ff) +
                                  (double)g.vocab * g.d_model);
-    const double kvbytes = 2.0 * g.max_batch * (double)g.n_layer * 2.0 * c->kv_cap * g.d_model;
-    c->stream_loads = (c->impl == 1 && c->arch == 0 && wbytes + kvbytes > 256.0 * (1 << 20)) ? 1 : 0;
+    const double kvbytes = caches * 2.0 * g.max_batch * (double)g.n_layer * 2.0 * c->kv_cap * g.d_model;
+    c->stream_loads = (c->impl == 1 && wbytes + kvbytes > 256.0 * (1 << 20)) ? 1 : 0;
   }
   hipStream_t s = (hipStream_t)hip_stream;
   auto fail = [&](int code) { (void)pd_destroy(c); return code; };
