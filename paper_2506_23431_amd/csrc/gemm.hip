@@ -700,7 +700,7 @@ static int launch_gemm_small(const GemmArgs &a, hipStream_t s) {
 template <int RT, int NT, int EPI, bool SPLIT>
 static int launch_gemm_wide_nt(GemmArgs a, int ks, hipStream_t s) {
   constexpr int NWK = 4;
-  constexpr int U = (NT + 2 * RT) <= 10 ? 4 : 2;
+  constexpr int U = (NT + 2 * RT) <= 16 ? 4 : 2;
   int KT = a.K / 32, groups = (a.n_tiles + NT - 1) / NT;
   a.k_share = ((KT + ks - 1) / ks + NWK - 1) / NWK;
   if (a.stream_w)
@@ -900,15 +900,13 @@ static int launch_gemm_zrows(GemmArgs a, int rows, hipStream_t s) {
   if (EPI == EPI_RESID)
     while (ks < a.max_parts && groups * rts * ks < 256 && KT / (2 * ks) >= 4) ks *= 2;
   const int per_block = (KT + ks - 1) / ks;
-  int nwk = NT;
-  while (nwk < 16 && (per_block + nwk - 1) / nwk > 4) nwk *= 2;      // one batch of at most 4 k-tiles per wave
+  // 4 or 8 waves along K (16 would leave a wave 128 registers, too few for 4 x 4 weight fragments in flight):
+  // one batch of 4 k-tiles per wave up to K = 1024 per slice, two up to 2048
+  const int nwk = per_block > 16 ? 8 : 4;
   a.k_share = (per_block + nwk - 1) / nwk;
   dim3 grid(groups, ks, rts);
-  switch (nwk) {
-    case 4: hipLaunchKernelGGL((k_gemm_s<1, NT, 4, U, EPI, SPLIT, false, true>), grid, dim3(256), 0, s, a); break;
-    case 8: hipLaunchKernelGGL((k_gemm_s<1, NT, 8, U, EPI, SPLIT, false, true>), grid, dim3(512), 0, s, a); break;
-    default: hipLaunchKernelGGL((k_gemm_s<1, NT, 16, U, EPI, SPLIT, false, true>), grid, dim3(1024), 0, s, a); break;
-  }
+  if (nwk == 4) hipLaunchKernelGGL((k_gemm_s<1, NT, 4, U, EPI, SPLIT, false, true>), grid, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL((k_gemm_s<1, NT, 8, U, EPI, SPLIT, false, true>), grid, dim3(512), 0, s, a);
   PD_CHECK_HIP(hipGetLastError());
   if (EPI == EPI_RESID && a.parts_out) *a.parts_out = ks;
   return PD_OK;
