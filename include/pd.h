@@ -257,6 +257,9 @@ int pd_reset_decode(pd_ctx *ctx, void *hip_stream);
  *                        first FFN projection, and that projection finishes the second norm of the
  *                        layer in its epilogue (one kernel less per layer); 0: a separate norm kernel,
  *                        as in steps with more rows.  Same results up to rounding order.
+ *                        2: models without rotary positions also hand over the first norm of the next
+ *                        layer the same way (second FFN projection -> QKV projection).  Not the default:
+ *                        that projection then cannot be cut along K over blocks, and measured slower.
  *   PD_OPT_STREAM_LOADS  1: decode steps load weights, keys and values with the non-temporal hint; 0: ordinary
  *                        loads.  Chosen at creation from the configuration: 1 when the bytes a step reads at
  *                        full capacity (every weight, every request's keys and values) exceed the 256 MB

@@ -117,6 +117,7 @@ int mfma_fold_norms(pd_ctx *c, hipStream_t s) {
   for (int l = 0; l < g.n_layer; ++l) {
     LayerPtrs &lp = c->layers[l];
     if ((rc = mfma_fold(lp.c1, lp.c2, lp.p_w1, lp.n2g, g.norm_kind == 0 ? lp.n2b : nullptr, n_out, g.d_model, s))) return rc;
+    if (c->arch == 0 && (rc = mfma_fold(lp.q1, lp.q2, lp.p_wqkv, lp.n1g, g.norm_kind == 0 ? lp.n1b : nullptr, 3 * g.d_model, g.d_model, s))) return rc;
   }
   return PD_OK;
 }

@@ -21,11 +21,16 @@ void mfma_gemm_base(pd_ctx *c, GemmArgs &a, int R) {
 // caches at the rows' slots.  `n_tiles` 16-column tiles of W, whose first d columns are section `sec0`
 // (0: queries, then keys, then values; 1: keys, then values).
 // An output projection (contraction over d_model) can prepare the next norm, and the projection behind
-// that norm finish it, when the step has one row tile.  The second FFN projection cannot give up its cut
-// along K over blocks for this: uncut, with the next layer's QKV projection finishing the norm, a step of
-// the 768 / 3072 shape measured 0.198 ms against 0.188 ms.
+// that norm finish it, when the step has one row tile.
 bool mfma_can_fuse_norm(pd_ctx *c, int R) {
   return c->opt_fuse_norm && R <= 16 && mfma_gemm_row_tiles(R) == 16;
+}
+// The second FFN projection has to give up its cut along K over blocks for this, which leaves one block
+// per 16 output columns.  With the next layer's QKV projection finishing the norm, a step of the 768 / 3072
+// shape measured 0.198 ms against 0.188 ms and one of the 2048 / 8192 shape 1.33-1.34 ms against 1.31 ms
+// (the uncut projection loses what the norm kernel took): only on request (value 2 of the option).
+static bool ffn2_prepares_norm(pd_ctx *c, int R) {
+  return mfma_can_fuse_norm(c, R) && c->opt_fuse_norm == 2 && c->cfg.pos_kind != 1;
 }
 
 int mfma_qkv(pd_ctx *c, GemmArgs &a, const bf16_t *W, int n_tiles, int sec0, void *kc, void *vc, void *kc_lo,
@@ -63,7 +68,8 @@ int mfma_out(pd_ctx *c, GemmArgs &a, const bf16_t *p_wo, int R, hipStream_t s, c
 }
 
 // output projection + residual, the norm in front of the FFN, the FFN + residual
-int mfma_out_ffn(pd_ctx *c, GemmArgs &a, const bf16_t *p_wo, const LayerPtrs &lw, int R, hipStream_t s) {
+int mfma_out_ffn(pd_ctx *c, GemmArgs &a, const bf16_t *p_wo, const LayerPtrs &lw, int R, hipStream_t s,
+                 const float *next_gain) {
   const pd_config &g = c->cfg;
   int d = g.d_model, ff = g.d_ff, rc;
   a.W = p_wo; a.xn = (const bf16_t *)c->att; a.xn_lo = mfma_lo(c, c->att, d); a.K = d; a.n_tiles = d / 16; a.x = c->ypart; a.ld = d;
@@ -95,6 +101,13 @@ int mfma_out_ffn(pd_ctx *c, GemmArgs &a, const bf16_t *p_wo, const LayerPtrs &lw
   if (rc) return rc;
   a.stats_in = nullptr;
   a.W = lw.p_w2; a.xn = (const bf16_t *)c->hb; a.xn_lo = mfma_lo(c, c->hb, ff); a.K = ff; a.n_tiles = d / 16; a.x = c->ypart; a.ld = d;
+  if (next_gain && ffn2_prepares_norm(c, R)) {
+    // completes x itself and leaves gain * x with the row sums for the next layer's QKV projection
+    a.x_res = c->x; a.gain = next_gain; a.stats_out = c->nstats;
+    a.out_bf = (bf16_t *)c->xn; a.out_lo = mfma_lo(c, c->xn, d);
+    c->norm_fused = true;
+    return mfma_gemm(EPI_RESID_NORM, a, R, s);
+  }
   return mfma_gemm(EPI_RESID, a, R, s);
 }
 
@@ -103,16 +116,21 @@ int mfma_layer(pd_ctx *c, int l, int R, int A, int nreq, int req0, int kv_overri
   const pd_config &g = c->cfg;
   const LayerPtrs &lw = c->layers[l];
   int rc;
-  if ((rc = mfma_norm(c, lw.n1g, lw.n1b, R, s))) return rc;
+  // the previous layer's second FFN projection may have prepared this norm already
+  const bool finish = c->norm_fused;
+  if (!finish && (rc = mfma_norm(c, lw.n1g, lw.n1b, R, s))) return rc;
   GemmArgs a;
   mfma_gemm_base(c, a, R);
   // QKV projection (+ rotary) + KV append
-  if ((rc = mfma_qkv(c, a, lw.p_wqkv, 3 * g.d_model / 16, 0, lw.kc, lw.vc, lw.kc_lo, lw.vc_lo, R, s))) return rc;
+  if ((rc = mfma_qkv(c, a, lw.p_wqkv, 3 * g.d_model / 16, 0, lw.kc, lw.vc, lw.kc_lo, lw.vc_lo, R, s,
+                     finish ? lw.q1 : nullptr, finish ? lw.q2 : nullptr)))
+    return rc;
   // context pass, last layer: only its keys and values are ever used (nothing reads the residual
   // stream of a context token after the last layer)
   if (kv_override >= 0 && l == g.n_layer - 1 && !mode) return PD_OK;
   if ((rc = mfma_attention(c, lw, A, nreq, req0, kv_override, s, mode))) return rc;
-  return mfma_out_ffn(c, a, lw.p_wo, lw, R, s);
+  const bool decode_step = kv_override < 0 && !mode;
+  return mfma_out_ffn(c, a, lw.p_wo, lw, R, s, decode_step && l + 1 < g.n_layer ? c->layers[l + 1].n1g : nullptr);
 }
 
 int mfma_head(pd_ctx *c, int R, bool want_logits, hipStream_t s, float *logits_to) {

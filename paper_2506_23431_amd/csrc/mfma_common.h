@@ -146,7 +146,9 @@ int mfma_qkv(pd_ctx *c, GemmArgs &a, const bf16_t *W, int n_tiles, int sec0, voi
 // next_gain != NULL (and at most 16 rows): the projection also prepares the norm with that gain for the
 // projection that follows (sets c->norm_fused)
 int mfma_out(pd_ctx *c, GemmArgs &a, const bf16_t *p_wo, int R, hipStream_t s, const float *next_gain = nullptr);
-int mfma_out_ffn(pd_ctx *c, GemmArgs &a, const bf16_t *p_wo, const LayerPtrs &lw, int R, hipStream_t s);
+// next_gain != NULL: the second FFN projection may prepare the next layer's first norm (sets c->norm_fused)
+int mfma_out_ffn(pd_ctx *c, GemmArgs &a, const bf16_t *p_wo, const LayerPtrs &lw, int R, hipStream_t s,
+                 const float *next_gain = nullptr);
 bool mfma_can_fuse_norm(pd_ctx *c, int R);
 int mfma_fold(float *c1, float *c2, const bf16_t *Wp, const float *gain, const float *bias, int n_out, int K,
               hipStream_t s);

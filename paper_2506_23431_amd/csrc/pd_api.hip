@@ -193,6 +193,7 @@ static size_t carve(const pd_config *g, char *base, pd_ctx *c, const pd_encdec_c
       lp.c1 = cv.take<float>((g->ffn_kind == 1 ? 2 : 1) * (size_t)ff);
       lp.c2 = cv.take<float>((g->ffn_kind == 1 ? 2 : 1) * (size_t)ff);
       lp.cx1 = e ? cv.take<float>(dd) : nullptr;
+      lp.q1 = cv.take<float>(3 * dd); lp.q2 = cv.take<float>(3 * dd);
     }
     x->nstats = cv.take<float2>((size_t)16 * (d / 16));
     x->p_lm_head = cv.take<bf16_t>((size_t)x->vocab_pad * d);
@@ -472,7 +473,7 @@ extern "C" int pd_set_option(pd_ctx *c, int key, int value) {
     case PD_OPT_STREAM_LOADS:
       c->stream_loads = value ? 1 : 0; drop_graph(c); return PD_OK;
     case PD_OPT_FUSE_NORM:
-      c->opt_fuse_norm = value ? 1 : 0; drop_graph(c); return PD_OK;
+      c->opt_fuse_norm = value < 0 ? 0 : value > 2 ? 2 : value; drop_graph(c); return PD_OK;
     case PD_OPT_PROFILE:
       c->opt_profile = (value == 2 || value == 3) ? value : (value ? 1 : 0); drop_graph(c); c->ev_used = 0; return PD_OK;
     default:

@@ -106,6 +106,7 @@ struct LayerPtrs {
   bf16_t *p_wqkv, *p_wo, *p_w1, *p_w2;
   float *c1, *c2;                                  // p_w1 times the second norm's gain / bias, per packed column
   float *cx1;                                      // p_cq times the gain of the norm in front of it
+  float *q1, *q2;                                  // p_wqkv times the first norm's gain / bias (layers after the first)
   void *kc, *vc;                                   // KV caches of this layer
   void *kc_lo, *vc_lo;                             // low halves (layers below kv_pair_layers), else NULL
   // encoder-decoder form, decoder layers: attention over the encoder states

@@ -554,6 +554,27 @@ def test_separate_second_norm_kernel(name):
     dec.close()
 
 
+@pytest.mark.parametrize("name", ["mfma-hd64", "mfma-hd32", "mfma-hd96", "mfma-sequential", "mfma-flat", "rms-learned"])
+def test_first_norm_prepared_by_the_previous_layer(name):
+    """Value 2 of PD_OPT_FUSE_NORM: the second FFN projection of a layer completes the residual rows and
+    hands gain * x with its row sums to the next layer's QKV projection, which finishes that layer's first
+    norm in its epilogue (steps of at most 16 rows, no rotary positions): packed pairs, separate low
+    parts, LayerNorm with bias and RMSNorm."""
+    from paper_2506_23431_amd import binding
+    cfg = CASES[name] if name in CASES else small(name, seed=52, dtype=DTYPE_BF16, d_model=160, n_head=5,
+                                                   head_dim=32, d_ff=288, vocab=700, ctx_len=61, n_sub=5,
+                                                   delta_t=1, sub_tokens=6, batch=2, n_layer=3,
+                                                   norm_kind=NORM_RMSNORM)
+    w = pi.make_weights(cfg, threads=4)
+    ctx = pi.make_context(cfg)
+    outs = oracle_run(cfg, w, ctx)
+    dec = make_decoder(cfg, w)
+    dec.set_option(binding.PD_OPT_FUSE_NORM, 2)
+    stats = compare_teacher_forced(cfg, w, ctx, dec, outs, log=say)
+    assert stats["rows"] == cfg.batch * (cfg.n_sub * (cfg.sub_tokens + 1) - 1)
+    dec.close()
+
+
 def test_sweep_runs_sequential_and_pipelined():
     """The sweep tool (sequential S = 1 against pipelined schedules with the same token count) runs on
     a two-layer variant of cfg2 and reports the step counts of the schedule's closed form."""
