@@ -286,8 +286,8 @@ int mfma_norm(pd_ctx *c, const float *gain, const float *bias, int R, hipStream_
 // kernel start so that they arrive with the first weights; what lies beyond (very wide models) is
 // read when the sums are taken.  Fixed order, no atomics: deterministic.
 constexpr int PS = 4;
-__device__ __forceinline__ void stats_request(const GemmArgs &a, int lane, int w, int nw, float4 (&pre)[PS]) {
-  const int m = lane & 15, g = lane >> 4, npair = a.stats_tiles >> 1;
+__device__ __forceinline__ void stats_request(const GemmArgs &a, int lane, int w, int nw, float4 (&pre)[PS], int r0) {
+  const int m = r0 + (lane & 15), g = lane >> 4, npair = a.stats_tiles >> 1;
   const float4 *sp = (const float4 *)(a.stats_in + (size_t)m * a.stats_tiles);
 #pragma unroll
   for (int u = 0; u < PS; ++u) {
@@ -295,8 +295,8 @@ __device__ __forceinline__ void stats_request(const GemmArgs &a, int lane, int w
     if (4 * (w + nw * u) < npair) pre[u] = sp[min(g + 4 * (w + nw * u), npair - 1)];   // the same for the whole wave
   }
 }
-__device__ __forceinline__ float2 stats_partial(const GemmArgs &a, int lane, int w, int nw, const float4 (&pre)[PS]) {
-  const int m = lane & 15, g = lane >> 4, npair = a.stats_tiles >> 1;
+__device__ __forceinline__ float2 stats_partial(const GemmArgs &a, int lane, int w, int nw, const float4 (&pre)[PS], int r0) {
+  const int m = r0 + (lane & 15), g = lane >> 4, npair = a.stats_tiles >> 1;
   const float4 *sp = (const float4 *)(a.stats_in + (size_t)m * a.stats_tiles);
   float s1 = 0.f, s2 = 0.f;
 #pragma unroll
@@ -557,7 +557,7 @@ __global__ __launch_bounds__(64 * NW_K) void k_gemm_s(GemmArgs a) {
   float4 pre_s[PS];
   const bool fused_norm = FUSED_IN && a.stats_in != nullptr;          // the same for the whole launch
   NormPre pre_n;
-  if (fused_norm) stats_request(a, lane, wk, NW_K, pre_s);
+  if (fused_norm) stats_request(a, lane, wk, NW_K, pre_s, rz * 16);
   if (fused_norm && wk < NT) {      // wave w < NT finishes tile nt0 + w
     const int n0 = min(nt0 + wk, a.n_tiles - 1) * 16 + 4 * (lane >> 4);
     pre_n.c1 = *(const float4 *)(a.c1 + n0);
@@ -569,7 +569,7 @@ __global__ __launch_bounds__(64 * NW_K) void k_gemm_s(GemmArgs a) {
     pre_r.g = *(const float4 *)(a.gain + n0);
     // (rows beyond R read row R - 1 and are masked where the value is used, not here: touching the
     // value now would make the wave wait for it before it has asked for its weights)
-    pre_r.x = *(const float4 *)(a.x_res + (size_t)min(m, max(a.R - 1, 0)) * a.ld + n0);
+    pre_r.x = *(const float4 *)(a.x_res + (size_t)min(rz * 16 + m, max(a.R - 1, 0)) * a.ld + n0);
   }
   constexpr int NA = (SPLIT && NT * RT <= 2) ? 2 : 1;
   floatx4 acc2[NT][RT][NA];
@@ -604,7 +604,7 @@ __global__ __launch_bounds__(64 * NW_K) void k_gemm_s(GemmArgs a) {
 #pragma unroll
       for (int i = 0; i < RT; ++i) red[((wk * NT + t) * RT + i) * 64 + lane] = acc[t][i];
     if (fused_norm) {
-      float2 sp = stats_partial(a, lane, wk, NW_K, pre_s);
+      float2 sp = stats_partial(a, lane, wk, NW_K, pre_s, rz * 16);
       if (lane < 16) sm_stat[wk][lane] = sp;
     }
     __syncthreads();
@@ -628,7 +628,7 @@ __global__ __launch_bounds__(64 * NW_K) void k_gemm_s(GemmArgs a) {
     }
   } else {
     float2 nrm[RT];
-    if (fused_norm) nrm[0] = stats_finish(a, stats_partial(a, lane, 0, 1, pre_s));
+    if (fused_norm) nrm[0] = stats_finish(a, stats_partial(a, lane, 0, 1, pre_s, rz * 16));
 #pragma unroll
     for (int t = 0; t < NT; ++t)
       if (nt0 + t < a.n_tiles)
@@ -716,14 +716,17 @@ static int launch_gemm_wide_nt(GemmArgs a, int ks, hipStream_t s) {
 template <int RT, int EPI, bool SPLIT>
 static int launch_gemm_wide(const GemmArgs &a, hipStream_t s) {
   // 4 * NT * RT KiB of LDS, at most 128-160; with 2 row tiles more than 4 column tiles measured slower
-  constexpr int NT_MAX = RT <= 2 ? 4 : (RT <= 4 ? 8 : (RT == 5 ? 6 : 4));
-  static const int nts[] = {1, 2, 3, 4, 6, 8};
+  // (7 only with 5 row tiles: the vocabulary projection of a 72-row step then makes 449 blocks, two rounds
+  // of one block per compute unit, instead of 524 with 6, where 12 blocks run a third round alone)
+  constexpr int NT_MAX = RT <= 2 ? 4 : (RT <= 4 ? 8 : (RT == 5 ? 7 : 4));
+  static const int nts[] = {1, 2, 3, 4, 6, 7, 8};
   int KT = a.K / 32, best_nt = 1, best_ks = 1;
   long best = -1;
   for (int ks = 1; ks <= (EPI == EPI_RESID ? a.max_parts : 1); ks *= 2) {
     if (ks > 1 && KT / ks < 8) break;
     for (int nt : nts) {
       if (nt > NT_MAX) break;
+      if (nt == 7 && RT != 5) continue;
       long blocks = (long)((a.n_tiles + nt - 1) / nt) * ks;
       long rounds = (blocks + 255) / 256;
       long cost = rounds * ((KT + ks - 1) / ks) * (nt + 2 * RT);
@@ -736,6 +739,7 @@ static int launch_gemm_wide(const GemmArgs &a, hipStream_t s) {
     case 3: return launch_gemm_wide_nt<RT, 3, EPI, SPLIT>(a, best_ks, s);
     case 4: return launch_gemm_wide_nt<RT, 4, EPI, SPLIT>(a, best_ks, s);
     case 6: return launch_gemm_wide_nt<RT, (NT_MAX >= 6 ? 6 : NT_MAX), EPI, SPLIT>(a, best_ks, s);
+    case 7: return launch_gemm_wide_nt<RT, (RT == 5 ? 7 : 1), EPI, SPLIT>(a, best_ks, s);
     default: return launch_gemm_wide_nt<RT, (NT_MAX >= 8 ? 8 : NT_MAX), EPI, SPLIT>(a, best_ks, s);
   }
 }
@@ -891,9 +895,11 @@ static int launch_gemm_rows(const GemmArgs &a, int rows, hipStream_t s) {
 // share one L2 and the repeats stay out of HBM.  Measured at 72 rows, width 1024 (cfg3): QKV 10.9 -> 6.9 us, first
 // FFN projection 11.5 -> 9.5, output projection 4.0 (K slices of 8 k-tiles), second FFN projection 8.4 -> 7.7;
 // 0.83 -> 0.76 ms per step.
-template <int EPI, bool SPLIT>
+// A projection that completes the residual rows and prepares the next norm (never cut along K over blocks)
+// takes one column tile per block, so that the launch still has a block per compute unit: 64 x 5 at width 1024.
+template <int EPI, bool SPLIT, int NT = 4>
 static int launch_gemm_zrows(GemmArgs a, int rows, hipStream_t s) {
-  constexpr int NT = 4, U = 4;
+  constexpr int U = 4;
   const int KT = a.K / 32, groups = (a.n_tiles + NT - 1) / NT, rts = (rows + 15) / 16;
   // the residual projections also cut K into slices over blocks (summed by the next norm kernel) until the
   // launch has a block per compute unit
@@ -915,10 +921,11 @@ static int launch_gemm_zrows(GemmArgs a, int rows, hipStream_t s) {
 
 template <int EPI, bool SPLIT>
 static int launch_gemm_split(const GemmArgs &a, int rows, hipStream_t s) {
-  constexpr bool zrows = EPI == EPI_QKV || EPI == EPI_QKV_ROPE || EPI == EPI_GELU || EPI == EPI_SWIGLU || EPI == EPI_RESID;
-  if (zrows && rows > 16 && (size_t)a.n_tiles * 16 * a.K * 2 <= ((size_t)16 << 20) &&
-      a.K / 32 <= 64 * (EPI == EPI_RESID ? a.max_parts : 1))
-    return launch_gemm_zrows<EPI, SPLIT>(a, rows, s);
+  constexpr bool zrows = EPI != EPI_LM;
+  if (zrows && mfma_gemm_row_tile_blocks(a.n_tiles, a.K, rows, EPI == EPI_RESID ? a.max_parts : 1))
+    return launch_gemm_zrows<EPI, SPLIT, (EPI == EPI_RESID_NORM ? 1 : 4)>(a, rows, s);
+  if (EPI == EPI_RESID_NORM || EPI == EPI_QKV_NORM)
+    PD_REQUIRE(rows <= 16, PD_EINVAL, "a projection of this shape cannot prepare or finish a norm for %d rows", rows);
   switch (mfma_gemm_row_tiles(rows)) {
     case 16: return launch_gemm_small<1, EPI, SPLIT, false>(a, s);
     case 32: return launch_gemm_wide<2, EPI, SPLIT>(a, s);
@@ -931,7 +938,8 @@ static int launch_gemm_split(const GemmArgs &a, int rows, hipStream_t s) {
 template <int EPI>
 static int launch_gemm(const GemmArgs &a, int rows, hipStream_t s) {
   if (EPI == EPI_RESID_NORM || EPI == EPI_QKV_NORM)
-    PD_REQUIRE(rows <= 16 && a.R <= 16, PD_EINVAL, "projections that prepare or finish a norm take at most 16 rows (%d)", rows);
+    PD_REQUIRE(rows <= 128 && a.R <= 128, PD_EINVAL,
+               "projections that prepare or finish a norm take at most 128 rows (%d)", rows);
   if (rows > 128) {
     PD_REQUIRE(!a.packed, PD_EINVAL, "packed activations hold at most 8 rows (%d)", rows);
     return a.xn_lo ? launch_gemm_rows<EPI, true>(a, rows, s) : launch_gemm_rows<EPI, false>(a, rows, s);
@@ -947,6 +955,12 @@ static int launch_gemm(const GemmArgs &a, int rows, hipStream_t s) {
 int PD_GEMM_ENTRY(const GemmArgs &a, int rows, hipStream_t s) { return launch_gemm<PD_GEMM_EPI>(a, rows, s); }
 
 #else   // ---- common part: dispatcher ----------------------------------------------------------
+
+// 17-128 rows against a weight matrix of at most 16 MB and a K that 8 waves (times the K slices over blocks)
+// cover in batches of 4 k-tiles: the launch gives every row tile blocks of its own (launch_gemm_zrows)
+bool mfma_gemm_row_tile_blocks(int n_tiles, int K, int rows, int k_slices) {
+  return rows > 16 && rows <= 128 && (size_t)n_tiles * 16 * K * 2 <= ((size_t)16 << 20) && K / 32 <= 64 * k_slices;
+}
 
 int mfma_gemm_row_tiles(int rows) {
   int rt = (rows + 15) / 16;

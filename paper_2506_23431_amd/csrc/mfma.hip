@@ -21,16 +21,20 @@ void mfma_gemm_base(pd_ctx *c, GemmArgs &a, int R) {
 // caches at the rows' slots.  `n_tiles` 16-column tiles of W, whose first d columns are section `sec0`
 // (0: queries, then keys, then values; 1: keys, then values).
 // An output projection (contraction over d_model) can prepare the next norm, and the projection behind
-// that norm finish it, when the step has one row tile.
+// that norm finish it, when every block of both launches works on one row tile: steps of at most 16 rows,
+// and steps of up to 128 rows whose projections are launched with a row tile per block (here: a d x d
+// producer and a d x d consumer; wider consumers are checked where they are launched).
 bool mfma_can_fuse_norm(pd_ctx *c, int R) {
-  return c->opt_fuse_norm && R <= 16 && mfma_gemm_row_tiles(R) == 16;
+  if (!c->opt_fuse_norm) return false;
+  const int d = c->cfg.d_model;
+  return R <= 16 || mfma_gemm_row_tile_blocks(d / 16, d, R, 1);
 }
 // The second FFN projection has to give up its cut along K over blocks for this, which leaves one block
 // per 16 output columns.  With the next layer's QKV projection finishing the norm, a step of the 768 / 3072
 // shape measured 0.198 ms against 0.188 ms and one of the 2048 / 8192 shape 1.33-1.34 ms against 1.31 ms
 // (the uncut projection loses what the norm kernel took): only on request (value 2 of the option).
 static bool ffn2_prepares_norm(pd_ctx *c, int R) {
-  return mfma_can_fuse_norm(c, R) && c->opt_fuse_norm == 2 && c->cfg.pos_kind != 1;
+  return R <= 16 && mfma_can_fuse_norm(c, R) && c->opt_fuse_norm == 2 && c->cfg.pos_kind != 1;
 }
 
 int mfma_qkv(pd_ctx *c, GemmArgs &a, const bf16_t *W, int n_tiles, int sec0, void *kc, void *vc, void *kc_lo,
@@ -77,7 +81,8 @@ int mfma_out_ffn(pd_ctx *c, GemmArgs &a, const bf16_t *p_wo, const LayerPtrs &lw
   // At most 16 rows: the projection is not cut along K over blocks, so its epilogue holds the final
   // x + y.  It writes x, gain * x as the activation fragments of the FFN, and per-tile row sums; the
   // first FFN projection finishes the norm in its epilogue and the norm kernel in between is gone.
-  const bool fuse = c->opt_fuse_norm && lw.c1 && R <= 16 && mfma_gemm_row_tiles(R) == 16;
+  const int ffn1_tiles = (g.ffn_kind == 1 ? 2 : 1) * ff / 16;
+  const bool fuse = lw.c1 && mfma_can_fuse_norm(c, R) && (R <= 16 || mfma_gemm_row_tile_blocks(ffn1_tiles, d, R, 1));
   if (fuse) {
     a.x_res = c->x; a.gain = lw.n2g; a.stats_out = c->nstats;
     a.out_bf = (bf16_t *)c->xn; a.out_lo = mfma_lo(c, c->xn, d);

@@ -135,6 +135,8 @@ struct GemmArgs {
 
 int mfma_gemm(int epi, const GemmArgs &a, int rows, hipStream_t s);
 int mfma_gemm_row_tiles(int rows);            // rows a launch reads/writes: 16 * RT
+// whether a projection of n_tiles x K at this many rows is launched with one row tile per block
+bool mfma_gemm_row_tile_blocks(int n_tiles, int K, int rows, int k_slices);
 int mfma_norm(pd_ctx *c, const float *gain, const float *bias, int R, hipStream_t s);
 // low-part twin of an activation buffer (NULL when the split is switched off)
 bf16_t *mfma_lo(pd_ctx *c, void *buf, size_t cols);

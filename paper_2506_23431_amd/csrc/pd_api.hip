@@ -195,7 +195,7 @@ static size_t carve(const pd_config *g, char *base, pd_ctx *c, const pd_encdec_c
       lp.cx1 = e ? cv.take<float>(dd) : nullptr;
       lp.q1 = cv.take<float>(3 * dd); lp.q2 = cv.take<float>(3 * dd);
     }
-    x->nstats = cv.take<float2>((size_t)16 * (d / 16));
+    x->nstats = cv.take<float2>(std::min<size_t>(Rp, 128) * (d / 16));   // steps of up to 128 rows hand norms over
     x->p_lm_head = cv.take<bf16_t>((size_t)x->vocab_pad * d);
     if (e) {
       for (LayerPtrs &lp : x->ed.enc) {
