@@ -252,7 +252,8 @@ int pd_reset_decode(pd_ctx *ctx, void *hip_stream);
  *                        path, 128 on the fp32 path; other values are rounded up to a multiple
  *                        of 16 and capped at that default).  Results do not depend on it beyond
  *                        rounding order.
- *   PD_OPT_FUSE_NORM     1 (default): in steps of at most 16 rows the output projection adds its result
+ *   PD_OPT_FUSE_NORM     1 (default): in steps of at most 16 rows (and of up to 128 rows against small
+ *                        matrices, where every block works on one row tile) the output projection adds its result
  *                        to the residual stream itself, hands gain * x and per-tile row sums to the
  *                        first FFN projection, and that projection finishes the second norm of the
  *                        layer in its epilogue (one kernel less per layer); 0: a separate norm kernel,
