@@ -538,10 +538,11 @@ def test_options_do_not_change_results():
         dec.close()
 
 
-@pytest.mark.parametrize("name", ["mfma-hd64", "mfma-llama-packed", "mfma-hd128-llama", "mfma-hd32"])
+@pytest.mark.parametrize("name", ["mfma-hd64", "mfma-llama-packed", "mfma-hd128-llama", "mfma-hd32", "mfma-manyrows"])
 def test_separate_second_norm_kernel(name):
-    """Steps of at most 16 rows normally finish the layer's second norm inside the first FFN projection
-    (PD_OPT_FUSE_NORM); with the option off they take the separate norm kernel that larger steps use."""
+    """Steps of at most 16 rows, and steps of up to 128 rows against small matrices (mfma-manyrows: 40),
+    normally finish the layer's second norm inside the first FFN projection (PD_OPT_FUSE_NORM); with the
+    option off they take the separate norm kernel that all other steps use."""
     from paper_2506_23431_amd import binding
     cfg = CASES[name]
     w = pi.make_weights(cfg, threads=4)
