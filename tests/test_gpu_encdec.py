@@ -34,7 +34,7 @@ CASES = {
     # one request, at most 5 rows: every decode step keeps its activations as packed pairs
     "encdec-hd128-packed": E("encdec-hd128-packed", 63, d_model=256, n_head=2, head_dim=128, d_ff=352, vocab=777,
                              ctx_len=200, n_sub=6, delta_t=2, sub_tokens=9, batch=1),
-    # up to 40 rows per step (three row tiles, no fused norm), input of exactly one 32-key block
+    # up to 40 rows per step (three row tiles, each with blocks of its own), input of exactly one 32-key block
     "encdec-manyrows": E("encdec-manyrows", 64, n_enc_layer=1, n_dec_layer=1, vocab=640, ctx_len=32, n_sub=20,
                          delta_t=1, sub_tokens=24, batch=2),
     # S = 1: ordinary greedy decoding with ordinary relative positions; input of one token
@@ -68,6 +68,22 @@ def make(cfg):
 @pytest.mark.parametrize("name", list(CASES))
 def test_encoder_decoder_parity(name):
     cfg = CASES[name]
+    say(f"[encdec] {name}: {cfg}")
+    rounded, ctx, dec = make(cfg)
+    outs = oracle_run(cfg, rounded, ctx)
+    stats = compare_teacher_forced(cfg, None, ctx, dec, outs, tol=2e-2, log=say)
+    assert stats["rows"] == cfg.batch * (cfg.n_sub * (cfg.sub_tokens + 1) - 1)
+    assert stats["exact"] > 0
+    dec.close()
+
+
+@pytest.mark.parametrize("name", sorted(pi.ENCDEC_CONFIGS))
+def test_backbone_shaped_models_at_full_size(name):
+    """The backbone-shaped models the sweep measures (Section 5.1: base and large size, and a smaller one;
+    random weights): 6 + 6 to 24 + 24 layers, 512 input tokens, vocabulary 32128, one request, 8
+    subsequences of 16 tokens.  The encoder pass runs the many-row kernels, the decode steps the packed
+    ones, the two larger models with streamed weight loads."""
+    cfg = pi.ENCDEC_CONFIGS[name]
     say(f"[encdec] {name}: {cfg}")
     rounded, ctx, dec = make(cfg)
     outs = oracle_run(cfg, rounded, ctx)
