@@ -133,3 +133,15 @@ def test_teacher_forced_rejects_what_it_cannot_run():
         with pytest.raises(PdError, match="matrix-core"):
             d2.teacher_forced([[[0, 1]]] * f32.batch)
         d2.close()
+
+
+def test_teacher_forced_at_the_full_size_of_cfg2():
+    """The 768-wide workload at full size (6 layers, 12 heads of 64, vocabulary 50265, 1024 context tokens):
+    one training target of 7 subsequences of 40 .. 63 tokens and the empty one, about 360 rows in one pass."""
+    cfg = pi.get_config("cfg2")
+    g = np.random.Generator(np.random.Philox(key=[cfg.seed, 9]))
+    Y = [[int(t) for t in g.integers(2, cfg.vocab, size=int(g.integers(40, 64)))] for _ in range(7)]
+    target = training.training_target(Y, cfg.bos_id, 1)
+    assert sum(len(s) for s in target) > 300
+    worst = check(cfg, [target])
+    assert worst < 5e-3
