@@ -77,13 +77,15 @@ def test_encoder_decoder_parity(name):
     dec.close()
 
 
-@pytest.mark.parametrize("name", sorted(pi.ENCDEC_CONFIGS))
+@pytest.mark.parametrize("name", sorted(pi.ENCDEC_CONFIGS) + ["encdec-base-x4"])
 def test_backbone_shaped_models_at_full_size(name):
     """The backbone-shaped models the sweep measures (Section 5.1: base and large size, and a smaller one;
     random weights): 6 + 6 to 24 + 24 layers, 512 input tokens, vocabulary 32128, one request, 8
     subsequences of 16 tokens.  The encoder pass runs the many-row kernels, the decode steps the packed
-    ones, the two larger models with streamed weight loads."""
-    cfg = pi.ENCDEC_CONFIGS[name]
+    ones, the two larger models with streamed weight loads.  The base size also with four requests at
+    once: 32 rows per step, two row tiles."""
+    cfg = (pi.ENCDEC_CONFIGS["encdec-base"].scaled(name="encdec-base-x4", batch=4) if name.endswith("-x4")
+           else pi.ENCDEC_CONFIGS[name])
     say(f"[encdec] {name}: {cfg}")
     rounded, ctx, dec = make(cfg)
     outs = oracle_run(cfg, rounded, ctx)
