@@ -535,6 +535,9 @@ def test_options_do_not_change_results():
         dec.set_option(binding.PD_OPT_SPLIT_ACT, 0)
         outs = oracle_run(cfg, w, ctx)
         compare_teacher_forced(cfg, w, ctx, dec, outs, log=say)
+        # ... also with a context pass in chunks of 40 rows (three row tiles, each with blocks of its own)
+        dec.set_option(binding.PD_OPT_PREFILL_CHUNK, 40)
+        compare_teacher_forced(cfg, w, ctx, dec, outs, log=say)
         dec.close()
 
 
