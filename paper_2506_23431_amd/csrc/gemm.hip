@@ -764,7 +764,7 @@ __global__ __launch_bounds__(64 * NW, OCC) void k_gemm_p(GemmArgs a) {
   static_assert(NW == 4 || NW == 8, "4 or 8 waves");
   constexpr int RT = 8, NA = SPLIT ? 2 * RT : RT, NAW = NA / NW;   // fragments per k-tile: all / staged by one wave
   static_assert(D % 2 == 0 || D == 1, "stages alternate between the two LDS buffers");
-  __shared__ uint4 sm_x[2][NA][64];
+  __shared__ bf16x8 sm_x[2][NA][64];   // (vector types throughout: struct copies would keep xr in scratch memory)
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int m = lane & 15;
   const int KT = a.K >> 5;
@@ -788,15 +788,15 @@ __global__ __launch_bounds__(64 * NW, OCC) void k_gemm_p(GemmArgs a) {
   const uint4 *wp = (const uint4 *)a.W + lane;
   // this wave's share of the activation fragments: fragment f = w * NAW + j is row tile f % RT of
   // the high (f < RT) or low parts
-  const uint4 *xsrc[NAW];
+  const bf16x8 *xsrc[NAW];
 #pragma unroll
   for (int j = 0; j < NAW; ++j) {
     int f = w * NAW + j;
     const bf16_t *base = (SPLIT && f >= RT) ? a.xn_lo : a.xn;
-    xsrc[j] = (const uint4 *)base + (size_t)(rt0 + f % RT) * KT * 64 + lane;
+    xsrc[j] = (const bf16x8 *)base + (size_t)(rt0 + f % RT) * KT * 64 + lane;
   }
   // D k-tiles are in flight per wave, each in registers of its own (slot = k-tile index mod D)
-  uint4 xr[D][NAW];
+  Frag xr[D][NAW];
   Frag wr[D][NT];
   const int len = kt1 - kt0;
   auto k_of = [&](int j) { return kt0 + min(j, len - 1); };   // steps past the end repeat the last k-tile
@@ -804,7 +804,7 @@ __global__ __launch_bounds__(64 * NW, OCC) void k_gemm_p(GemmArgs a) {
   for (int d = 0; d < D; ++d) {
     int k = len > 0 ? k_of(d) : 0;
 #pragma unroll
-    for (int j = 0; j < NAW; ++j) xr[d][j] = xsrc[j][(size_t)k * 64];
+    for (int j = 0; j < NAW; ++j) xr[d][j].v = xsrc[j][(size_t)k * 64];
 #pragma unroll
     for (int t = 0; t < NT; ++t) wr[d][t].u = wp[((size_t)tile[t] * KT + k) * 64];
   }
@@ -815,34 +815,44 @@ __global__ __launch_bounds__(64 * NW, OCC) void k_gemm_p(GemmArgs a) {
         const int buf = D == 1 ? (j0 & 1) : (d & 1);
         Frag wc[NT];
 #pragma unroll
-        for (int j = 0; j < NAW; ++j) sm_x[buf][w * NAW + j][lane] = xr[d][j];
+        for (int j = 0; j < NAW; ++j) sm_x[buf][w * NAW + j][lane] = xr[d][j].v;
 #pragma unroll
         for (int t = 0; t < NT; ++t) wc[t] = wr[d][t];
         {                           // refill the slot with the k-tile D further on
           int k = k_of(j0 + d + D);
 #pragma unroll
-          for (int j = 0; j < NAW; ++j) xr[d][j] = xsrc[j][(size_t)k * 64];
+          for (int j = 0; j < NAW; ++j) xr[d][j].v = xsrc[j][(size_t)k * 64];
 #pragma unroll
           for (int t = 0; t < NT; ++t) wr[d][t].u = wp[((size_t)tile[t] * KT + k) * 64];
         }
         // one barrier per k-tile is enough with two buffers: a wave can only write k-tile i + 2 into
         // this buffer after the barrier of k-tile i + 1, which every wave reaches after its reads of i
         __syncthreads();
-        // all LDS reads of the k-tile are issued before the first multiply (left to itself the
-        // compiler reads two fragments at a time and waits for each pair)
-        Frag xf[NA];
+        // The k-tile's fragments pass from LDS to the matrix cores in groups of GS (fragment f: row tile
+        // f % RT, high parts first): two groups are requested up front, and while one group is multiplied
+        // the next but one is requested into the registers of the group before it.  A wave then holds 2 GS
+        // fragments instead of all NA (which, with the accumulators and the weights in flight, did not fit
+        // the 256 registers of a wave at two waves per SIMD), and its LDS reads run under its multiplies.
+        // Products into the same accumulator (high and low part of a row tile) are NT * RT multiplies apart.
+        constexpr int GS = 4, NG = NA / GS;
+        Frag xg[2][GS];
 #pragma unroll
-        for (int f = 0; f < NA; ++f) xf[f].u = sm_x[buf][f][lane];
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+          for (int u = 0; u < GS; ++u) xg[h][u].v = sm_x[buf][h * GS + u][lane];
         __builtin_amdgcn_sched_barrier(0);
-        // (two products into the same accumulator are kept NT multiplies apart: back to back the
-        // second would wait for the first to leave the pipeline)
 #pragma unroll
-        for (int i = 0; i < RT; ++i) {
+        for (int gi = 0; gi < NG; ++gi) {
 #pragma unroll
-          for (int t = 0; t < NT; ++t) acc[t][i] = mfma16(wc[t], xf[i], acc[t][i]);
-          if (SPLIT) {
+          for (int u = 0; u < GS; ++u)
 #pragma unroll
-            for (int t = 0; t < NT; ++t) acc[t][i] = mfma16(wc[t], xf[RT + i], acc[t][i]);
+            for (int t = 0; t < NT; ++t)
+              acc[t][(gi * GS + u) % RT] = mfma16(wc[t], xg[gi & 1][u], acc[t][(gi * GS + u) % RT]);
+          __builtin_amdgcn_sched_barrier(0);
+          if (gi + 2 < NG) {
+#pragma unroll
+            for (int u = 0; u < GS; ++u) xg[gi & 1][u].v = sm_x[buf][(gi + 2) * GS + u][lane];
+            __builtin_amdgcn_sched_barrier(0);
           }
         }
       }
