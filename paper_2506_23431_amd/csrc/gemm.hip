@@ -228,12 +228,106 @@ __global__ __launch_bounds__(256) void k_norm_bf16(bf16_t *xn, bf16_t *xn_lo, co
   }
 }
 
+// The same for launches of many rows (the context pass): a wave per row, four rows per block.  Lane l takes the
+// 8-value granules l, l + 64, ... of its row, the two sums are wave reductions (no barrier, no LDS), and gain and
+// bias are asked for only when the statistics are known (they sit in the caches), so a wave holds little more
+// than its row and many waves are resident.
+template <int NGW, int NP>     // granules per lane: d <= 512 * NGW; NP pending slices
+__global__ __launch_bounds__(256) void k_norm_rows(bf16_t *xn, bf16_t *xn_lo, float *x, const float *g,
+                                                   const float *b, int d, int kind, float eps,
+                                                   const int32_t *flags, int R, const float *ypart,
+                                                   size_t part_stride) {
+  const int lane = threadIdx.x & 63, r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const bool valid = r < R && (flags[r] & ROW_VALID);
+  float *xr = x + (size_t)r * d;
+  float v[NGW][8];
+#pragma unroll
+  for (int i = 0; i < NGW; ++i) {
+    const int c = (lane + 64 * i) * 8;
+    const bool in = c < d;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      float4 t = in ? *(const float4 *)(xr + c + 4 * h) : make_float4(0.f, 0.f, 0.f, 0.f);
+      float4 y[NP > 0 ? NP : 1];
+#pragma unroll
+      for (int pp = 0; pp < NP; ++pp)
+        y[pp] = in ? *(const float4 *)(ypart + pp * part_stride + (size_t)r * d + c + 4 * h)
+                   : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+      for (int pp = 0; pp < NP; ++pp) { t.x += y[pp].x; t.y += y[pp].y; t.z += y[pp].z; t.w += y[pp].w; }
+      if (NP > 0 && in && r < R) *(float4 *)(xr + c + 4 * h) = t;
+      v[i][4 * h] = t.x; v[i][4 * h + 1] = t.y; v[i][4 * h + 2] = t.z; v[i][4 * h + 3] = t.w;
+    }
+  }
+  float s1 = 0.f;
+#pragma unroll
+  for (int i = 0; i < NGW; ++i)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s1 += v[i][e];
+  for (int o = 32; o > 0; o >>= 1) s1 += __shfl_xor(s1, o);
+  const float mean = kind == 0 ? s1 / d : 0.f;
+  float q = 0.f;
+#pragma unroll
+  for (int i = 0; i < NGW; ++i) {
+    const bool in = (lane + 64 * i) * 8 < d;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float t = in ? v[i][e] - mean : 0.f;
+      q += t * t;
+    }
+  }
+  for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o);
+  const float rstd = rsqrtf(q / d + eps);
+#pragma unroll
+  for (int i = 0; i < NGW; ++i) {
+    const int c = (lane + 64 * i) * 8;
+    if (c >= d) continue;
+    float gv[8], bv[8];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      float4 tg = *(const float4 *)(g + c + 4 * h);
+      float4 tb = (kind == 0 && b) ? *(const float4 *)(b + c + 4 * h) : make_float4(0.f, 0.f, 0.f, 0.f);
+      gv[4 * h] = tg.x; gv[4 * h + 1] = tg.y; gv[4 * h + 2] = tg.z; gv[4 * h + 3] = tg.w;
+      bv[4 * h] = tb.x; bv[4 * h + 1] = tb.y; bv[4 * h + 2] = tb.z; bv[4 * h + 3] = tb.w;
+    }
+    Frag hi, lo;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float y = valid ? (v[i][e] - mean) * rstd * gv[e] + bv[e] : 0.f;
+      hi.h[e] = f32_to_bf16(y);
+      lo.h[e] = f32_to_bf16(bf16_residual(y, hi.h[e]));
+    }
+    size_t off = act_off(r, c, d);
+    *(uint4 *)(xn + off) = hi.u;
+    if (xn_lo) *(uint4 *)(xn_lo + off) = lo.u;
+  }
+}
+
 int mfma_norm(pd_ctx *c, const float *gain, const float *bias, int R, hipStream_t s) {
   // packed pairs: rows 8-15 of the fragments belong to the low parts of rows 0-7
   int rows = c->packed ? 8 : (R + 15) / 16 * 16, d = c->cfg.d_model;
   bf16_t *xn = (bf16_t *)c->xn;
   const pd_config &g = c->cfg;
   PD_REQUIRE(d <= 2048 * 4, PD_EINVAL, "d_model %d too large for the norm kernel", d);
+  if (rows > 128 && !c->embed_pending && !c->packed) {
+#define PD_NORM_R(G, P)                                                                           \
+  hipLaunchKernelGGL((k_norm_rows<G, P>), dim3(rows / 4), dim3(256), 0, s, xn, mfma_lo(c, xn, d), c->x, gain, bias, \
+                     d, g.norm_kind, g.norm_eps, c->rows.flags, R, c->ypart, (size_t)c->R_pad * d)
+#define PD_NORM_RP(G)                                                                            \
+  switch (c->pend_parts) {                                                                       \
+    case 0: PD_NORM_R(G, 0); break;                                                              \
+    case 1: PD_NORM_R(G, 1); break;                                                              \
+    case 2: PD_NORM_R(G, 2); break;                                                              \
+    case 4: PD_NORM_R(G, 4); break;                                                              \
+    default: pd_set_error("unsupported number of pending slices: %d", c->pend_parts); return PD_EINVAL; \
+  }
+    if (d <= 2048) { PD_NORM_RP(4) } else if (d <= 4096) { PD_NORM_RP(8) } else { PD_NORM_RP(16) }
+#undef PD_NORM_RP
+#undef PD_NORM_R
+    PD_CHECK_HIP(hipGetLastError());
+    c->pend_parts = 0;
+    return PD_OK;
+  }
 #define PD_NORM(V, P, E)                                                                         \
   hipLaunchKernelGGL((k_norm_bf16<V, P, E>), dim3(rows), dim3(256), 0, s, xn, mfma_lo(c, xn, d), c->x, gain, bias, \
                      d, g.norm_kind, g.norm_eps, c->rows.flags, R, c->x, c->ypart, (size_t)c->R_pad * d,   \
@@ -876,8 +970,9 @@ static int launch_gemm_rows_nt(GemmArgs a, int rows, hipStream_t s) {
 }
 
 // Column tiles per wave (2, 3 or 4; blocks of 8 waves, one block per compute unit): what finishes
-// first by the measured time of a block per k-tile (1.6 / 1.9 / 1.95 us; QKV and FFN1 shapes of cfg4
-// and cfg5 with 1024 rows) times the rounds of 256 blocks the launch needs.
+// first by the measured time of a block per k-tile (1.03 / 1.39 / 1.93 us: close to proportional, the
+// matrix cores set the pace; QKV and FFN1 shapes of cfg4 in chunks of 4096 rows) times the rounds of
+// 256 blocks the launch needs.
 template <int EPI, bool SPLIT>
 static int launch_gemm_rows(const GemmArgs &a, int rows, hipStream_t s) {
   auto cost = [&](int nt, double t) {
@@ -889,7 +984,7 @@ static int launch_gemm_rows(const GemmArgs &a, int rows, hipStream_t s) {
     }
     return (double)((b + 255) / 256) * t;
   };
-  double c2 = cost(2, 1.6), c3 = cost(3, 1.9), c4 = cost(4, 1.95);
+  double c2 = cost(2, 1.03), c3 = cost(3, 1.39), c4 = cost(4, 1.93);
   if (c4 <= c3 && c4 <= c2) return launch_gemm_rows_nt<4, EPI, SPLIT>(a, rows, s);
   if (c3 <= c2) return launch_gemm_rows_nt<3, EPI, SPLIT>(a, rows, s);
   return launch_gemm_rows_nt<2, EPI, SPLIT>(a, rows, s);
