@@ -272,8 +272,8 @@ int pd_reset_decode(pd_ctx *ctx, void *hip_stream);
  *                        the matrix-core kernels): 1 (default) as pairs of bf16 values (high + low part, what the
  *                        decode step uses), 0 as single bf16 values (half the multiplies of its projections).
  *                        Measured over whole runs against the fp64 oracle: width 1024, 24 layers 4.2e-4 -> 2.6e-3
- *                        of logit error for 0.032 -> 0.026 s; width 2048, 24 layers 4.8e-4 -> 3.4e-3 for 0.071 ->
- *                        0.051 s (8192 context tokens), all tokens with a margin above 0.05 unchanged; width
+ *                        of logit error for 0.017 -> 0.014 s; width 2048, 24 layers 4.8e-4 -> 3.4e-3 for 0.049 ->
+ *                        0.036 s (8192 context tokens), all tokens with a margin above 0.05 unchanged; width
  *                        4096, 32 layers 9.3e-4 -> 8.6e-2, outside the 2e-2 tolerance: a caller's trade, not the
  *                        library's.  pd_get_info(PD_INFO_CONTEXT_PAIRS) reports the setting in use.  */
 #define PD_OPT_ATTN_SPLITS 1

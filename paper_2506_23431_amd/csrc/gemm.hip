@@ -848,10 +848,10 @@ static int launch_gemm_wide(const GemmArgs &a, hipStream_t s) {
 // through LDS (two buffers of 16 KiB), and every wave multiplies all of them with its weights.  A
 // k-tile then costs the compute unit 16 + 8 NT requests for 128 NT multiplies, against 16 + NT for
 // 16 NT when the waves cut K instead.
-// Measured with 1024 rows (useful rate; twice that is executed with the low parts): QKV of cfg5
-// 241 us = 0.43 PFLOP/s with NT = 3 (256 blocks), QKV of cfg4 101 us = 0.25 PFLOP/s with NT = 2 (192
-// blocks: the smaller the matrix, the fewer blocks of this size a chunk of rows makes).  With 4
-// waves per block and twice the column tiles per wave the same launches take 450 and 128 us.
+// Measured (useful rate; twice that is executed with the low parts): QKV of cfg5 with 2048 rows
+// 320 us = 0.64 PFLOP/s with NT = 3 (512 blocks), gate + up 608 us = 0.61; QKV of cfg4 with 4096 rows
+// 177 us = 0.58 PFLOP/s.  An earlier version with 4 waves per block and twice the column tiles per
+// wave took nearly twice the time of the 8-wave version of its day.
 // ---------------------------------------------------------------------------
 template <int NT, int D, int OCC, int EPI, bool SPLIT, int NW = 4, int TAG = 0>
 __global__ __launch_bounds__(64 * NW, OCC) void k_gemm_p(GemmArgs a) {

@@ -91,8 +91,8 @@ static size_t carve(const pd_config *g, char *base, pd_ctx *c, const pd_encdec_c
   // encoder states the input only; one capacity serves both kinds
   x->kv_cap = ((e ? std::max(g->max_ctx, x->gen_cap) : g->max_ctx + x->gen_cap) + 63) / 64 * 64;
   // Rows of the context pass per launch: as many as give the many-row projection kernel a block
-  // per compute unit even for small matrices (measured: the cfg4 context pass takes 0.180 s in chunks
-  // of 128 rows, 0.095 s in chunks of 1024, 0.075 s in chunks of 2048 and 0.070 s in chunks of 4096),
+  // per compute unit even for small matrices (measured: the cfg4 context pass takes 0.172 s in chunks
+  // of 128 rows, 0.059 s in chunks of 1024, 0.052 s in chunks of 2048 and 0.049 s in chunks of 4096),
   // at most the 4096 (request, head, 16 rows) units of one attention launch allow.  The fp32 path
   // keeps one score row per (row, head) and stays at 128.
   {
@@ -440,7 +440,7 @@ extern "C" int pd_destroy(pd_ctx *c) {
 // Whether the context pass carries activations as bf16 pairs (high + low part, as the decode step does;
 // the default) or as single bf16 values (PD_OPT_CONTEXT_SPLIT_ACT 0), which halves the multiplies of its
 // projections.  Measured over whole runs against the oracle: width 1024 (cfg3) 4.2e-4 -> 2.6e-3 of logit
-// error and 0.032 -> 0.026 s, width 2048 (cfg4) 4.8e-4 -> 3.4e-3 and 0.071 -> 0.051 s, every token with a
+// error and 0.017 -> 0.014 s, width 2048 (cfg4) 4.8e-4 -> 3.4e-3 and 0.049 -> 0.036 s, every token with a
 // margin above 0.05 still equal; width 4096 with 32 layers (cfg5) 9.3e-4 -> 8.6e-2, and a small model with
 // a vocabulary projection of 15 times the usual scale 2.1e-2: outside the 2e-2 tolerance, which is why
 // the library does not choose single values by itself.
