@@ -268,12 +268,17 @@ int pd_reset_decode(pd_ctx *ctx, void *hip_stream);
  *                        1.37 -> 1.31 ms per step, cfg5 6.55 -> 6.09); 0 for models the cache serves step after
  *                        step (cfg2: 0.187 ms, 0.202 with the hint).  Same results bit for bit.
  *                        pd_get_info(PD_INFO_STREAM_LOADS) reports the setting.
+ *   PD_OPT_CONTEXT_ATTN  attention kernel of the context pass (bf16 path, head_dim 64 or 128, layers without
+ *                        pair caches): 1 (default) the kernel with 32 queries per block where a chunk makes
+ *                        at least 512 such blocks, else the decode step's kernel (16 queries per block, split
+ *                        over the keys); 0 always the decode step's kernel; 2 the 32-query kernel wherever the
+ *                        shape allows it.  Same results up to rounding order.
  *   PD_OPT_CONTEXT_SPLIT_ACT  activations of the context pass (pd_prefill_context of a decoder-only context on
  *                        the matrix-core kernels): 1 (default) as pairs of bf16 values (high + low part, what the
  *                        decode step uses), 0 as single bf16 values (half the multiplies of its projections).
  *                        Measured over whole runs against the fp64 oracle: width 1024, 24 layers 4.2e-4 -> 2.6e-3
- *                        of logit error for 0.017 -> 0.014 s; width 2048, 24 layers 4.8e-4 -> 3.4e-3 for 0.049 ->
- *                        0.036 s (8192 context tokens), all tokens with a margin above 0.05 unchanged; width
+ *                        of logit error for 0.017 -> 0.014 s; width 2048, 24 layers 4.8e-4 -> 3.4e-3 for 0.047 ->
+ *                        0.033 s (8192 context tokens), all tokens with a margin above 0.05 unchanged; width
  *                        4096, 32 layers 9.3e-4 -> 8.6e-2, outside the 2e-2 tolerance: a caller's trade, not the
  *                        library's.  pd_get_info(PD_INFO_CONTEXT_PAIRS) reports the setting in use.  */
 #define PD_OPT_ATTN_SPLITS 1
@@ -284,6 +289,7 @@ int pd_reset_decode(pd_ctx *ctx, void *hip_stream);
 #define PD_OPT_FUSE_NORM 6
 #define PD_OPT_CONTEXT_SPLIT_ACT 7
 #define PD_OPT_STREAM_LOADS 8
+#define PD_OPT_CONTEXT_ATTN 9
 int pd_set_option(pd_ctx *ctx, int key, int value);
 
 /* Average time in microseconds between the two events of the brackets recorded since the

@@ -16,6 +16,7 @@ PD_OPT_ATTN_SPLITS, PD_OPT_USE_GRAPH, PD_OPT_PROFILE, PD_OPT_SPLIT_ACT, PD_OPT_P
 PD_OPT_FUSE_NORM = 6
 PD_OPT_CONTEXT_SPLIT_ACT = 7
 PD_OPT_STREAM_LOADS = 8
+PD_OPT_CONTEXT_ATTN = 9
 PD_INFO_KERNEL_PATH, PD_INFO_KV_PAIR_LAYERS, PD_INFO_KV_SATURATED, PD_INFO_CONTEXT_PAIRS = 1, 2, 3, 4
 PD_INFO_STREAM_LOADS = 5
 

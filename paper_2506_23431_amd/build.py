@@ -11,7 +11,7 @@ LIB = os.path.join(HERE, "libpd.so")
 # (source, extra defines, object name); gemm.hip is compiled once per epilogue (its kernels are many
 # template instances) and once for the parts all epilogues share
 SOURCES = [("pd_api.hip", [], "pd_api.o"), ("sched.hip", [], "sched.o"), ("simple.hip", [], "simple.o"),
-           ("mfma.hip", [], "mfma.o"), ("attn.hip", [], "attn.o"), ("encdec.hip", [], "encdec.o"), ("gemm.hip", [], "gemm.o")] + \
+           ("mfma.hip", [], "mfma.o"), ("attn.hip", [], "attn.o"), ("attn_ctx.hip", [], "attn_ctx.o"), ("encdec.hip", [], "encdec.o"), ("gemm.hip", [], "gemm.o")] + \
           [("gemm.hip", [f"-DPD_GEMM_EPI={e}"], f"gemm_epi{e}.o") for e in range(8)]
 
 

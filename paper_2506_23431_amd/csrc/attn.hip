@@ -384,6 +384,10 @@ static void launch_attn(dim3 grid, hipStream_t s, hipEvent_t e0, hipEvent_t e1, 
 int mfma_attention(pd_ctx *c, const LayerPtrs &lw, int A, int nreq, int req0, int kv_override,
                    hipStream_t s, const AttnMode *mode) {
   const pd_config &g = c->cfg;
+  if (kv_override >= 0 && !mode && c->opt_profile == 0) {     // context pass: many rows per request
+    int rc = mfma_attention_ctx(c, lw, A, nreq, req0, kv_override, s);
+    if (rc != 1) return rc;
+  }
   AttnArgs a;
   memset(&a, 0, sizeof(a));
   a.q = (const f16_t *)c->q; a.q_lo = (const f16_t *)mfma_lo(c, c->q, g.d_model);

@@ -170,3 +170,5 @@ struct AttnMode {
 };
 int mfma_attention(pd_ctx *c, const LayerPtrs &lw, int A, int nreq, int req0, int kv_override,
                    hipStream_t s, const AttnMode *mode = nullptr);
+// context pass, many rows: PD_OK when it ran the launch, 1 when the shape is not one it serves (attn_ctx.hip)
+int mfma_attention_ctx(pd_ctx *c, const LayerPtrs &lw, int A, int nreq, int req0, int n_keys, hipStream_t s);

@@ -228,7 +228,7 @@ __global__ void k_fill_zero(uint4 *p, size_t n16) {
 // the workspace, re-packing the weights.  `c` has its configuration, pointers and carve-up.
 static int finish_create(pd_ctx *c, size_t need, void *hip_stream, bool no_alloc, pd_ctx **out) {
   c->prefilled = false; c->host_steps = 0;
-  c->embed_pending = false; c->norm_fused = false; c->packed = false; c->opt_splits = 0; c->opt_graph = 0; c->opt_profile = 0; c->opt_split = 1; c->opt_chunk = 0; c->opt_fuse_norm = 1; c->opt_ctx_split = 1;
+  c->embed_pending = false; c->norm_fused = false; c->packed = false; c->opt_splits = 0; c->opt_graph = 0; c->opt_profile = 0; c->opt_split = 1; c->opt_chunk = 0; c->opt_fuse_norm = 1; c->opt_ctx_split = 1; c->opt_ctx_attn = 1;
   c->graph_exec = nullptr; c->graph_ready = false; c->ev_used = 0; c->h_pinned = nullptr;
   c->B = c->L = c->Lx = c->S = c->dt = c->M = c->time_max = c->A = c->R = 0;
   {
@@ -440,7 +440,7 @@ extern "C" int pd_destroy(pd_ctx *c) {
 // Whether the context pass carries activations as bf16 pairs (high + low part, as the decode step does;
 // the default) or as single bf16 values (PD_OPT_CONTEXT_SPLIT_ACT 0), which halves the multiplies of its
 // projections.  Measured over whole runs against the oracle: width 1024 (cfg3) 4.2e-4 -> 2.6e-3 of logit
-// error and 0.017 -> 0.014 s, width 2048 (cfg4) 4.8e-4 -> 3.4e-3 and 0.049 -> 0.036 s, every token with a
+// error and 0.017 -> 0.014 s, width 2048 (cfg4) 4.8e-4 -> 3.4e-3 and 0.047 -> 0.033 s, every token with a
 // margin above 0.05 still equal; width 4096 with 32 layers (cfg5) 9.3e-4 -> 8.6e-2, and a small model with
 // a vocabulary projection of 15 times the usual scale 2.1e-2: outside the 2e-2 tolerance, which is why
 // the library does not choose single values by itself.
@@ -472,6 +472,8 @@ extern "C" int pd_set_option(pd_ctx *c, int key, int value) {
       c->opt_ctx_split = value ? 1 : 0; return PD_OK;
     case PD_OPT_STREAM_LOADS:
       c->stream_loads = value ? 1 : 0; drop_graph(c); return PD_OK;
+    case PD_OPT_CONTEXT_ATTN:
+      c->opt_ctx_attn = value < 0 ? 0 : value > 2 ? 2 : value; return PD_OK;
     case PD_OPT_FUSE_NORM:
       c->opt_fuse_norm = value < 0 ? 0 : value > 2 ? 2 : value; drop_graph(c); return PD_OK;
     case PD_OPT_PROFILE:

@@ -182,7 +182,7 @@ struct pd_ctx {
   bool prefilled;
   int host_steps;           // decode steps enqueued since prefill/reset
   // options
-  int opt_splits, opt_graph, opt_profile, opt_split, opt_chunk, opt_fuse_norm, opt_ctx_split;
+  int opt_splits, opt_graph, opt_profile, opt_split, opt_chunk, opt_fuse_norm, opt_ctx_split, opt_ctx_attn;
   hipGraphExec_t graph_exec; bool graph_ready;
   std::vector<hipEvent_t> ev_pool; size_t ev_used;
   int32_t *h_pinned;        // small host staging buffer (pinned unless stage_pinned is false)

@@ -464,11 +464,13 @@ def test_cfg5_all_layers_short_context():
     dec.close()
 
 
-@pytest.mark.parametrize("chunk", [256, 160, 48])
-def test_context_pass_in_several_chunks(chunk):
+@pytest.mark.parametrize("chunk,ctx_attn", [(256, 1), (160, 1), (48, 1), (256, 2), (160, 2), (48, 2), (0, 2), (40, 2)])
+def test_context_pass_in_several_chunks(chunk, ctx_attn):
     """600 context tokens in chunks of 256 (two launches of the many-row kernels and a tail of 88
-    rows in the 128-row kernels), 160 (three and a tail of 120) and 48 rows: the caches the context
-    pass leaves behind must give the oracle's logits whatever the chunking."""
+    rows in the 128-row kernels), 160 (three and a tail of 120), 48 and 40 rows, and all at once: the
+    caches the context pass leaves behind must give the oracle's logits whatever the chunking, with the
+    decode step's attention kernel (what the library picks at this size) and with the 32-query kernel
+    of large context passes (PD_OPT_CONTEXT_ATTN 2; chunks with a ragged last query tile included)."""
     from paper_2506_23431_amd import binding
     cfg = CASES["mfma-flat"]
     w = pi.make_weights(cfg, threads=4)
@@ -476,6 +478,26 @@ def test_context_pass_in_several_chunks(chunk):
     outs = oracle_run(cfg, w, ctx)
     dec = make_decoder(cfg, w)
     dec.set_option(binding.PD_OPT_PREFILL_CHUNK, chunk)
+    dec.set_option(binding.PD_OPT_CONTEXT_ATTN, ctx_attn)
+    stats = compare_teacher_forced(cfg, w, ctx, dec, outs, log=say)
+    assert stats["rows"] == cfg.batch * (cfg.n_sub * (cfg.sub_tokens + 1) - 1)
+    dec.close()
+
+
+@pytest.mark.parametrize("name,split_act", [("mfma-hd128-llama", 1), ("mfma-flat", 0), ("mfma-hd64", 1),
+                                            ("mfma-hd64", 0), ("mfma-manyrows", 1), ("mfma-llama-packed", 1)])
+def test_context_attention_kernel_of_large_passes(name, split_act):
+    """PD_OPT_CONTEXT_ATTN 2: the 32-query attention kernel that large context passes pick by themselves,
+    here on small shapes: head sizes 128 and 64, several requests, contexts that are no multiple of the
+    32-key block or of the 32-query block, queries with and without low parts."""
+    from paper_2506_23431_amd import binding
+    cfg = CASES[name]
+    w = pi.make_weights(cfg, threads=4)
+    ctx = pi.make_context(cfg)
+    outs = oracle_run(cfg, w, ctx)
+    dec = make_decoder(cfg, w)
+    dec.set_option(binding.PD_OPT_CONTEXT_ATTN, 2)
+    dec.set_option(binding.PD_OPT_SPLIT_ACT, split_act)
     stats = compare_teacher_forced(cfg, w, ctx, dec, outs, log=say)
     assert stats["rows"] == cfg.batch * (cfg.n_sub * (cfg.sub_tokens + 1) - 1)
     dec.close()
