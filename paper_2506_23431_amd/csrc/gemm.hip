@@ -125,16 +125,9 @@ int mfma_fold_norms(pd_ctx *c, hipStream_t s) {
 // ---------------------------------------------------------------------------
 // norm -> bf16 activations.  One block per row; rows without a token become zero.
 // The row is read once into registers (gain and bias are requested at the same
-// time), so the kernel costs one memory round trip plus two block reductions.
+// time), so the kernel costs one memory round trip plus one block reduction (sum and sum of squares
+// together: the variance is E[x^2] - mean^2, as in the projections that finish a norm).
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ float block_sum256(float v, float *sh) {
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
-  __syncthreads();
-  return sh[0] + sh[1] + sh[2] + sh[3];
-}
-
 // EMB: the row is not read from x but gathered from the embedding tables (first norm of a step:
 // x = E_tok[token] (+ E_pos[position]), zero for rows without a token) and written to x.
 template <int NG, int NP, bool EMB>     // 8-value granules per thread: d <= 2048 * NG; NP pending slices
@@ -144,7 +137,6 @@ __global__ __launch_bounds__(256) void k_norm_bf16(bf16_t *xn, bf16_t *xn_lo, co
                                                    const float *ypart, size_t part_stride,
                                                    const bf16_t *tok_emb, const bf16_t *pos_emb,
                                                    const int32_t *tok, const int32_t *pos) {
-  __shared__ float sh[4];
   int r = blockIdx.x;
   int fl = r < R ? flags[r] : 0;
   const float *xr = x + (size_t)r * d;
@@ -194,23 +186,20 @@ __global__ __launch_bounds__(256) void k_norm_bf16(bf16_t *xn, bf16_t *xn_lo, co
     }
   }
   bool valid = fl & ROW_VALID;
-  float s = 0.f;
+  float s = 0.f, q = 0.f;
 #pragma unroll
   for (int i = 0; i < NG; ++i)
 #pragma unroll
-    for (int e = 0; e < 8; ++e) s += v[i][e];
-  float mean = kind == 0 ? block_sum256(s, sh) / d : 0.f;
-  float q = 0.f;
-#pragma unroll
-  for (int i = 0; i < NG; ++i) {
-    bool in = (threadIdx.x + i * 256) * 8 < d;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float t = in ? v[i][e] - mean : 0.f;
-      q += t * t;
-    }
-  }
-  float rstd = rsqrtf(block_sum256(q, sh) / d + eps);
+    for (int e = 0; e < 8; ++e) { s += v[i][e]; q += v[i][e] * v[i][e]; }
+  // one reduction for both sums (values beyond d are zero)
+  for (int o = 32; o > 0; o >>= 1) { s += __shfl_xor(s, o); q += __shfl_xor(q, o); }
+  __shared__ float2 sh2[4];
+  if ((threadIdx.x & 63) == 0) sh2[threadIdx.x >> 6] = make_float2(s, q);
+  __syncthreads();
+  s = (sh2[0].x + sh2[1].x) + (sh2[2].x + sh2[3].x);
+  q = (sh2[0].y + sh2[1].y) + (sh2[2].y + sh2[3].y);
+  float mean = kind == 0 ? s / d : 0.f;
+  float rstd = rsqrtf(fmaxf(q / d - mean * mean, 0.f) + eps);
 #pragma unroll
   for (int i = 0; i < NG; ++i) {
     int c = (threadIdx.x + i * 256) * 8;
