@@ -55,8 +55,8 @@ def test_whole_run_against_stored_oracle_results(workload):
     import torch
     cfg, w, ctx = workload
     gold = stored_runs(cfg.name)
-    if not gold:
-        pytest.skip(f"no stored oracle results for {cfg.name} (tests/golden/make_full_run.py writes them)")
+    assert sorted(gold) == list(range(cfg.batch)), \
+        f"stored oracle results of every request of {cfg.name} are part of the repository (tests/golden/make_full_run.py writes them)"
     B, S, T, tol = cfg.batch, cfg.n_sub, cfg.time_steps, TOL[cfg.dtype]
     rows_at = {}
     for b, g in gold.items():
