@@ -545,7 +545,8 @@ def test_options_do_not_change_results():
                          (binding.PD_OPT_PREFILL_CHUNK, 16), (binding.PD_OPT_PREFILL_CHUNK, 40),
                          (binding.PD_OPT_PREFILL_CHUNK, 128), (binding.PD_OPT_PREFILL_CHUNK, 144),
                          (binding.PD_OPT_PROFILE, 3),        # the attention kernel launched twice per layer
-                         (binding.PD_OPT_STREAM_LOADS, 1)):  # non-temporal loads of weights, keys and values
+                         (binding.PD_OPT_STREAM_LOADS, 1),   # non-temporal loads of weights, keys and values
+                         (binding.PD_OPT_CONTEXT_ATTN, 2)):  # the 32-query attention kernel in the context pass
             dec.set_option(key, val)
             for rep in range(3 if key == binding.PD_OPT_USE_GRAPH else 1):
                 got = dec.generate(*args)
