@@ -1050,10 +1050,13 @@ int PD_GEMM_ENTRY(const GemmArgs &a, int rows, hipStream_t s) { return launch_ge
 
 #else   // ---- common part: dispatcher ----------------------------------------------------------
 
-// 17-128 rows against a weight matrix of at most 16 MB and a K that 8 waves (times the K slices over blocks)
-// cover in batches of 4 k-tiles: the launch gives every row tile blocks of its own (launch_gemm_zrows)
+// 17-128 rows against a weight matrix of at most 16 MB (17-32 rows: 64 MB; the blocks of both row tiles are then
+// resident together and the second reader of a weight line finds it in L2) and a K that 8 waves (times the K
+// slices over blocks) cover in batches of 4 k-tiles: the launch gives every row tile blocks of its own
+// (launch_gemm_zrows)
 bool mfma_gemm_row_tile_blocks(int n_tiles, int K, int rows, int k_slices) {
-  return rows > 16 && rows <= 128 && (size_t)n_tiles * 16 * K * 2 <= ((size_t)16 << 20) && K / 32 <= 64 * k_slices;
+  const size_t bytes = (size_t)n_tiles * 16 * K * 2;
+  return rows > 16 && rows <= 128 && (bytes <= ((size_t)16 << 20) || (rows <= 32 && bytes <= ((size_t)64 << 20))) && K / 32 <= 64 * k_slices;
 }
 
 int mfma_gemm_row_tiles(int rows) {

@@ -401,6 +401,8 @@ WIDE = {
     # name: (config, iterations)
     "cfg3-wide": (pi.get_config("cfg3").scaled(name="cfg3-wide", n_layer=2, qkv_std=0.03), 40),
     "cfg4-wide": (pi.get_config("cfg4").scaled(name="cfg4-wide", n_layer=2, qkv_std=0.03), 72),
+    # dt=1: 17-32 rows per step from iteration 17 on (two row tiles against matrices of 25-34 MB)
+    "cfg4-wide-dt1": (pi.get_config("cfg4").scaled(name="cfg4-wide-dt1", n_layer=2, qkv_std=0.03, delta_t=1), 34),
     # dt=1 instead of 4: all 16 rows per request (64 rows in all) are reached within 16 iterations
     "cfg5-wide": (pi.get_config("cfg5").scaled(name="cfg5-wide", n_layer=2, qkv_std=0.03, delta_t=1), 12),
 }
